@@ -1,0 +1,240 @@
+// extern "C" entry points: argument checks, then the internal launchers.
+// Every check runs before the first launch, so a failing call has no side effect.
+#include "plan.h"
+
+using namespace gnn;
+
+namespace {
+
+hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
+
+bool bad_align(const void *p) { return (reinterpret_cast<uintptr_t>(p) % kAlign) != 0; }
+
+gnn_status_t check_graph(const gnn_plan_t *plan, const gnn_graph_t *g, bool need_val, bool need_transpose,
+                         bool need_perm) {
+    if (!g) return GNN_ERR_INVALID_ARG;
+    if (g->n != plan->desc.n || g->nnz != plan->desc.nnz) return GNN_ERR_BAD_GRAPH;
+    if (!g->csr_rowptr || (g->nnz > 0 && !g->csr_col)) return GNN_ERR_BAD_GRAPH;
+    if (need_val && g->nnz > 0 && !g->csr_val) return GNN_ERR_BAD_GRAPH;
+    if (need_transpose) {
+        if (!g->csc_colptr || (g->nnz > 0 && !g->csc_row)) return GNN_ERR_BAD_GRAPH;
+        if (g->nnz > 0 && need_perm && !g->csc_perm) return GNN_ERR_BAD_GRAPH;
+    }
+    return GNN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *gnn_status_string(gnn_status_t s) {
+    switch (s) {
+        case GNN_OK: return "ok";
+        case GNN_ERR_INVALID_ARG: return "invalid argument";
+        case GNN_ERR_BAD_GRAPH: return "graph does not match the plan or lacks required arrays";
+        case GNN_ERR_BUFFER_TOO_SMALL: return "buffer too small";
+        case GNN_ERR_STATE: return "backward needs a cache that no forward has filled";
+        case GNN_ERR_UNSUPPORTED: return "unsupported shape";
+        case GNN_ERR_HIP: return "HIP error";
+    }
+    return "unknown status";
+}
+
+gnn_status_t gnn_plan_create(const gnn_plan_desc_t *desc, gnn_plan_t **out) { return plan_create(desc, out); }
+
+gnn_status_t gnn_plan_query(const gnn_plan_t *plan, gnn_plan_info_t *out) {
+    if (!plan || !out) return GNN_ERR_INVALID_ARG;
+    *out = plan->info;
+    return GNN_OK;
+}
+
+void gnn_plan_destroy(gnn_plan_t *plan) { delete plan; }
+
+gnn_status_t gcn_layer_fwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W,
+                           const float *b, float *Y, void *cache, void *workspace, void *hip_stream) {
+    if (!plan || plan->desc.layer != GNN_LAYER_GCN) return GNN_ERR_INVALID_ARG;
+    GNN_TRY(check_graph(plan, graph, true, false, false));
+    if (!X || !W || !Y || !workspace) return GNN_ERR_INVALID_ARG;
+    if (plan->desc.has_bias && !b) return GNN_ERR_INVALID_ARG;
+    if (plan->info.cache == GNN_CACHE_AX && !cache) return GNN_ERR_INVALID_ARG;
+    if (bad_align(workspace) || (cache && bad_align(cache))) return GNN_ERR_INVALID_ARG;
+    if (plan->desc.n == 0) return GNN_OK;
+    return gcn_forward(*plan, *graph, X, W, b, Y, cache, workspace, as_stream(hip_stream));
+}
+
+gnn_status_t gcn_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W,
+                           const float *Y, const float *dY, float *dW, float *db, float *dX,
+                           void *cache, void *workspace, void *hip_stream) {
+    if (!plan || plan->desc.layer != GNN_LAYER_GCN) return GNN_ERR_INVALID_ARG;
+    const bool cached = plan->info.cache == GNN_CACHE_AX;
+    const bool needs_t = !graph || !graph->symmetric;
+    const bool runs_spmm_t = plan->info.bwd == GNN_BWD_FUSED_PROPAGATE || plan->desc.need_input_grad;
+    GNN_TRY(check_graph(plan, graph, true, needs_t && runs_spmm_t, graph && !graph->csc_val));
+    if (!W || !dY || !dW || !workspace) return GNN_ERR_INVALID_ARG;
+    if (!cached && !X) return GNN_ERR_INVALID_ARG;
+    if (plan->desc.fuse_relu && !Y) return GNN_ERR_INVALID_ARG;
+    if (plan->desc.has_bias && !db) return GNN_ERR_INVALID_ARG;
+    if (plan->desc.need_input_grad && !dX) return GNN_ERR_INVALID_ARG;
+    if (cached && !cache) return GNN_ERR_INVALID_ARG;
+    if (bad_align(workspace) || (cache && bad_align(cache))) return GNN_ERR_INVALID_ARG;
+    if (cached && !plan->cache_filled) return GNN_ERR_STATE;
+    if (plan->desc.n == 0) {
+        // an empty graph has zero gradients; dW / db still have to be written
+        hipStream_t st = as_stream(hip_stream);
+        if (hipMemsetAsync(dW, 0, sizeof(float) * plan->desc.f_in * plan->desc.f_out, st) != hipSuccess)
+            return GNN_ERR_HIP;
+        if (plan->desc.has_bias && hipMemsetAsync(db, 0, sizeof(float) * plan->desc.f_out, st) != hipSuccess)
+            return GNN_ERR_HIP;
+        return GNN_OK;
+    }
+    return gcn_backward(*plan, *graph, X, W, Y, dY, dW, db, dX, cache, workspace, as_stream(hip_stream));
+}
+
+gnn_status_t gat_layer_fwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W,
+                           const float *a_src, const float *a_dst, const float *b, float *Y,
+                           void *cache, void *workspace, void *hip_stream) {
+    if (!plan || plan->desc.layer != GNN_LAYER_GAT) return GNN_ERR_INVALID_ARG;
+    GNN_TRY(check_graph(plan, graph, false, false, false));
+    if (!X || !W || !a_src || !a_dst || !Y || !workspace) return GNN_ERR_INVALID_ARG;
+    if (plan->desc.has_bias && !b) return GNN_ERR_INVALID_ARG;
+    if (plan->info.cache != GNN_CACHE_NONE && !cache) return GNN_ERR_INVALID_ARG;
+    if (bad_align(workspace) || (cache && bad_align(cache))) return GNN_ERR_INVALID_ARG;
+    if (plan->desc.n == 0) return GNN_OK;
+    return gat_forward(*plan, *graph, X, W, a_src, a_dst, b, Y, cache, workspace, as_stream(hip_stream));
+}
+
+gnn_status_t gat_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W,
+                           const float *a_src, const float *a_dst, const float *dY,
+                           float *dW, float *da_src, float *da_dst, float *db, float *dX,
+                           void *cache, void *workspace, void *hip_stream) {
+    if (!plan || plan->desc.layer != GNN_LAYER_GAT) return GNN_ERR_INVALID_ARG;
+    GNN_TRY(check_graph(plan, graph, false, true, true));
+    if (!X || !W || !a_src || !a_dst || !dY || !dW || !da_src || !da_dst || !workspace) return GNN_ERR_INVALID_ARG;
+    if (plan->desc.has_bias && !db) return GNN_ERR_INVALID_ARG;
+    if (plan->desc.need_input_grad && !dX) return GNN_ERR_INVALID_ARG;
+    if (plan->info.cache != GNN_CACHE_NONE && !cache) return GNN_ERR_INVALID_ARG;
+    if (bad_align(workspace) || (cache && bad_align(cache))) return GNN_ERR_INVALID_ARG;
+    if (plan->info.cache != GNN_CACHE_NONE && !plan->cache_filled) return GNN_ERR_STATE;
+    if (plan->desc.n == 0) {
+        hipStream_t st = as_stream(hip_stream);
+        const size_t f = (size_t)plan->desc.heads * plan->desc.f_out;
+        if (hipMemsetAsync(dW, 0, sizeof(float) * plan->desc.f_in * f, st) != hipSuccess) return GNN_ERR_HIP;
+        if (hipMemsetAsync(da_src, 0, sizeof(float) * f, st) != hipSuccess) return GNN_ERR_HIP;
+        if (hipMemsetAsync(da_dst, 0, sizeof(float) * f, st) != hipSuccess) return GNN_ERR_HIP;
+        if (plan->desc.has_bias && hipMemsetAsync(db, 0, sizeof(float) * f, st) != hipSuccess) return GNN_ERR_HIP;
+        return GNN_OK;
+    }
+    return gat_backward(*plan, *graph, X, W, a_src, a_dst, dY, dW, da_src, da_dst, db, dX, cache, workspace,
+                        as_stream(hip_stream));
+}
+
+// ---- preprocessing ---------------------------------------------------------------
+
+size_t gnn_scan_workspace_bytes(int32_t n) { return scan_workspace_bytes(n > 0 ? n : 0); }
+
+gnn_status_t gnn_add_self_loops_degree(int32_t n, int32_t nnz, const int32_t *rowptr, const int32_t *col,
+                                       int32_t *rowptr_out, int32_t *col_out, int32_t *deg_out,
+                                       int32_t *nnz_out_host, void *workspace, size_t workspace_bytes,
+                                       void *hip_stream) {
+    if (n < 0 || nnz < 0 || !rowptr || !rowptr_out || !col_out || !nnz_out_host || !workspace) return GNN_ERR_INVALID_ARG;
+    if ((nnz > 0 && !col) || (n > 0 && !deg_out)) return GNN_ERR_INVALID_ARG;
+    if ((int64_t)nnz + n > INT32_MAX) return GNN_ERR_UNSUPPORTED;
+    if (workspace_bytes < scan_workspace_bytes(n)) return GNN_ERR_BUFFER_TOO_SMALL;
+    hipStream_t st = as_stream(hip_stream);
+    GNN_TRY(add_self_loops_launch(n, nnz, rowptr, col, rowptr_out, col_out, deg_out, workspace, st));
+    if (hipMemcpyAsync(nnz_out_host, rowptr_out + n, sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return GNN_ERR_HIP;
+    return hipStreamSynchronize(st) == hipSuccess ? GNN_OK : GNN_ERR_HIP;
+}
+
+gnn_status_t gnn_gcn_normalize(int32_t n, const int32_t *rowptr, const int32_t *col, const int32_t *deg,
+                               float *val_out, void *hip_stream) {
+    if (n < 0 || !rowptr) return GNN_ERR_INVALID_ARG;
+    if (n > 0 && (!deg || !col || !val_out)) return GNN_ERR_INVALID_ARG;
+    return normalize_launch(n, rowptr, col, deg, val_out, as_stream(hip_stream));
+}
+
+size_t gnn_transpose_workspace_bytes(int32_t n, int32_t nnz) {
+    return transpose_workspace_bytes(n > 0 ? n : 0, nnz > 0 ? nnz : 0);
+}
+
+gnn_status_t gnn_csr_transpose(int32_t n, int32_t nnz, const int32_t *rowptr, const int32_t *col,
+                               int32_t *colptr_out, int32_t *row_out, int32_t *perm_out,
+                               void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (n < 0 || nnz < 0 || !rowptr || !colptr_out || !workspace) return GNN_ERR_INVALID_ARG;
+    if (nnz > 0 && (!col || !row_out || !perm_out)) return GNN_ERR_INVALID_ARG;
+    if (workspace_bytes < transpose_workspace_bytes(n, nnz)) return GNN_ERR_BUFFER_TOO_SMALL;
+    if (bad_align(workspace)) return GNN_ERR_INVALID_ARG;
+    return transpose_launch(n, nnz, rowptr, col, colptr_out, row_out, perm_out, workspace, as_stream(hip_stream));
+}
+
+gnn_status_t gnn_expand_ptr(int32_t n, int32_t nnz, const int32_t *ptr, int32_t *out, void *hip_stream) {
+    if (n < 0 || nnz < 0 || !ptr || (nnz > 0 && !out)) return GNN_ERR_INVALID_ARG;
+    return expand_ptr_launch(n, nnz, ptr, out, as_stream(hip_stream));
+}
+
+gnn_status_t gnn_gather_f32(int64_t count, const float *in, const int32_t *perm, float *out, void *hip_stream) {
+    if (count < 0 || (count > 0 && (!in || !perm || !out))) return GNN_ERR_INVALID_ARG;
+    return gather_f32_launch(count, in, perm, out, as_stream(hip_stream));
+}
+
+// ---- operators ----------------------------------------------------------------------
+
+size_t gnn_spmm_workspace_bytes(int32_t n, int32_t nnz, int32_t f) {
+    (void)n;
+    return spmm_workspace_bytes(nnz > 0 ? nnz : 0, f > 0 ? f : 1);
+}
+
+gnn_status_t gnn_spmm_csr(int32_t n, int32_t nnz, const int32_t *rowptr, const int32_t *col, const float *val,
+                          const int32_t *erow, const float *B, int32_t f, float *C,
+                          const float *bias, int32_t relu,
+                          void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (n < 0 || nnz < 0 || f <= 0 || !rowptr) return GNN_ERR_INVALID_ARG;
+    if (n > 0 && !C) return GNN_ERR_INVALID_ARG;
+    if (nnz > 0 && (!col || !B)) return GNN_ERR_INVALID_ARG;
+    if (erow && nnz > 0) {
+        if (!workspace || bad_align(workspace)) return GNN_ERR_INVALID_ARG;
+        if (workspace_bytes < spmm_workspace_bytes(nnz, f)) return GNN_ERR_BUFFER_TOO_SMALL;
+    }
+    return spmm_launch(n, nnz, rowptr, col, erow, EdgeWeights{val, nullptr, 1, f}, B, f, C, bias, relu, workspace,
+                       as_stream(hip_stream));
+}
+
+gnn_status_t gnn_sddmm_csr(int32_t n, int32_t nnz, const int32_t *rowptr, const int32_t *col, const float *val,
+                           const float *B, const float *Ct, int32_t heads, int32_t f, float *D,
+                           void *hip_stream) {
+    if (n < 0 || nnz < 0 || f <= 0 || heads <= 0 || !rowptr) return GNN_ERR_INVALID_ARG;
+    if (nnz > 0 && (!col || !B || !Ct || !D)) return GNN_ERR_INVALID_ARG;
+    return sddmm_launch(n, nnz, rowptr, col, val, B, Ct, heads, f, D, as_stream(hip_stream));
+}
+
+size_t gnn_gemm_workspace_bytes(int32_t trans_a, int32_t trans_b, int64_t M, int64_t N, int64_t K) {
+    if (M <= 0 || N <= 0 || K <= 0) return kAlign;
+    return gemm_workspace_bytes(trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K);
+}
+
+gnn_status_t gnn_gemm(int32_t trans_a, int32_t trans_b, int64_t M, int64_t N, int64_t K,
+                      const float *A, const float *B, float *C, const float *bias, int32_t relu,
+                      void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (M < 0 || N < 0 || K < 0) return GNN_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return GNN_OK;
+    if (!C || (K > 0 && (!A || !B))) return GNN_ERR_INVALID_ARG;
+    if (trans_a && trans_b) return GNN_ERR_UNSUPPORTED;
+    const size_t need = gnn_gemm_workspace_bytes(trans_a, trans_b, M, N, K);
+    if (need > kAlign) {
+        if (!workspace || bad_align(workspace)) return GNN_ERR_INVALID_ARG;
+        if (workspace_bytes < need) return GNN_ERR_BUFFER_TOO_SMALL;
+    }
+    return gemm_launch(trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K, A, B, C, bias, relu, workspace,
+                       as_stream(hip_stream));
+}
+
+gnn_status_t gnn_softmax_xent(int32_t n, int32_t c, const float *Z, const int32_t *labels, float *dZ,
+                              float *loss_out, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (n < 0 || c <= 0 || !loss_out) return GNN_ERR_INVALID_ARG;
+    if (n > 0 && (!Z || !labels || !dZ || !workspace)) return GNN_ERR_INVALID_ARG;
+    if (workspace_bytes < sizeof(float) * (size_t)ceil_div(n > 0 ? n : 1, 256)) return GNN_ERR_BUFFER_TOO_SMALL;
+    return softmax_xent_launch(n, c, Z, labels, dZ, loss_out, workspace, as_stream(hip_stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,105 @@
+// Internal helpers shared by the host and device translation units of the library.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "gnn.h"
+
+namespace gnn {
+
+constexpr int kWave = 64;            // CDNA wavefront width
+constexpr size_t kAlign = 256;       // alignment of every carved workspace / cache block
+
+static inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Carves consecutive aligned blocks out of one caller buffer.
+struct Carver {
+    char *base;
+    size_t off = 0;
+    explicit Carver(void *p) : base(static_cast<char *>(p)) {}
+    template <typename T> T *take(size_t count) {
+        T *r = reinterpret_cast<T *>(base + off);
+        off += align_up(count * sizeof(T));
+        return r;
+    }
+};
+
+static inline gnn_status_t launch_status() {
+    return hipGetLastError() == hipSuccess ? GNN_OK : GNN_ERR_HIP;
+}
+
+#define GNN_TRY(expr)                                  \
+    do {                                               \
+        gnn_status_t _s = (expr);                      \
+        if (_s != GNN_OK) return _s;                   \
+    } while (0)
+
+// ---- sparse operators (spmm.hip) -------------------------------------------------
+// How the weight of a stored entry is fetched.
+struct EdgeWeights {
+    const float *val;       // NULL: every weight is 1
+    const int32_t *perm;    // NULL: slot e reads val[e...]; else val[perm[e]...]
+    int32_t heads;          // 1: one weight per entry; >1: val is [nnz][heads], feature c uses head c / head_dim
+    int32_t head_dim;
+};
+
+int spmm_segment_len(int64_t nnz, int f);
+size_t spmm_workspace_bytes(int64_t nnz, int f);
+gnn_status_t spmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *col, const int32_t *erow,
+                         EdgeWeights w, const float *B, int f, float *C, const float *bias, int relu,
+                         void *workspace, hipStream_t st);
+
+// ---- dense products (gemm.hip) ----------------------------------------------------
+size_t gemm_workspace_bytes(int ta, int tb, int64_t M, int64_t N, int64_t K);
+gnn_status_t gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A, const float *B,
+                         float *C, const float *bias, int relu, void *workspace, hipStream_t st);
+
+// ---- element-wise and reductions (elementwise.hip) ---------------------------------
+// out = G * [Y > 0]
+gnn_status_t relu_mask_launch(int64_t count, const float *G, const float *Y, float *out, hipStream_t st);
+// out[c] = sum_i G[i][c], deterministic two-stage; workspace colsum_workspace_bytes(n, f)
+size_t colsum_workspace_bytes(int64_t n, int f);
+gnn_status_t colsum_launch(int64_t n, int f, const float *G, float *out, void *workspace, hipStream_t st);
+gnn_status_t softmax_xent_launch(int n, int c, const float *Z, const int32_t *labels, float *dZ, float *loss,
+                                 void *workspace, hipStream_t st);
+
+// ---- preprocessing (prep.hip) -------------------------------------------------------
+size_t scan_workspace_bytes(int64_t n);
+size_t transpose_workspace_bytes(int n, int nnz);
+gnn_status_t add_self_loops_launch(int n, int nnz, const int32_t *rowptr, const int32_t *col, int32_t *rowptr_out,
+                                   int32_t *col_out, int32_t *deg_out, void *workspace, hipStream_t st);
+gnn_status_t normalize_launch(int n, const int32_t *rowptr, const int32_t *col, const int32_t *deg, float *val,
+                              hipStream_t st);
+gnn_status_t transpose_launch(int n, int nnz, const int32_t *rowptr, const int32_t *col, int32_t *colptr,
+                              int32_t *row, int32_t *perm, void *workspace, hipStream_t st);
+gnn_status_t expand_ptr_launch(int n, int nnz, const int32_t *ptr, int32_t *out, hipStream_t st);
+gnn_status_t gather_f32_launch(int64_t count, const float *in, const int32_t *perm, float *out, hipStream_t st);
+
+// ---- GAT kernels (gat.hip) -----------------------------------------------------------
+gnn_status_t gat_node_attention_launch(int n, int h, int k, const float *M, const float *a_src, const float *a_dst,
+                                       float *s, float *d, hipStream_t st);
+// alpha [nnz][h] (= softmax over each row of LeakyReLU(s_i + d_j)); mask [nnz][h] or NULL
+gnn_status_t gat_edge_softmax_launch(int n, int nnz, int h, const int32_t *rowptr, const int32_t *col,
+                                     const float *s, const float *d, float slope, float *alpha, uint8_t *mask,
+                                     hipStream_t st);
+// gy [nnz][h], ds [n][h]; mask NULL: the sign is recomputed from s, d
+gnn_status_t gat_edge_backward_launch(int n, int nnz, int h, int k, const int32_t *rowptr, const int32_t *col,
+                                      const float *G, const float *M, const float *alpha, const uint8_t *mask,
+                                      const float *s, const float *d, float slope, float *gy, float *ds,
+                                      hipStream_t st);
+// dd[j][p] = sum over column j of gy (through perm);  dM_j = ds_j a_src + dd_j a_dst + agg_j (agg already in dM)
+gnn_status_t gat_column_sums_launch(int n, int h, const int32_t *colptr, const int32_t *perm, const float *gy,
+                                    float *dd, hipStream_t st);
+gnn_status_t gat_add_rank1_launch(int n, int h, int k, const float *ds, const float *dd, const float *a_src,
+                                  const float *a_dst, float *dM, hipStream_t st);
+// da[p][c] = sum_i w[i][p] M[i][p][c]; workspace colsum_workspace_bytes(n, h*k)
+gnn_status_t gat_attention_grad_launch(int n, int h, int k, const float *w, const float *M, float *da,
+                                       void *workspace, hipStream_t st);
+gnn_status_t sddmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *col, const float *val,
+                          const float *B, const float *Ct, int heads, int f, float *D, hipStream_t st);
+
+}  // namespace gnn

@@ -1,0 +1,156 @@
+// Element-wise kernels and tall column reductions (bias gradient, ReLU mask,
+// attention-vector gradient, softmax cross-entropy).  All reductions are
+// two-stage with a fixed summation order, so results are reproducible.
+#include "common.h"
+
+namespace gnn {
+namespace {
+
+__global__ void __launch_bounds__(256)
+relu_mask_kernel(long count4, long count, const float *__restrict__ G, const float *__restrict__ Y,
+                 float *__restrict__ out, int vec) {
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (vec) {
+        if (i >= count4) return;
+        const float4 g = reinterpret_cast<const float4 *>(G)[i];
+        const float4 y = reinterpret_cast<const float4 *>(Y)[i];
+        reinterpret_cast<float4 *>(out)[i] =
+            make_float4(y.x > 0.f ? g.x : 0.f, y.y > 0.f ? g.y : 0.f, y.z > 0.f ? g.z : 0.f, y.w > 0.f ? g.w : 0.f);
+    } else {
+        if (i >= count) return;
+        out[i] = Y[i] > 0.f ? G[i] : 0.f;
+    }
+}
+
+// Stage 1 of out[c] = sum_i wgt(i, c) * G[i][c].  The 256 threads of a block form
+// (256 / fp) row lanes x fp columns (fp = power of two >= min(f, 256)); each block owns
+// `rows_per_block` consecutive rows and writes one partial row of f sums.
+__global__ void __launch_bounds__(256)
+colsum_partial_kernel(long n, int f, int fp, long rows_per_block, const float *__restrict__ G,
+                      const float *__restrict__ wgt, int heads, int head_dim, float *__restrict__ part) {
+    __shared__ float red[256];
+    const int c0 = threadIdx.x % fp, rl = threadIdx.x / fp, lanes = 256 / fp;
+    const long r0 = (long)blockIdx.x * rows_per_block;
+    const long r1 = min(n, r0 + rows_per_block);
+    for (int cb = 0; cb < f; cb += fp) {
+        const int c = cb + c0;
+        float a = 0.f;
+        if (c < f) {
+            const int hd = wgt ? c / head_dim : 0;
+            for (long i = r0 + rl; i < r1; i += lanes) {
+                const float g = G[(size_t)i * f + c];
+                a += wgt ? g * wgt[(size_t)i * heads + hd] : g;
+            }
+        }
+        red[threadIdx.x] = a;
+        __syncthreads();
+        if (rl == 0 && c < f) {
+            float s = 0.f;
+            for (int k = 0; k < lanes; ++k) s += red[k * fp + c0];
+            part[(size_t)blockIdx.x * f + c] = s;
+        }
+        __syncthreads();
+    }
+}
+
+__global__ void __launch_bounds__(256)
+colsum_final_kernel(int f, int blocks, const float *__restrict__ part, float *__restrict__ out) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= f) return;
+    float s = 0.f;
+    for (int b = 0; b < blocks; ++b) s += part[(size_t)b * f + c];
+    out[c] = s;
+}
+
+// One thread per node: stable softmax, loss term, dZ = softmax - onehot.
+__global__ void __launch_bounds__(256)
+softmax_xent_kernel(int n, int c, const float *__restrict__ Z, const int32_t *__restrict__ labels,
+                    float *__restrict__ dZ, float *__restrict__ block_loss) {
+    __shared__ float red[256];
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    float loss = 0.f;
+    if (i < n) {
+        const float *z = Z + (size_t)i * c;
+        float mx = z[0];
+        for (int t = 1; t < c; ++t) mx = fmaxf(mx, z[t]);
+        float sum = 0.f;
+        for (int t = 0; t < c; ++t) sum += expf(z[t] - mx);
+        const int lab = labels[i];
+        loss = logf(sum) + mx - z[lab];
+        const float inv = 1.f / sum;
+        for (int t = 0; t < c; ++t) dZ[(size_t)i * c + t] = expf(z[t] - mx) * inv - (t == lab ? 1.f : 0.f);
+    }
+    red[threadIdx.x] = loss;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float s = 0.f;
+        for (int k = 0; k < 256; ++k) s += red[k];
+        block_loss[blockIdx.x] = s;
+    }
+}
+
+__global__ void sum_serial_kernel(int count, const float *__restrict__ in, float *__restrict__ out) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        double s = 0.0;
+        for (int i = 0; i < count; ++i) s += (double)in[i];
+        out[0] = (float)s;
+    }
+}
+
+long colsum_rows_per_block(long n) {
+    long r = ceil_div(n, 1024);
+    return r < 64 ? 64 : r;
+}
+
+}  // namespace
+
+gnn_status_t relu_mask_launch(int64_t count, const float *G, const float *Y, float *out, hipStream_t st) {
+    if (count <= 0) return GNN_OK;
+    const int vec = count % 4 == 0 && aligned16(G) && aligned16(Y) && aligned16(out);
+    const long threads = vec ? count / 4 : count;
+    hipLaunchKernelGGL(relu_mask_kernel, dim3((unsigned)ceil_div(threads, 256)), dim3(256), 0, st, (long)(count / 4),
+                       (long)count, G, Y, out, vec);
+    return launch_status();
+}
+
+size_t colsum_workspace_bytes(int64_t n, int f) {
+    const long blocks = ceil_div(n > 0 ? n : 1, colsum_rows_per_block(n));
+    return align_up((size_t)blocks * f * sizeof(float));
+}
+
+static gnn_status_t colsum_weighted(int64_t n, int f, const float *G, const float *wgt, int heads, int head_dim,
+                                    float *out, void *workspace, hipStream_t st) {
+    if (f <= 0) return GNN_OK;
+    const long rpb = colsum_rows_per_block(n);
+    const int blocks = (int)ceil_div(n > 0 ? n : 1, rpb);
+    int fp = 1;
+    while (fp < f && fp < 256) fp <<= 1;
+    float *part = static_cast<float *>(workspace);
+    hipLaunchKernelGGL(colsum_partial_kernel, dim3(blocks), dim3(256), 0, st, (long)n, f, fp, rpb, G, wgt, heads,
+                       head_dim, part);
+    GNN_TRY(launch_status());
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)ceil_div(f, 256)), dim3(256), 0, st, f, blocks, part, out);
+    return launch_status();
+}
+
+gnn_status_t colsum_launch(int64_t n, int f, const float *G, float *out, void *workspace, hipStream_t st) {
+    return colsum_weighted(n, f, G, nullptr, 1, f, out, workspace, st);
+}
+
+gnn_status_t gat_attention_grad_launch(int n, int h, int k, const float *w, const float *M, float *da,
+                                       void *workspace, hipStream_t st) {
+    return colsum_weighted(n, h * k, M, w, h, k, da, workspace, st);
+}
+
+gnn_status_t softmax_xent_launch(int n, int c, const float *Z, const int32_t *labels, float *dZ, float *loss,
+                                 void *workspace, hipStream_t st) {
+    if (n <= 0) return GNN_OK;
+    const int blocks = (int)ceil_div(n, 256);
+    float *part = static_cast<float *>(workspace);
+    hipLaunchKernelGGL(softmax_xent_kernel, dim3(blocks), dim3(256), 0, st, n, c, Z, labels, dZ, part);
+    GNN_TRY(launch_status());
+    hipLaunchKernelGGL(sum_serial_kernel, dim3(1), dim3(64), 0, st, blocks, part, loss);
+    return launch_status();
+}
+
+}  // namespace gnn

@@ -1,0 +1,169 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what the header declares,
+chooses schemes by the paper's tables and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+from paper_2308_12093_amd import binding as B  # noqa: E402
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "gnn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b((?:gnn|gcn|gat)_[a-z0-9_]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    declared = header_functions()
+    assert len(declared) >= 20
+    for name in declared:
+        assert hasattr(B.lib, name), name
+        assert name in B.EXPORTS, name
+    assert sorted(B.EXPORTS) == declared
+
+
+def test_status_strings():
+    assert B.gnn_status_string(0) == "ok"
+    for s in range(1, 7):
+        assert B.gnn_status_string(s) not in ("ok", "unknown status")
+
+
+def plan(m, k, dx, cache=B.GNN_CACHE_AUTO, order=B.GNN_ORDER_AUTO, bwd=B.GNN_BWD_AUTO, n=1000, nnz=9000, **kw):
+    return B.Plan(B.GNN_LAYER_GCN, n, nnz, m, k, need_input_grad=dx, cache=cache, order=order, bwd=bwd, **kw)
+
+
+TF, PF = B.GNN_ORDER_TRANSFORM_FIRST, B.GNN_ORDER_PROPAGATE_FIRST
+FP, SP = B.GNN_BWD_FUSED_PROPAGATE, B.GNN_BWD_SPLIT_PROPAGATE
+
+
+@pytest.mark.parametrize("m", [1, 7, 64, 128, 500])
+def test_gcn_rule_without_caching(m):
+    """Table "GCN schemes": forward TF iff k < m; backward FP iff k < 2m (with dX) / k < m (without)."""
+    for k in sorted({1, m // 2, m - 1, m, m + 1, 2 * m - 1, 2 * m, 2 * m + 1, 5 * m} - {0}):
+        for dx in (True, False):
+            info = plan(m, k, dx, cache=B.GNN_CACHE_NONE).info
+            assert info.order == (TF if k < m else PF), (m, k, dx)
+            assert info.bwd == (FP if k < (2 * m if dx else m) else SP), (m, k, dx)
+            assert info.cache == B.GNN_CACHE_NONE and info.cache_bytes == 0
+
+
+@pytest.mark.parametrize("m", [2, 7, 64, 128, 500])
+def test_gcn_rule_with_caching(m):
+    """Table "GCN schemes with caching": TF+FP iff k < m (with dX) / k < m/2 (without); else PF+SP with cache."""
+    for k in sorted({1, (m - 1) // 2, m // 2, m // 2 + 1, m - 1, m, m + 1, 3 * m} - {0}):
+        for dx in (True, False):
+            info = plan(m, k, dx).info
+            small = (k < m) if dx else (2 * k < m)
+            assert info.order == (TF if small else PF), (m, k, dx)
+            assert info.bwd == (FP if small else SP), (m, k, dx)
+            assert info.cache == (B.GNN_CACHE_NONE if small else B.GNN_CACHE_AX), (m, k, dx)
+
+
+def test_observed_thresholds_at_128_input_features():
+    """App. F: with 128 input features the schemes switch at 128 / 256 (no caching, without / with dX)
+    and at 64 / 128 (caching, without / with dX)."""
+    def first_switch(dx, cache):
+        for k in (8, 16, 32, 64, 128, 256, 512, 1024):
+            if plan(128, k, dx, cache=cache).info.bwd == SP:
+                return k
+    assert first_switch(False, B.GNN_CACHE_NONE) == 128
+    assert first_switch(True, B.GNN_CACHE_NONE) == 256
+    assert first_switch(False, B.GNN_CACHE_AUTO) == 64
+    assert first_switch(True, B.GNN_CACHE_AUTO) == 128
+
+
+def test_transients_and_spmm_widths_follow_the_tables():
+    n, m = 1000, 128
+    # TF + FP: nk; nk, two SpMMs of width k
+    i = plan(m, 16, True).info
+    assert (i.transient_fwd, i.transient_bwd, i.spmm_width_fwd, i.spmm_width_bwd) == (n * 16, n * 16, 16, 16)
+    # PF + SP with cache, with dX: nm; nm, SpMMs of width m in each pass
+    i = plan(m, 512, True).info
+    assert (i.transient_fwd, i.transient_bwd, i.spmm_width_fwd, i.spmm_width_bwd) == (n * m, n * m, m, m)
+    assert i.cache_bytes >= 4 * n * m and i.cache_bytes < 4 * n * m + 256
+    # ... without dX: nm; 0 and no SpMM in backward
+    i = plan(m, 512, False).info
+    assert (i.transient_fwd, i.transient_bwd, i.spmm_width_bwd) == (n * m, 0, 0)
+    # split-propagate without cache: two SpMMs of width m, 2nm transients
+    i = plan(m, 512, True, cache=B.GNN_CACHE_NONE).info
+    assert (i.bwd, i.transient_bwd, i.spmm_width_bwd) == (SP, 2 * n * m, 2 * m)
+
+
+def test_forced_schemes_and_invalid_combinations():
+    i = plan(128, 16, True, order=PF, bwd=SP).info
+    assert (i.order, i.bwd, i.cache) == (PF, SP, B.GNN_CACHE_AX)
+    i = plan(128, 16, True, order=PF, bwd=SP, cache=B.GNN_CACHE_NONE).info
+    assert (i.order, i.bwd, i.cache) == (PF, SP, B.GNN_CACHE_NONE)
+    i = plan(128, 512, True, order=TF, bwd=FP).info
+    assert (i.order, i.bwd, i.cache) == (TF, FP, B.GNN_CACHE_NONE)
+    with pytest.raises(B.GnnError) as e:
+        plan(128, 512, True, order=TF, cache=B.GNN_CACHE_AX)      # A'X does not exist in transform-first
+    assert e.value.status == B.GNN_ERR_INVALID_ARG
+    for bad in (dict(m=0, k=4), dict(m=4, k=0), dict(m=4, k=4, n=-1)):
+        with pytest.raises(B.GnnError):
+            plan(bad.pop("m"), bad.pop("k"), True, **bad)
+    with pytest.raises(B.GnnError):
+        plan(4, 4, True, cache=B.GNN_CACHE_GAT_FEAT)
+
+
+def test_gat_cache_sizes():
+    """Table "GAT caching": 4nhk, 4nh(k+2), 4nhk + 5qh bytes (plus alignment padding per block)."""
+    n, q, h, k = 1000, 9000, 8, 8
+    want = {B.GNN_CACHE_NONE: 0, B.GNN_CACHE_GAT_FEAT: 4 * n * h * k,
+            B.GNN_CACHE_GAT_FEAT_NODEATT: 4 * n * h * (k + 2), B.GNN_CACHE_GAT_FEAT_EDGE: 4 * n * h * k + 5 * q * h}
+    for variant, size in want.items():
+        info = B.Plan(B.GNN_LAYER_GAT, n, q, 256, k, heads=h, cache=variant).info
+        assert size <= info.cache_bytes <= size + 3 * 256, (variant, info.cache_bytes, size)
+        assert info.cache == variant
+    assert B.Plan(B.GNN_LAYER_GAT, n, q, 256, k, heads=h).info.cache == B.GNN_CACHE_GAT_FEAT_EDGE
+
+
+def test_layer_calls_reject_bad_arguments_before_any_launch():
+    p = plan(8, 4, True, n=10, nnz=30)
+    g = B.gnn_graph_t(10, 30, 256, 256, 256, None, None, None, None, None, None, 1)
+    null = ctypes.c_void_p(None)
+    one = ctypes.c_void_p(256)
+    # NULL X
+    assert B.lib.gcn_layer_fwd(p.handle, ctypes.byref(g), null, one, null, one, null, one, null) == B.GNN_ERR_INVALID_ARG
+    # misaligned workspace
+    assert B.lib.gcn_layer_fwd(p.handle, ctypes.byref(g), one, one, null, one, null, ctypes.c_void_p(260), null) == B.GNN_ERR_INVALID_ARG
+    # graph that does not match the plan
+    g2 = B.gnn_graph_t(11, 30, 256, 256, 256, None, None, None, None, None, None, 1)
+    assert B.lib.gcn_layer_fwd(p.handle, ctypes.byref(g2), one, one, null, one, null, one, null) == B.GNN_ERR_BAD_GRAPH
+    # GCN needs edge values
+    g3 = B.gnn_graph_t(10, 30, 256, 256, None, None, None, None, None, None, None, 1)
+    assert B.lib.gcn_layer_fwd(p.handle, ctypes.byref(g3), one, one, null, one, null, one, null) == B.GNN_ERR_BAD_GRAPH
+    # backward on a directed graph without CSC arrays
+    g4 = B.gnn_graph_t(10, 30, 256, 256, 256, None, None, None, None, None, None, 0)
+    assert B.lib.gcn_layer_bwd(p.handle, ctypes.byref(g4), one, one, null, one, one, null, one, null, one, null) == B.GNN_ERR_BAD_GRAPH
+    # missing dX although the plan needs it
+    assert B.lib.gcn_layer_bwd(p.handle, ctypes.byref(g), one, one, null, one, one, null, null, null, one, null) == B.GNN_ERR_INVALID_ARG
+    # a GAT call on a GCN plan
+    assert B.lib.gat_layer_fwd(p.handle, ctypes.byref(g), one, one, one, one, null, one, null, one, null) == B.GNN_ERR_INVALID_ARG
+
+
+def test_backward_before_forward_with_cached_plan_is_a_state_error():
+    p = plan(8, 16, True, n=10, nnz=30)
+    assert p.info.cache == B.GNN_CACHE_AX
+    g = B.gnn_graph_t(10, 30, 256, 256, 256, None, None, None, None, None, None, 1)
+    null, one = ctypes.c_void_p(None), ctypes.c_void_p(256)
+    st = B.lib.gcn_layer_bwd(p.handle, ctypes.byref(g), null, one, null, one, one, null, one, one, one, null)
+    assert st == B.GNN_ERR_STATE
+
+
+def test_operator_calls_check_sizes():
+    null, one = ctypes.c_void_p(None), ctypes.c_void_p(256)
+    need = B.gnn_spmm_workspace_bytes(100, 1000, 64)
+    assert need >= 2 * (1000 // 256) * 64 * 4
+    st = B.lib.gnn_spmm_csr(100, 1000, one, one, one, one, one, 64, one, null, 0, one, need - 1, null)
+    assert st == B.GNN_ERR_BUFFER_TOO_SMALL
+    assert B.lib.gnn_spmm_csr(100, 1000, one, one, one, one, one, 0, one, null, 0, one, need, null) == B.GNN_ERR_INVALID_ARG
+    assert B.lib.gnn_gemm(1, 1, 4, 4, 4, one, one, one, null, 0, null, 0, null) == B.GNN_ERR_UNSUPPORTED
+    assert B.lib.gnn_gemm(0, 0, -1, 4, 4, one, one, one, null, 0, null, 0, null) == B.GNN_ERR_INVALID_ARG
+    tw = B.gnn_transpose_workspace_bytes(100, 1000)
+    assert B.lib.gnn_csr_transpose(100, 1000, one, one, one, one, one, one, tw - 1, null) == B.GNN_ERR_BUFFER_TOO_SMALL

@@ -1,0 +1,142 @@
+"""Parity of gcn_layer_fwd / gcn_layer_bwd with the fp64 oracle for every scheme, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2308_12093_amd import synth
+from tests._util import assert_close, dev, host, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2308_12093_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def G():
+    from paper_2308_12093_amd import graphs
+    return graphs
+
+
+def schemes(B):
+    return {
+        "auto": dict(),
+        "tf_fp": dict(order=B.GNN_ORDER_TRANSFORM_FIRST, bwd=B.GNN_BWD_FUSED_PROPAGATE, cache=B.GNN_CACHE_NONE),
+        "pf_sp_nocache": dict(order=B.GNN_ORDER_PROPAGATE_FIRST, bwd=B.GNN_BWD_SPLIT_PROPAGATE, cache=B.GNN_CACHE_NONE),
+        "pf_sp_cache": dict(order=B.GNN_ORDER_PROPAGATE_FIRST, bwd=B.GNN_BWD_SPLIT_PROPAGATE, cache=B.GNN_CACHE_AX),
+        "pf_fp": dict(order=B.GNN_ORDER_PROPAGATE_FIRST, bwd=B.GNN_BWD_FUSED_PROPAGATE, cache=B.GNN_CACHE_NONE),
+        "tf_sp": dict(order=B.GNN_ORDER_TRANSFORM_FIRST, bwd=B.GNN_BWD_SPLIT_PROPAGATE, cache=B.GNN_CACHE_NONE),
+    }
+
+
+def run_layer(B, g, X, W, b, dY, need_dx, relu, scheme, Y_for_mask=None):
+    """One forward + backward through the C ABI.  Returns host arrays."""
+    n, m = X.shape
+    k = W.shape[1]
+    plan = B.Plan(B.GNN_LAYER_GCN, g.n, g.nnz, m, k, need_input_grad=need_dx, has_bias=b is not None,
+                  fuse_relu=relu, **scheme)
+    ws = B.alloc(plan.info.workspace_bytes)
+    cache = B.alloc(plan.info.cache_bytes) if plan.info.cache_bytes else None
+    dX_, dW_, db_ = dev(X), dev(W), None if b is None else dev(b)
+    Y = torch.full((n, k), float("nan"), dtype=torch.float32, device="cuda")
+    B.gcn_layer_fwd(plan, g, dX_, dW_, db_, Y, cache, ws)
+    torch.cuda.synchronize()
+    ws.fill_(0xFF)                                             # backward must not rely on forward's scratch
+    gW = torch.full((m, k), float("nan"), dtype=torch.float32, device="cuda")
+    gb = None if b is None else torch.full((k,), float("nan"), dtype=torch.float32, device="cuda")
+    gX = torch.full((n, m), float("nan"), dtype=torch.float32, device="cuda") if need_dx else None
+    Ymask = None
+    if relu:
+        Ymask = Y if Y_for_mask is None else dev(Y_for_mask)
+    x_arg = None if plan.info.cache == B.GNN_CACHE_AX else dX_    # with A'X cached the input is not needed
+    B.gcn_layer_bwd(plan, g, x_arg, dW_, Ymask, dev(dY), gW, gb, gX, cache, ws)
+    torch.cuda.synchronize()
+    return host(Y), host(gW), None if gb is None else host(gb), None if gX is None else host(gX), plan.info
+
+
+def oracle_layer(rp, c, val, X, W, b, dY, need_dx, relu, Y_for_mask=None):
+    Y = oracle.gcn_forward(rp, c, val, X, W, b, relu)
+    mask_src = None
+    if relu:
+        mask_src = Y_for_mask if Y_for_mask is not None else Y.astype(np.float32)
+    dW, db, dX = oracle.gcn_backward(rp, c, val, X, W, dY, mask_src, need_dx)
+    return Y, dW, db, dX
+
+
+def check(B, G, rowptr, col, X, W, b, dY, need_dx, relu, scheme, symmetric=True, label=""):
+    g = G.gcn_graph(rowptr, col, symmetric=symmetric)
+    rp, c, deg = oracle.add_self_loops_degree(rowptr, col)
+    val = oracle.gcn_normalize(rp, c, deg)
+    # both sides take the ReLU sign decisions from the same float32 array: the oracle's forward output
+    Ymask = oracle.gcn_forward(rp, c, val, X, W, b, True).astype(np.float32) if relu else None
+    Y, gW, gb, gX, info = run_layer(B, g, X, W, b, dY, need_dx, relu, scheme, Ymask)
+    rY, rW, rb, rX = oracle_layer(rp, c, val, X, W, b, dY, need_dx, relu, Ymask)
+    assert_close(Y, rY, f"{label} Y")
+    assert_close(gW, rW, f"{label} dW")
+    if b is not None:
+        assert_close(gb, rb, f"{label} db")
+    if need_dx:
+        assert_close(gX, rX, f"{label} dX")
+    assert rel_fro(gW, rW) < 1e-5
+    return info
+
+
+@pytest.mark.parametrize("name", ["auto", "tf_fp", "pf_sp_nocache", "pf_sp_cache", "pf_fp", "tf_sp"])
+@pytest.mark.parametrize("m,k", [(48, 16), (16, 48), (32, 32), (100, 47)])
+def test_every_scheme_small_rmat(B, G, name, m, k):
+    s = synth.streams(11)
+    rowptr, col = synth.rmat_graph(11, 12, False, s["graph"], s["relabel"])
+    n = rowptr.size - 1
+    X, W = synth.normal(s["X"], n, m), synth.glorot_uniform(s["W"], (m, k), m, k)
+    b, dY = synth.normal(s["b"], k), synth.normal(s["dY"], n, k)
+    for need_dx in (True, False):
+        for relu in (False, True):
+            check(B, G, rowptr, col, X, W, b if relu else None, dY, need_dx, relu, schemes(B)[name],
+                  label=f"{name} m={m} k={k} dx={need_dx} relu={relu}")
+
+
+@pytest.mark.parametrize("name", ["tf_fp", "pf_sp_nocache", "pf_sp_cache"])
+def test_directed_graph_uses_the_transpose(B, G, name):
+    s = synth.streams(12)
+    rowptr, col = synth.rmat_graph(11, 10, True, s["graph"], s["relabel"])
+    n = rowptr.size - 1
+    X, W = synth.normal(s["X"], n, 24), synth.glorot_uniform(s["W"], (24, 40), 24, 40)
+    check(B, G, rowptr, col, X, W, synth.normal(s["b"], 40), synth.normal(s["dY"], n, 40), True, False,
+          schemes(B)[name], symmetric=False, label=f"directed {name}")
+
+
+def test_config1_both_orderings(B, G):
+    w = synth.config1()
+    X, W, dY, b = w.tensors["X"], w.tensors["W16"], w.tensors["dY16"], None
+    assert w.n == 2048 and w.col.size == 16384 and X.shape == (2048, 512) and W.shape == (512, 16)
+    info = check(B, G, w.rowptr, w.col, X, W, b, dY, True, False, schemes(B)["auto"], label="cfg1 auto")
+    assert info.order == B.GNN_ORDER_TRANSFORM_FIRST and info.bwd == B.GNN_BWD_FUSED_PROPAGATE
+    for name in ("pf_sp_cache", "pf_sp_nocache"):
+        for need_dx in (True, False):
+            check(B, G, w.rowptr, w.col, X, W, b, dY, need_dx, False, schemes(B)[name], label=f"cfg1 {name}")
+
+
+@pytest.mark.parametrize("k", [16, 128, 512])
+def test_config2_full_size(B, G, k):
+    """The benchmark workload itself, every element compared."""
+    w = synth.config2(f_outs=(k,))
+    X, W, dY = w.tensors["X"], w.tensors[f"W{k}"], w.tensors[f"dY{k}"]
+    for name in ("auto", "tf_fp"):
+        check(B, G, w.rowptr, w.col, X, W, None, dY, True, False, schemes(B)[name], label=f"cfg2 k={k} {name}")
+
+
+def test_cached_backward_needs_a_forward_first(B, G):
+    s = synth.streams(13)
+    rowptr, col = synth.rmat_graph(8, 6, False, s["graph"], s["relabel"])
+    g = G.gcn_graph(rowptr, col)
+    plan = B.Plan(B.GNN_LAYER_GCN, g.n, g.nnz, 8, 16)
+    assert plan.info.cache == B.GNN_CACHE_AX
+    ws, cache = B.alloc(plan.info.workspace_bytes), B.alloc(plan.info.cache_bytes)
+    t = lambda *shape: torch.zeros(shape, dtype=torch.float32, device="cuda")
+    with pytest.raises(B.GnnError) as e:
+        B.gcn_layer_bwd(plan, g, None, t(8, 16), None, t(g.n, 16), t(8, 16), None, t(g.n, 8), cache, ws)
+    assert e.value.status == B.GNN_ERR_STATE

@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the GCN layer hot path on one MI355X.
+
+A step = forward + backward of one GCN layer for every F_out of the workload
+(default: the R-MAT 2^17 graph with F_in = 128 and F_out in {16, 128, 512}),
+each with the plan that gnn_plan_create picks (adaptive ordering + caching,
+input gradient required).  Inputs are seeded and synthetic, resident in HBM
+before the timed region, and all graph preprocessing (self-loops, degrees,
+normalisation, row-index expansion) has run in the library's kernels.
+
+Prints ONE JSON line:
+  value      edge.features per second, sum_k q (F_in + F_out_k) / time per step
+  roofline   the entry-balanced SpMM kernel: algorithmic (compulsory) HBM bytes
+             per launch / its average duration, timed with HIP events recorded
+             around that kernel alone on the launch stream
+  cpu_baseline  the fp64 oracle, one step of the same workload, host cores
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg5"])
+    ap.add_argument("--scale", type=int, default=None, help="override the R-MAT scale (debug)")
+    ap.add_argument("--scheme", default="auto", choices=["auto", "tf_fp", "pf_sp_nocache", "pf_sp_cache"])
+    ap.add_argument("--no-input-grad", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="also print per-F_out / per-scheme timings to stderr")
+    return ap.parse_args()
+
+
+class HipEvents:
+    """Raw HIP events (the torch ones hide their handles until recorded)."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        e = ctypes.c_void_p()
+        assert self.hip.hipEventCreate(ctypes.byref(e)) == 0
+        return e
+
+    def elapsed_ms(self, a, b):
+        assert self.hip.hipEventSynchronize(b) == 0
+        ms = ctypes.c_float()
+        assert self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
+        return ms.value
+
+
+def spmm_bytes(n, q, f):
+    """Algorithmic HBM bytes of one SpMM launch of width f: every operand once.
+
+    Row index, column index and value per entry (12 q), the dense operand read
+    once (4 n f) and the result written once (4 n f).  Re-reads of dense rows
+    that miss the caches are not counted: they are what a better kernel avoids."""
+    return 12 * q + 8 * n * f
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU; there is no multi-GPU path (--gpus must be 1)")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    from paper_2308_12093_amd import binding as B, graphs, synth
+
+    if args.workload == "cfg1":
+        w = synth.config1()
+    elif args.workload == "cfg2":
+        w = synth.config2(scale=args.scale or 17)
+    else:
+        w = synth.config5(scale=args.scale or 22)
+    f_in, f_outs = w.dims["f_in"], w.dims["f_outs"]
+    need_dx = not args.no_input_grad
+
+    dev = "cuda"
+    g = graphs.gcn_graph(w.rowptr, w.col, dev, symmetric=True)
+    n, q = g.n, g.nnz
+    X = torch.from_numpy(w.tensors["X"]).to(dev)
+
+    scheme_kw = {
+        "auto": {},
+        "tf_fp": dict(order=B.GNN_ORDER_TRANSFORM_FIRST, bwd=B.GNN_BWD_FUSED_PROPAGATE, cache=B.GNN_CACHE_NONE),
+        "pf_sp_nocache": dict(order=B.GNN_ORDER_PROPAGATE_FIRST, bwd=B.GNN_BWD_SPLIT_PROPAGATE, cache=B.GNN_CACHE_NONE),
+        "pf_sp_cache": dict(order=B.GNN_ORDER_PROPAGATE_FIRST, bwd=B.GNN_BWD_SPLIT_PROPAGATE, cache=B.GNN_CACHE_AX),
+    }
+
+    def make_layer(k, scheme, dx):
+        plan = B.Plan(B.GNN_LAYER_GCN, n, q, f_in, k, need_input_grad=dx, **scheme_kw[scheme])
+        L = dict(k=k, plan=plan,
+                 W=torch.from_numpy(w.tensors[f"W{k}"]).to(dev), dY=torch.from_numpy(w.tensors[f"dY{k}"]).to(dev),
+                 Y=torch.empty((n, k), dtype=torch.float32, device=dev),
+                 dW=torch.empty((f_in, k), dtype=torch.float32, device=dev),
+                 dX=torch.empty((n, f_in), dtype=torch.float32, device=dev) if dx else None,
+                 ws=B.alloc(plan.info.workspace_bytes),
+                 cache=B.alloc(plan.info.cache_bytes) if plan.info.cache_bytes else None)
+        return L
+
+    def fwd(L):
+        B.gcn_layer_fwd(L["plan"], g, X, L["W"], None, L["Y"], L["cache"], L["ws"])
+
+    def bwd(L):
+        B.gcn_layer_bwd(L["plan"], g, X, L["W"], None, L["dY"], L["dW"], None, L["dX"], L["cache"], L["ws"])
+
+    layers = [make_layer(k, args.scheme, need_dx) for k in f_outs]
+
+    def step():
+        for L in layers:
+            fwd(L)
+            bwd(L)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    edge_feat = sum(q * (f_in + k) for k in f_outs)
+    value = edge_feat / (ms_per_step * 1e-3)
+
+    # ---- per-kernel timing of the dominant kernel: the entry-balanced SpMM ----
+    ev = HipEvents()
+    e0, e1 = ev.create(), ev.create()
+    B.gnn_profile_spmm_events(e0, e1)
+    launch_widths = []                       # dense width of every SpMM launch of one step
+    for L in layers:
+        info = L["plan"].info
+        launch_widths.append(int(info.spmm_width_fwd))
+        if info.bwd == B.GNN_BWD_FUSED_PROPAGATE:
+            launch_widths.append(L["k"])
+        else:
+            launch_widths += [f_in] * int(info.spmm_width_bwd // f_in)
+    widths = sorted(set(launch_widths))
+    per_width = {}
+    tot_bytes = tot_ms = 0.0
+    launches = 0
+    for f in widths:
+        Bm = torch.randn((n, f), dtype=torch.float32, device=dev)
+        C = torch.empty((n, f), dtype=torch.float32, device=dev)
+        ws = B.alloc(B.gnn_spmm_workspace_bytes(n, q, f))
+        times = []
+        for it in range(5 + max(10, args.steps)):
+            B.gnn_spmm_csr(n, q, g.rowptr, g.col, g.val, g.erow, Bm, f, C, None, False, ws)
+            ms = ev.elapsed_ms(e0, e1)
+            if it >= 5:
+                times.append(ms)
+        avg = float(np.mean(times))
+        per_width[f] = dict(avg_ms=avg, min_ms=float(np.min(times)), bytes=spmm_bytes(n, q, f),
+                            gbps=spmm_bytes(n, q, f) / avg / 1e6,
+                            gather_gbps=(12 * q + 4 * q * f + 4 * n * f) / avg / 1e6,
+                            edge_feat_per_s=q * f / (avg * 1e-3))
+        cnt = launch_widths.count(f)
+        tot_bytes += cnt * spmm_bytes(n, q, f)
+        tot_ms += cnt * avg
+        launches += cnt
+    B.gnn_profile_spmm_events(None, None)
+    achieved = tot_bytes / tot_ms / 1e6          # GB/s over all SpMM launches of one step
+    roofline = {"bound": "hbm", "kernel": "spmm_seg_kernel", "achieved": round(achieved, 1), "peak": 8000.0,
+                "unit": "GB/s", "frac": round(achieved / 8000.0, 4), "traffic": None,
+                "launches_per_step": launches,
+                "bytes_per_launch": {str(f): per_width[f]["bytes"] for f in widths},
+                "avg_ms_per_launch": {str(f): round(per_width[f]["avg_ms"], 5) for f in widths},
+                "no_reuse_gather_GBps": {str(f): round(per_width[f]["gather_gbps"], 1) for f in widths},
+                "spmm_time_share_of_step": round(tot_ms / ms_per_step, 3)}
+
+    # ---- CPU baseline: the fp64 oracle, one step of the same workload ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        rp, c, deg = oracle.add_self_loops_degree(w.rowptr, w.col)
+        val = oracle.gcn_normalize(rp, c, deg)
+        t0 = time.perf_counter()
+        for k in f_outs:
+            oracle.gcn_forward(rp, c, val, w.tensors["X"], w.tensors[f"W{k}"])
+            oracle.gcn_backward(rp, c, val, w.tensors["X"], w.tensors[f"W{k}"], w.tensors[f"dY{k}"], None, need_dx)
+        dt = time.perf_counter() - t0
+        cpu = {"value": edge_feat / dt, "unit": "edge*feat/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"one full step (fwd+bwd for F_out in {list(f_outs)}) of the same workload, {dt:.1f} s",
+               "ms_per_step": dt * 1e3}
+
+    if args.breakdown:
+        for L in layers:
+            for name, fn in (("fwd", fwd), ("bwd", bwd)):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(20):
+                    fn(L)
+                torch.cuda.synchronize()
+                info = L["plan"].info
+                print(f"k={L['k']:4d} {name} {(time.perf_counter() - t0) * 50:.4f} ms  "
+                      f"order={info.order} bwd={info.bwd} cache={info.cache}", file=sys.stderr)
+        for f in widths:
+            print(f"spmm f={f}: {per_width[f]}", file=sys.stderr)
+
+    out = {
+        "metric": "GCN layer fwd+bwd edge-feat/s (adaptive ordering + caching)", "value": value,
+        "unit": "edge*feat/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: R-MAT/ER graph n={n}, nnz={q} (self-loops incl.), F_in={f_in}, "
+                               f"F_out={list(f_outs)}, GCN single layer fwd+bwd, scheme={args.scheme}, "
+                               f"input_grad={need_dx}",
+                   "schemes": {str(L["k"]): {"order": int(L["plan"].info.order), "bwd": int(L["plan"].info.bwd),
+                                             "cache": int(L["plan"].info.cache)} for L in layers}},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -250,6 +250,15 @@ gnn_status_t gnn_spmm_csr(int32_t n, int32_t nnz, const int32_t *rowptr, const i
 size_t gnn_spmm_workspace_bytes(int32_t n, int32_t nnz, int32_t f);
 
 /*
+ * gnn_profile_spmm_events - profiling aid (App. E.1 kernel timing).  While both arguments are
+ * non-NULL hipEvent_t handles, every later launch of the entry-balanced SpMM kernel (from
+ * gnn_spmm_csr or from a layer) records `start_event` right before and `stop_event` right
+ * after that one kernel on the launch stream, so a caller can time the kernel alone.
+ * Pass NULL, NULL to switch it off.  Process-wide, not thread-safe; the events stay the caller's.
+ */
+void gnn_profile_spmm_events(void *start_event, void *stop_event);
+
+/*
  * gnn_sddmm_csr - D_e = val_e * <B_i, Ct_j> for every stored entry e = (i, j) (App. E.2),
  *   batched over `heads` with the head as the middle axis: B, Ct [n][heads][f], D [nnz][heads].
  *   val NULL = all ones.

@@ -79,6 +79,7 @@ _PROTOS = {
     "gnn_gather_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
     "gnn_spmm_csr": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _sz, _vp]),
     "gnn_spmm_workspace_bytes": (_sz, [_i32, _i32, _i32]),
+    "gnn_profile_spmm_events": (None, [_vp, _vp]),
     "gnn_sddmm_csr": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp]),
     "gnn_gemm": (ctypes.c_int, [_i32, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]),
     "gnn_gemm_workspace_bytes": (_sz, [_i32, _i32, _i64, _i64, _i64]),
@@ -240,6 +241,10 @@ def gnn_spmm_workspace_bytes(n, nnz, f):
 def gnn_spmm_csr(n, nnz, rowptr, col, val, erow, B, f, C, bias=None, relu=False, workspace=None):
     _check(lib.gnn_spmm_csr(n, nnz, _ptr(rowptr), _ptr(col), _ptr(val), _ptr(erow), _ptr(B), f, _ptr(C),
                             _ptr(bias), int(relu), _ptr(workspace), _nbytes(workspace), _stream()), "gnn_spmm_csr")
+
+
+def gnn_profile_spmm_events(start_event, stop_event):
+    lib.gnn_profile_spmm_events(start_event, stop_event)
 
 
 def gnn_sddmm_csr(n, nnz, rowptr, col, val, B, Ct, heads, f, D):

@@ -208,6 +208,10 @@ gnn_status_t gnn_sddmm_csr(int32_t n, int32_t nnz, const int32_t *rowptr, const 
     return sddmm_launch(n, nnz, rowptr, col, val, B, Ct, heads, f, D, as_stream(hip_stream));
 }
 
+void gnn_profile_spmm_events(void *start_event, void *stop_event) {
+    spmm_profile_events(static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event));
+}
+
 size_t gnn_gemm_workspace_bytes(int32_t trans_a, int32_t trans_b, int64_t M, int64_t N, int64_t K) {
     if (M <= 0 || N <= 0 || K <= 0) return kAlign;
     return gemm_workspace_bytes(trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K);

@@ -1,6 +1,8 @@
 // Element-wise kernels and tall column reductions (bias gradient, ReLU mask,
 // attention-vector gradient, softmax cross-entropy).  All reductions are
-// two-stage with a fixed summation order, so results are reproducible.
+// two-stage with a fixed summation order, so results are reproducible; they sum
+// over every node, so they accumulate in double (a float sum of millions of
+// terms of either sign is not accurate enough when the total is near zero).
 #include "common.h"
 
 namespace gnn {
@@ -27,25 +29,25 @@ relu_mask_kernel(long count4, long count, const float *__restrict__ G, const flo
 // `rows_per_block` consecutive rows and writes one partial row of f sums.
 __global__ void __launch_bounds__(256)
 colsum_partial_kernel(long n, int f, int fp, long rows_per_block, const float *__restrict__ G,
-                      const float *__restrict__ wgt, int heads, int head_dim, float *__restrict__ part) {
-    __shared__ float red[256];
+                      const float *__restrict__ wgt, int heads, int head_dim, double *__restrict__ part) {
+    __shared__ double red[256];
     const int c0 = threadIdx.x % fp, rl = threadIdx.x / fp, lanes = 256 / fp;
     const long r0 = (long)blockIdx.x * rows_per_block;
     const long r1 = min(n, r0 + rows_per_block);
     for (int cb = 0; cb < f; cb += fp) {
         const int c = cb + c0;
-        float a = 0.f;
+        double a = 0.0;
         if (c < f) {
             const int hd = wgt ? c / head_dim : 0;
             for (long i = r0 + rl; i < r1; i += lanes) {
-                const float g = G[(size_t)i * f + c];
-                a += wgt ? g * wgt[(size_t)i * heads + hd] : g;
+                const double g = G[(size_t)i * f + c];
+                a += wgt ? g * (double)wgt[(size_t)i * heads + hd] : g;
             }
         }
         red[threadIdx.x] = a;
         __syncthreads();
         if (rl == 0 && c < f) {
-            float s = 0.f;
+            double s = 0.0;
             for (int k = 0; k < lanes; ++k) s += red[k * fp + c0];
             part[(size_t)blockIdx.x * f + c] = s;
         }
@@ -54,12 +56,12 @@ colsum_partial_kernel(long n, int f, int fp, long rows_per_block, const float *_
 }
 
 __global__ void __launch_bounds__(256)
-colsum_final_kernel(int f, int blocks, const float *__restrict__ part, float *__restrict__ out) {
+colsum_final_kernel(int f, int blocks, const double *__restrict__ part, float *__restrict__ out) {
     const int c = blockIdx.x * 256 + threadIdx.x;
     if (c >= f) return;
-    float s = 0.f;
+    double s = 0.0;
     for (int b = 0; b < blocks; ++b) s += part[(size_t)b * f + c];
-    out[c] = s;
+    out[c] = (float)s;
 }
 
 // One thread per node: stable softmax, loss term, dZ = softmax - onehot.
@@ -115,7 +117,7 @@ gnn_status_t relu_mask_launch(int64_t count, const float *G, const float *Y, flo
 
 size_t colsum_workspace_bytes(int64_t n, int f) {
     const long blocks = ceil_div(n > 0 ? n : 1, colsum_rows_per_block(n));
-    return align_up((size_t)blocks * f * sizeof(float));
+    return align_up((size_t)blocks * f * sizeof(double));
 }
 
 static gnn_status_t colsum_weighted(int64_t n, int f, const float *G, const float *wgt, int heads, int head_dim,
@@ -125,7 +127,7 @@ static gnn_status_t colsum_weighted(int64_t n, int f, const float *G, const floa
     const int blocks = (int)ceil_div(n > 0 ? n : 1, rpb);
     int fp = 1;
     while (fp < f && fp < 256) fp <<= 1;
-    float *part = static_cast<float *>(workspace);
+    double *part = static_cast<double *>(workspace);
     hipLaunchKernelGGL(colsum_partial_kernel, dim3(blocks), dim3(256), 0, st, (long)n, f, fp, rpb, G, wgt, heads,
                        head_dim, part);
     GNN_TRY(launch_status());

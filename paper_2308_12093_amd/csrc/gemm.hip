@@ -1,54 +1,72 @@
-// fp32 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x2_f32) for the tall-skinny
-// products of the GCN / GAT layers:  X Theta,  G Theta^T  (rows = nodes, a few hundred
-// columns at most) and  X^T H  (a small output reduced over all nodes).
+// Dense products of the GCN / GAT layers on the gfx950 matrix cores:
+//   X Theta,  G Theta^T   rows = nodes, a few hundred columns at most   (fp32 MFMA)
+//   X^T H                 a small output reduced over all nodes          (fp64 MFMA)
 //
 // One block = 256 threads = 4 wavefronts arranged WM x WN; each wavefront owns
-// TM x TN tiles of 32 x 32 outputs (16 accumulator registers per tile and lane).
-// Both operands are staged through LDS k-major ([BK][rows + pad]) so that the
-// operand reads of the matrix instruction are consecutive words; the loaders
-// transpose on the way in when the source is stored the other way round.  The
-// next k-tile is fetched into registers while the current one is multiplied.
+// TM x TN output tiles of one matrix instruction (32 x 32 for
+// v_mfma_f32_32x32x2_f32, 16 x 16 for v_mfma_f64_16x16x4_f64).  Both operands are
+// staged through LDS k-major ([BK][rows + pad]) so that the operand reads of the
+// matrix instruction are consecutive words; the loaders transpose on the way in
+// when the source is stored the other way round.  The next k-tile is fetched into
+// registers while the current one is multiplied.
 //
-// The transposed-A form splits the long reduction into `splits` chunks
-// (blockIdx.y), writes one partial product per chunk and adds the partials in
-// chunk order in a second kernel, so the result does not depend on scheduling.
+// The transposed-A form  X^T H  sums over every node (up to millions of terms of
+// either sign).  A float accumulator loses ~1e-7 * sqrt(#terms) * |term| there, which
+// is above the accuracy asked of gradients whose value happens to be near zero, so
+// that product runs on the fp64 matrix instruction: operands are widened from float
+// when they leave LDS (their products are then exact) and accumulated in double.
+// The reduction is split into chunks; each chunk writes one double partial and a
+// second kernel adds the partials in chunk order, so the result does not depend on
+// scheduling.
 //
 // Block ids are remapped so that the eight XCDs (ids are dealt round-robin to
-// them) each work on a contiguous range of tiles: column tiles of one row
-// block, which re-read the same rows of A, share an L2.
+// them) each work on a contiguous range of (chunk, tile) pairs: the tiles that
+// re-read the same rows of an operand share an L2 and run close in time.
+#include <type_traits>
+
 #include "common.h"
 
 namespace gnn {
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef double doublex4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 32;
 
-template <bool TA, bool TB, int WM, int WN, int TM, int TN>
+// F64 = false:  C[M][N] (float)  = A[M][K] * (TB ? B[N][K]^T : B[K][N]) + bias, ReLU
+// F64 = true :  P[chunk][M][N] (double) = A[K][M]^T * B[K][N] over one chunk of K
+template <bool F64, bool TB, int WM, int WN, int TM, int TN>
 __global__ void __launch_bounds__(256)
-gemm_kernel(int M, int N, long K, const float *__restrict__ A, const float *__restrict__ B, float *__restrict__ C,
-            const float *__restrict__ bias, int relu, long k_chunk, int tiles_m, int tiles_n, int vec_a, int vec_b) {
-    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+gemm_kernel(int M, int N, long K, const float *__restrict__ A, const float *__restrict__ B, void *__restrict__ Cv,
+            const float *__restrict__ bias, int relu, long k_chunk, int tiles_m, int tiles_n, int splits, int vec_a,
+            int vec_b) {
+    constexpr bool TA = F64;
+    constexpr int UNIT = F64 ? 16 : 32;                 // edge of one matrix-instruction tile
+    constexpr int KSTEP = F64 ? 4 : 2;                  // reduction depth of one instruction
+    constexpr int BM = WM * TM * UNIT, BN = WN * TN * UNIT;
     constexpr int PA = TA ? 4 : 1, PB = TB ? 1 : 4;
-    constexpr int GA = BM * BK / 4 / 256, GB = BN * BK / 4 / 256;   // float4 granules per thread
+    constexpr int NA = BM * BK / 4, NB = BN * BK / 4;   // float4 granules per tile
+    constexpr int GA = (NA + 255) / 256, GB = (NB + 255) / 256;
     __shared__ float As[BK][BM + PA];
     __shared__ float Bs[BK][BN + PB];
 
-    const long total = (long)tiles_m * tiles_n;
+    const long tiles = (long)tiles_m * tiles_n;
+    const long total = tiles * splits;
     const long per_xcd = (total + 7) / 8;
     const long logical = (long)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     if (logical >= total) return;
-    const int m0 = (int)(logical / tiles_n) * BM;
-    const int n0 = (int)(logical % tiles_n) * BN;
-    const long kbeg = (long)blockIdx.y * k_chunk;
+    const int split = (int)(logical / tiles);
+    const int tile = (int)(logical % tiles);
+    const int m0 = (tile / tiles_n) * BM;
+    const int n0 = (tile % tiles_n) * BN;
+    const long kbeg = (long)split * k_chunk;
     const long kend = min(K, kbeg + k_chunk);
-    float *Cout = C + (size_t)blockIdx.y * (size_t)M * N;
 
     const int t = threadIdx.x;
     const int wave = t / 64, lane = t % 64;
     const int wm = wave / WN, wn = wave % WN;
-    const int l32 = lane % 32, half = lane / 32;
+    const int lu = lane % UNIT, lk = lane / UNIT;       // position inside the instruction's operand
 
     float4 ra[GA], rb[GB];
 
@@ -57,30 +75,32 @@ gemm_kernel(int M, int N, long K, const float *__restrict__ A, const float *__re
         for (int p = 0; p < GA; ++p) {
             const int j = t + 256 * p;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if constexpr (!TA) {                           // A[M][K], granule runs along k
-                const int row = j / (BK / 4), kq = (j % (BK / 4)) * 4;
-                const long gi = m0 + row, gk = k0 + kq;
-                if (gi < M) {
-                    const float *src = A + gi * K + gk;
-                    if (vec_a && gk + 3 < kend) v = *reinterpret_cast<const float4 *>(src);
-                    else {
-                        if (gk < kend) v.x = src[0];
-                        if (gk + 1 < kend) v.y = src[1];
-                        if (gk + 2 < kend) v.z = src[2];
-                        if (gk + 3 < kend) v.w = src[3];
+            if (NA % 256 == 0 || j < NA) {
+                if constexpr (!TA) {                       // A[M][K], granule runs along k
+                    const int row = j / (BK / 4), kq = (j % (BK / 4)) * 4;
+                    const long gi = m0 + row, gk = k0 + kq;
+                    if (gi < M) {
+                        const float *src = A + gi * K + gk;
+                        if (vec_a && gk + 3 < kend) v = *reinterpret_cast<const float4 *>(src);
+                        else {
+                            if (gk < kend) v.x = src[0];
+                            if (gk + 1 < kend) v.y = src[1];
+                            if (gk + 2 < kend) v.z = src[2];
+                            if (gk + 3 < kend) v.w = src[3];
+                        }
                     }
-                }
-            } else {                                       // A[K][M], granule runs along the output row index
-                const int kk = j / (BM / 4), iq = (j % (BM / 4)) * 4;
-                const long gk = k0 + kk, gi = m0 + iq;
-                if (gk < kend) {
-                    const float *src = A + gk * M + gi;
-                    if (vec_a && gi + 3 < M) v = *reinterpret_cast<const float4 *>(src);
-                    else {
-                        if (gi < M) v.x = src[0];
-                        if (gi + 1 < M) v.y = src[1];
-                        if (gi + 2 < M) v.z = src[2];
-                        if (gi + 3 < M) v.w = src[3];
+                } else {                                   // A[K][M], granule runs along the output row index
+                    const int kk = j / (BM / 4), iq = (j % (BM / 4)) * 4;
+                    const long gk = k0 + kk, gi = m0 + iq;
+                    if (gk < kend) {
+                        const float *src = A + gk * M + gi;
+                        if (vec_a && gi + 3 < M) v = *reinterpret_cast<const float4 *>(src);
+                        else {
+                            if (gi < M) v.x = src[0];
+                            if (gi + 1 < M) v.y = src[1];
+                            if (gi + 2 < M) v.z = src[2];
+                            if (gi + 3 < M) v.w = src[3];
+                        }
                     }
                 }
             }
@@ -90,30 +110,32 @@ gemm_kernel(int M, int N, long K, const float *__restrict__ A, const float *__re
         for (int p = 0; p < GB; ++p) {
             const int j = t + 256 * p;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if constexpr (!TB) {                           // B[K][N], granule runs along the output column index
-                const int kk = j / (BN / 4), jq = (j % (BN / 4)) * 4;
-                const long gk = k0 + kk, gj = n0 + jq;
-                if (gk < kend) {
-                    const float *src = B + gk * N + gj;
-                    if (vec_b && gj + 3 < N) v = *reinterpret_cast<const float4 *>(src);
-                    else {
-                        if (gj < N) v.x = src[0];
-                        if (gj + 1 < N) v.y = src[1];
-                        if (gj + 2 < N) v.z = src[2];
-                        if (gj + 3 < N) v.w = src[3];
+            if (NB % 256 == 0 || j < NB) {
+                if constexpr (!TB) {                       // B[K][N], granule runs along the output column index
+                    const int kk = j / (BN / 4), jq = (j % (BN / 4)) * 4;
+                    const long gk = k0 + kk, gj = n0 + jq;
+                    if (gk < kend) {
+                        const float *src = B + gk * N + gj;
+                        if (vec_b && gj + 3 < N) v = *reinterpret_cast<const float4 *>(src);
+                        else {
+                            if (gj < N) v.x = src[0];
+                            if (gj + 1 < N) v.y = src[1];
+                            if (gj + 2 < N) v.z = src[2];
+                            if (gj + 3 < N) v.w = src[3];
+                        }
                     }
-                }
-            } else {                                       // B[N][K], granule runs along k
-                const int cj = j / (BK / 4), kq = (j % (BK / 4)) * 4;
-                const long gj = n0 + cj, gk = k0 + kq;
-                if (gj < N) {
-                    const float *src = B + gj * K + gk;
-                    if (vec_b && gk + 3 < kend) v = *reinterpret_cast<const float4 *>(src);
-                    else {
-                        if (gk < kend) v.x = src[0];
-                        if (gk + 1 < kend) v.y = src[1];
-                        if (gk + 2 < kend) v.z = src[2];
-                        if (gk + 3 < kend) v.w = src[3];
+                } else {                                   // B[N][K], granule runs along k
+                    const int cj = j / (BK / 4), kq = (j % (BK / 4)) * 4;
+                    const long gj = n0 + cj, gk = k0 + kq;
+                    if (gj < N) {
+                        const float *src = B + gj * K + gk;
+                        if (vec_b && gk + 3 < kend) v = *reinterpret_cast<const float4 *>(src);
+                        else {
+                            if (gk < kend) v.x = src[0];
+                            if (gk + 1 < kend) v.y = src[1];
+                            if (gk + 2 < kend) v.z = src[2];
+                            if (gk + 3 < kend) v.w = src[3];
+                        }
                     }
                 }
             }
@@ -125,6 +147,7 @@ gemm_kernel(int M, int N, long K, const float *__restrict__ A, const float *__re
 #pragma unroll
         for (int p = 0; p < GA; ++p) {
             const int j = t + 256 * p;
+            if (NA % 256 != 0 && j >= NA) continue;
             if constexpr (!TA) {
                 const int row = j / (BK / 4), kq = (j % (BK / 4)) * 4;
                 As[kq + 0][row] = ra[p].x; As[kq + 1][row] = ra[p].y;
@@ -137,6 +160,7 @@ gemm_kernel(int M, int N, long K, const float *__restrict__ A, const float *__re
 #pragma unroll
         for (int p = 0; p < GB; ++p) {
             const int j = t + 256 * p;
+            if (NB % 256 != 0 && j >= NB) continue;
             if constexpr (!TB) {
                 const int kk = j / (BN / 4), jq = (j % (BN / 4)) * 4;
                 *reinterpret_cast<float4 *>(&Bs[kk][jq]) = rb[p];
@@ -148,13 +172,15 @@ gemm_kernel(int M, int N, long K, const float *__restrict__ A, const float *__re
         }
     };
 
-    floatx16 acc[TM][TN];
+    using AccT = typename std::conditional<F64, doublex4, floatx16>::type;
+    constexpr int NV = F64 ? 4 : 16;
+    AccT acc[TM][TN];
 #pragma unroll
     for (int a = 0; a < TM; ++a)
 #pragma unroll
         for (int b = 0; b < TN; ++b)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+            for (int v = 0; v < NV; ++v) acc[a][b][v] = 0;
 
     if (kbeg < kend) {
         fetch(kbeg);
@@ -164,17 +190,21 @@ gemm_kernel(int M, int N, long K, const float *__restrict__ A, const float *__re
             const bool more = k0 + BK < kend;
             if (more) fetch(k0 + BK);
 #pragma unroll
-            for (int kk = 0; kk < BK; kk += 2) {
+            for (int kk = 0; kk < BK; kk += KSTEP) {
                 float a[TM], b[TN];
 #pragma unroll
-                for (int x = 0; x < TM; ++x) a[x] = As[kk + half][(wm * TM + x) * 32 + l32];
+                for (int x = 0; x < TM; ++x) a[x] = As[kk + lk][(wm * TM + x) * UNIT + lu];
 #pragma unroll
-                for (int y = 0; y < TN; ++y) b[y] = Bs[kk + half][(wn * TN + y) * 32 + l32];
+                for (int y = 0; y < TN; ++y) b[y] = Bs[kk + lk][(wn * TN + y) * UNIT + lu];
 #pragma unroll
                 for (int x = 0; x < TM; ++x)
 #pragma unroll
-                    for (int y = 0; y < TN; ++y)
-                        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[x], b[y], acc[x][y], 0, 0, 0);
+                    for (int y = 0; y < TN; ++y) {
+                        if constexpr (F64)
+                            acc[x][y] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a[x], (double)b[y], acc[x][y], 0, 0, 0);
+                        else
+                            acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[x], b[y], acc[x][y], 0, 0, 0);
+                    }
             }
             __syncthreads();
             if (more) {
@@ -184,42 +214,53 @@ gemm_kernel(int M, int N, long K, const float *__restrict__ A, const float *__re
         }
     }
 
-    // accumulator register v of lane (half, l32) holds row 8*(v/4) + 4*half + v%4, column l32 of the tile
+    // Accumulator register v of lane (lk, lu) holds column lu and
+    //   fp32 32x32: row 8*(v/4) + 4*lk + v%4      fp64 16x16: row 4*v + lk
 #pragma unroll
     for (int x = 0; x < TM; ++x)
 #pragma unroll
         for (int y = 0; y < TN; ++y) {
-            const int gj = n0 + (wn * TN + y) * 32 + l32;
+            const int gj = n0 + (wn * TN + y) * UNIT + lu;
             if (gj >= N) continue;
-            const float bj = bias ? bias[gj] : 0.f;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int gi = m0 + (wm * TM + x) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                if (gi < M) {
-                    float o = acc[x][y][v] + bj;
+            for (int v = 0; v < NV; ++v) {
+                const int r = F64 ? 4 * v + lk : 8 * (v / 4) + 4 * lk + (v % 4);
+                const int gi = m0 + (wm * TM + x) * UNIT + r;
+                if (gi >= M) continue;
+                if constexpr (F64) {
+                    static_cast<double *>(Cv)[((size_t)split * M + gi) * N + gj] = acc[x][y][v];
+                } else {
+                    float o = acc[x][y][v] + (bias ? bias[gj] : 0.f);
                     if (relu) o = fmaxf(o, 0.f);
-                    Cout[(size_t)gi * N + gj] = o;
+                    static_cast<float *>(Cv)[(size_t)gi * N + gj] = o;
                 }
             }
         }
 }
 
 __global__ void __launch_bounds__(256)
-splitk_reduce_kernel(long count, int splits, const float *__restrict__ part, float *__restrict__ C) {
+splitk_reduce_kernel(long count, int splits, const double *__restrict__ part, float *__restrict__ C) {
     const long i = (long)blockIdx.x * 256 + threadIdx.x;
     if (i >= count) return;
-    float a = 0.f;
+    double a = 0.0;
     for (int s = 0; s < splits; ++s) a += part[(size_t)s * count + i];
-    C[i] = a;
+    C[i] = (float)a;
 }
 
 struct Tiling {
     int wm, wn, tm, tn;
-    int bm() const { return wm * tm * 32; }
-    int bn() const { return wn * tn * 32; }
 };
 
-Tiling pick_tiling(int64_t M, int64_t N) {
+int tile_m(bool f64, const Tiling &t) { return t.wm * t.tm * (f64 ? 16 : 32); }
+int tile_n(bool f64, const Tiling &t) { return t.wn * t.tn * (f64 ? 16 : 32); }
+
+Tiling pick_tiling(bool f64, int64_t M, int64_t N) {
+    if (f64) {
+        if (N <= 16) return Tiling{4, 1, 1, 1};            // 64 x 16
+        if (N <= 32) return Tiling{4, 1, 1, 2};            // 64 x 32
+        if (M >= 256 && N >= 256) return Tiling{2, 2, 4, 4};   // 128 x 128
+        return Tiling{2, 2, 2, 2};                         // 64 x 64
+    }
     if (M <= 64) return N <= 64 ? Tiling{2, 2, 1, 1} : Tiling{2, 2, 1, 2};
     if (N <= 32) return Tiling{4, 1, 1, 1};
     if (N <= 64) return Tiling{4, 1, 1, 2};
@@ -227,14 +268,15 @@ Tiling pick_tiling(int64_t M, int64_t N) {
 }
 
 // Number of chunks the reduction of a transposed-A product is cut into: enough blocks
-// to fill the chip, as long as the partials stay a small fraction of the operand bytes.
+// to fill the chip, as long as the double partials (written and read once each) stay
+// within a quarter of the operand bytes.
 int pick_splits(int ta, int64_t M, int64_t N, int64_t K) {
     if (!ta) return 1;
-    const Tiling tl = pick_tiling(M, N);
-    const int64_t tiles = ceil_div(M, tl.bm()) * ceil_div(N, tl.bn());
-    int64_t s = 1024 / tiles;
+    const Tiling tl = pick_tiling(true, M, N);
+    const int64_t tiles = ceil_div(M, tile_m(true, tl)) * ceil_div(N, tile_n(true, tl));
+    int64_t s = ceil_div(2048, tiles);
     const int64_t by_k = K / (4 * BK);
-    const int64_t by_traffic = K * (M + N) / (8 * M * N);
+    const int64_t by_traffic = K * (M + N) / (16 * M * N);
     if (s > by_k) s = by_k;
     if (s > by_traffic) s = by_traffic;
     if (s < 1) s = 1;
@@ -245,49 +287,53 @@ int pick_splits(int ta, int64_t M, int64_t N, int64_t K) {
 
 size_t gemm_workspace_bytes(int ta, int tb, int64_t M, int64_t N, int64_t K) {
     (void)tb;
-    const int s = pick_splits(ta, M, N, K);
-    return s > 1 ? align_up((size_t)s * M * N * sizeof(float)) : kAlign;
+    if (!ta) return kAlign;
+    return align_up((size_t)pick_splits(ta, M, N, K) * M * N * sizeof(double));
 }
 
-#define GEMM_CASE(TA_, TB_, WM_, WN_, TM_, TN_)                                                                   \
-    if (ta == TA_ && tb == TB_ && tl.wm == WM_ && tl.wn == WN_ && tl.tm == TM_ && tl.tn == TN_) {                 \
-        hipLaunchKernelGGL((gemm_kernel<TA_, TB_, WM_, WN_, TM_, TN_>), grid, dim3(256), 0, st, (int)M, (int)N,   \
-                           (long)K, A, B, out, splits > 1 ? nullptr : bias, splits > 1 ? 0 : relu, k_chunk,       \
-                           tiles_m, tiles_n, vec_a, vec_b);                                                       \
+#define GEMM_CASE(F64_, TB_, WM_, WN_, TM_, TN_)                                                                  \
+    if (f64 == F64_ && tbb == TB_ && tl.wm == WM_ && tl.wn == WN_ && tl.tm == TM_ && tl.tn == TN_) {              \
+        hipLaunchKernelGGL((gemm_kernel<F64_, TB_, WM_, WN_, TM_, TN_>), grid, dim3(256), 0, st, (int)M, (int)N,  \
+                           (long)K, A, B, out, bias, relu, k_chunk, tiles_m, tiles_n, splits, vec_a, vec_b);      \
         launched = true;                                                                                          \
     }
-#define GEMM_TILINGS(TA_, TB_)                                                                          \
-    GEMM_CASE(TA_, TB_, 2, 2, 1, 1) GEMM_CASE(TA_, TB_, 2, 2, 1, 2) GEMM_CASE(TA_, TB_, 4, 1, 1, 1)     \
-    GEMM_CASE(TA_, TB_, 4, 1, 1, 2) GEMM_CASE(TA_, TB_, 2, 2, 2, 2)
+#define GEMM_F32_TILINGS(TB_)                                                                                 \
+    GEMM_CASE(false, TB_, 2, 2, 1, 1) GEMM_CASE(false, TB_, 2, 2, 1, 2) GEMM_CASE(false, TB_, 4, 1, 1, 1)     \
+    GEMM_CASE(false, TB_, 4, 1, 1, 2) GEMM_CASE(false, TB_, 2, 2, 2, 2)
 
 gnn_status_t gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A, const float *B,
                          float *C, const float *bias, int relu, void *workspace, hipStream_t st) {
     if (M <= 0 || N <= 0) return GNN_OK;
     if (ta && tb) return GNN_ERR_UNSUPPORTED;
     if (M > INT32_MAX / 2 || N > INT32_MAX / 2) return GNN_ERR_UNSUPPORTED;
-    const Tiling tl = pick_tiling(M, N);
-    const int tiles_m = (int)ceil_div(M, tl.bm()), tiles_n = (int)ceil_div(N, tl.bn());
-    const int splits = pick_splits(ta, M, N, K);
+    const bool f64 = ta != 0, tbb = tb != 0;
+    const Tiling tl = pick_tiling(f64, M, N);
+    const int tiles_m = (int)ceil_div(M, tile_m(f64, tl)), tiles_n = (int)ceil_div(N, tile_n(f64, tl));
+    int splits = pick_splits(ta, M, N, K);
     long k_chunk = K;
-    if (splits > 1) k_chunk = ceil_div(ceil_div(K, splits), BK) * BK;
-    const int real_splits = splits > 1 ? (int)ceil_div(K, k_chunk) : 1;
-    float *out = splits > 1 ? static_cast<float *>(workspace) : C;
+    if (f64) {
+        k_chunk = ceil_div(ceil_div(K > 0 ? K : 1, splits), BK) * BK;
+        splits = (int)ceil_div(K > 0 ? K : 1, k_chunk);
+    }
+    void *out = f64 ? workspace : static_cast<void *>(C);
     // a float4 may be read only if every granule start is 16-byte aligned
     const int vec_a = aligned16(A) && (ta ? M % 4 == 0 : K % 4 == 0);
     const int vec_b = aligned16(B) && (tb ? K % 4 == 0 : N % 4 == 0);
-    const long total = (long)tiles_m * tiles_n;
-    dim3 grid((unsigned)(8 * ceil_div(total, 8)), (unsigned)real_splits);
+    const long total = (long)tiles_m * tiles_n * splits;
+    dim3 grid((unsigned)(8 * ceil_div(total, 8)));
     bool launched = false;
-    const bool TAb = ta != 0, TBb = tb != 0;
-    if (!TAb && !TBb) { GEMM_TILINGS(false, false) }
-    else if (!TAb && TBb) { GEMM_TILINGS(false, true) }
-    else { GEMM_TILINGS(true, false) }
+    if (!f64) {
+        if (!tbb) { GEMM_F32_TILINGS(false) } else { GEMM_F32_TILINGS(true) }
+    } else {
+        GEMM_CASE(true, false, 4, 1, 1, 1) GEMM_CASE(true, false, 4, 1, 1, 2)
+        GEMM_CASE(true, false, 2, 2, 2, 2) GEMM_CASE(true, false, 2, 2, 4, 4)
+    }
     if (!launched) return GNN_ERR_UNSUPPORTED;
     GNN_TRY(launch_status());
-    if (splits > 1) {
+    if (f64) {
         const long count = (long)M * N;
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count,
-                           real_splits, out, C);
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count, splits,
+                           static_cast<const double *>(workspace), C);
         GNN_TRY(launch_status());
     }
     return GNN_OK;

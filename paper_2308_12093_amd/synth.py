@@ -37,6 +37,12 @@ def streams(seed: int) -> dict:
     return {name: np.random.Generator(np.random.PCG64(k)) for name, k in zip(STREAMS, kids)}
 
 
+def substream(seed: int, name: str, index: int) -> np.random.Generator:
+    """Generator number ``index`` below the named stream (same tree as ``streams``)."""
+    ss = np.random.SeedSequence(seed, spawn_key=(STREAMS.index(name), index))
+    return np.random.Generator(np.random.PCG64(ss))
+
+
 # --------------------------------------------------------------------------
 # graphs
 # --------------------------------------------------------------------------
@@ -172,13 +178,10 @@ def gcn_single(name, graph_kind, f_in, f_outs, seed=0, **gkw) -> Workload:
     t = {"X": normal(s["X"], n, f_in)}
     # one W / dY draw per F_out, each from its own child stream so that the
     # arrays for one F_out do not depend on which others are requested
-    w_kids = s["W"].spawn(1024)
-    g_kids = s["dY"].spawn(1024)
-    b_kids = s["b"].spawn(1024)
     for k in f_outs:
-        t[f"W{k}"] = glorot_uniform(w_kids[k % 1024], (f_in, k), f_in, k)
-        t[f"dY{k}"] = normal(g_kids[k % 1024], n, k)
-        t[f"b{k}"] = normal(b_kids[k % 1024], k)
+        t[f"W{k}"] = glorot_uniform(substream(seed, "W", k), (f_in, k), f_in, k)
+        t[f"dY{k}"] = normal(substream(seed, "dY", k), n, k)
+        t[f"b{k}"] = normal(substream(seed, "b", k), k)
     return Workload(name, "gcn", n, rowptr, col, t, {"f_in": f_in, "f_outs": list(f_outs), "k_max": k_max})
 
 

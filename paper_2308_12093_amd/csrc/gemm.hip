@@ -238,13 +238,32 @@ gemm_kernel(int M, int N, long K, const float *__restrict__ A, const float *__re
         }
 }
 
+// C[i] = sum over chunks of part[chunk][i].  A block covers 16 consecutive outputs with
+// 16 chunk lanes each (lane j takes chunks j, j+16, ... into four rotating accumulators);
+// the lanes are then added in lane order, so the association is fixed.
 __global__ void __launch_bounds__(256)
 splitk_reduce_kernel(long count, int splits, const double *__restrict__ part, float *__restrict__ C) {
-    const long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= count) return;
-    double a = 0.0;
-    for (int s = 0; s < splits; ++s) a += part[(size_t)s * count + i];
-    C[i] = (float)a;
+    __shared__ double red[16][17];
+    const int o = threadIdx.x % 16, sl = threadIdx.x / 16;
+    const long i = (long)blockIdx.x * 16 + o;
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+    if (i < count) {
+        int s = sl;
+        for (; s + 48 < splits; s += 64) {
+            a0 += part[(size_t)s * count + i];
+            a1 += part[(size_t)(s + 16) * count + i];
+            a2 += part[(size_t)(s + 32) * count + i];
+            a3 += part[(size_t)(s + 48) * count + i];
+        }
+        for (; s < splits; s += 16) a0 += part[(size_t)s * count + i];
+    }
+    red[sl][o] = (a0 + a1) + (a2 + a3);
+    __syncthreads();
+    if (sl == 0 && i < count) {
+        double t = 0.0;
+        for (int k = 0; k < 16; ++k) t += red[k][o];
+        C[i] = (float)t;
+    }
 }
 
 struct Tiling {
@@ -332,7 +351,7 @@ gnn_status_t gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const 
     GNN_TRY(launch_status());
     if (f64) {
         const long count = (long)M * N;
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count, splits,
+        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)ceil_div(count, 16)), dim3(256), 0, st, count, splits,
                            static_cast<const double *>(workspace), C);
         GNN_TRY(launch_status());
     }

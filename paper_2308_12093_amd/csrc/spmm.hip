@@ -39,14 +39,49 @@ __device__ __forceinline__ void store_row(float *dst, const float (&a)[VEC]) {
     }
 }
 
+template <int N> struct IntVec;
+template <> struct IntVec<8> { int4 a, b; __device__ int get(int i) const { const int4 &q = i < 4 ? a : b; i &= 3; return i == 0 ? q.x : i == 1 ? q.y : i == 2 ? q.z : q.w; } };
+template <> struct IntVec<4> { int4 a; __device__ int get(int i) const { return i == 0 ? a.x : i == 1 ? a.y : i == 2 ? a.z : a.w; } };
+template <> struct IntVec<2> { int2 a; __device__ int get(int i) const { return i == 0 ? a.x : a.y; } };
+
+template <int N>
+__device__ __forceinline__ IntVec<N> lds_read(const int32_t *p) {
+    IntVec<N> v;
+    if constexpr (N == 8) { v.a = *reinterpret_cast<const int4 *>(p); v.b = *reinterpret_cast<const int4 *>(p + 4); }
+    else if constexpr (N == 4) v.a = *reinterpret_cast<const int4 *>(p);
+    else v.a = *reinterpret_cast<const int2 *>(p);
+    return v;
+}
+
+// The block first copies the index data of all its segments (erow, col and the weight
+// or weight slot of span = GPB * seg consecutive entries) into LDS with coalesced
+// loads; the gather loop then takes U entries at a time from LDS with wide reads,
+// so no global index load sits between two batches of dense-row gathers.
 template <int VEC, int LPE, int NT, int U, bool HEADS>
 __global__ void __launch_bounds__(256)
 spmm_seg_kernel(int nnz, int f, int seg, long nseg, const int32_t *__restrict__ erow,
                 const int32_t *__restrict__ col, EdgeWeights w, const float *__restrict__ B,
                 float *__restrict__ C, float *__restrict__ part, const float *__restrict__ bias, int relu) {
+    extern __shared__ __align__(16) int32_t smem[];
     constexpr int GPB = 256 / LPE;
+    const int span = GPB * seg;
+    int32_t *s_row = smem, *s_col = smem + span, *s_w = smem + 2 * span;
+    const long blk_first = (long)blockIdx.x * span;
+    for (int i = threadIdx.x; i < span; i += 256) {
+        const long x = blk_first + i;
+        if (x < nnz) {
+            s_row[i] = erow[x];
+            s_col[i] = col[x];
+            const int slot = w.perm ? w.perm[x] : (int)x;
+            if constexpr (HEADS) s_w[i] = slot;
+            else s_w[i] = __float_as_int(w.val ? w.val[slot] : 1.f);
+        }
+    }
+    __syncthreads();
+
     const int l = threadIdx.x % LPE;
-    const long g = (long)blockIdx.x * GPB + threadIdx.x / LPE;
+    const int gl = threadIdx.x / LPE;                      // group inside the block
+    const long g = (long)blockIdx.x * GPB + gl;
     if (g >= nseg) return;
 
     const int fbase = blockIdx.y * (LPE * VEC * NT);
@@ -60,10 +95,12 @@ spmm_seg_kernel(int nnz, int f, int seg, long nseg, const int32_t *__restrict__ 
         head[t] = HEADS ? (fok[t] ? foff[t] / w.head_dim : 0) : 0;
     }
 
-    const int s = (int)(g * seg);
-    const int e = min(nnz, s + seg);
-    const int first = erow[s];
-    const bool head_open = s > 0 && erow[s - 1] == first;
+    const int lb = gl * seg;                               // first LDS slot of this segment
+    const long s = g * seg;
+    const int cnt = (int)min((long)seg, (long)nnz - s);
+    const int first = s_row[lb];
+    const int before = gl > 0 ? s_row[lb - 1] : (s > 0 ? erow[s - 1] : -1);
+    const bool head_open = before == first;
 
     float acc[NT][VEC];
 #pragma unroll
@@ -88,27 +125,15 @@ spmm_seg_kernel(int nnz, int f, int seg, long nseg, const int32_t *__restrict__ 
         }
     };
 
-    for (int x = s; x < e; x += U) {
-        int r[U], c[U];
+    auto batch = [&](const int (&r)[U], const int (&c)[U], const int (&wv)[U], int valid) {
         float v[U][NT];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int idx = min(x + u, e - 1);
-            r[u] = erow[idx];
-            c[u] = col[idx];
-            const int slot = w.perm ? w.perm[idx] : idx;
-            if (!w.val) {
+        for (int u = 0; u < U; ++u)
 #pragma unroll
-                for (int t = 0; t < NT; ++t) v[u][t] = 1.f;
-            } else if constexpr (HEADS) {
-#pragma unroll
-                for (int t = 0; t < NT; ++t) v[u][t] = w.val[(size_t)slot * w.heads + head[t]];
-            } else {
-                const float vv = w.val[slot];
-#pragma unroll
-                for (int t = 0; t < NT; ++t) v[u][t] = vv;
+            for (int t = 0; t < NT; ++t) {
+                if constexpr (HEADS) v[u][t] = w.val[(size_t)wv[u] * w.heads + head[t]];
+                else v[u][t] = __int_as_float(wv[u]);
             }
-        }
         float b[U][NT][VEC];
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -129,7 +154,7 @@ spmm_seg_kernel(int nnz, int f, int seg, long nseg, const int32_t *__restrict__ 
             }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if (x + u < e) {
+            if (u < valid) {
                 if (r[u] != cur) {
                     flush(cur, cur == first && head_open, false);
 #pragma unroll
@@ -144,22 +169,52 @@ spmm_seg_kernel(int nnz, int f, int seg, long nseg, const int32_t *__restrict__ 
                     for (int i = 0; i < VEC; ++i) acc[t][i] = fmaf(v[u][t], b[u][t][i], acc[t][i]);
             }
         }
+    };
+
+    int x = 0;
+    for (; x + U <= cnt; x += U) {                         // full batches: wide LDS reads
+        const IntVec<U> vr = lds_read<U>(s_row + lb + x), vc = lds_read<U>(s_col + lb + x),
+                        vw = lds_read<U>(s_w + lb + x);
+        int r[U], c[U], wv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) { r[u] = vr.get(u); c[u] = vc.get(u); wv[u] = vw.get(u); }
+        batch(r, c, wv, U);
     }
-    const bool tail_open = e < nnz && erow[e] == cur;
+    if (x < cnt) {                                         // ragged end of the entry list
+        int r[U], c[U], wv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = lb + min(x + u, cnt - 1);
+            r[u] = s_row[i]; c[u] = s_col[i]; wv[u] = s_w[i];
+        }
+        batch(r, c, wv, cnt - x);
+    }
+    const long e = s + cnt;
+    const int after = e >= nnz ? -1 : (gl + 1 < GPB ? s_row[lb + seg] : erow[e]);
     const bool in_head = cur == first && head_open;
-    flush(cur, in_head, !in_head && tail_open);
+    flush(cur, in_head, !in_head && after == cur);
 }
 
-// Adds up, in segment order, the partials of every row that a segment boundary cuts.
+// Second pass of the entry-balanced SpMM, one wavefront per segment g:
+//  (1) if a row starts in segment g and continues past its end, add that row's
+//      partials (slot 2g+1, then slot 2x of every later segment x it reaches) and
+//      write the row.  The 64 lanes form 64/LPF slots of LPF lanes; slot s takes the
+//      partials g+1+s, g+1+s+slots, ... into four rotating accumulators, the slots
+//      are then combined by a fixed shuffle tree: a hub row that spans hundreds of
+//      segments is summed in parallel, and always in the same order.
+//  (2) lane i of wavefront w gives row 64 w + i the epilogue of zero if it is empty.
 template <int VEC>
 __global__ void __launch_bounds__(256)
-spmm_fixup_kernel(int nnz, int f, int seg, long nseg, const int32_t *__restrict__ erow,
+spmm_fixup_kernel(int n, int nnz, int f, int seg, long nseg, int lpf, const int32_t *__restrict__ erow,
                   const int32_t *__restrict__ rowptr, const float *__restrict__ part, float *__restrict__ C,
                   const float *__restrict__ bias, int relu) {
-    const int fc = f / VEC;
-    const long tid = (long)blockIdx.x * 256 + threadIdx.x;
-    const long g = tid / fc;
-    const int c = (int)(tid % fc) * VEC;
+    const int lane = threadIdx.x % kWave;
+    const long g = (long)blockIdx.x * 4 + threadIdx.x / kWave;
+
+    const long row = g * kWave + lane;
+    if (row < n && rowptr[row] == rowptr[row + 1])
+        for (int c = 0; c < f; ++c) C[(size_t)row * f + c] = epilogue(0.f, bias, c, relu);
+
     if (g >= nseg) return;
     const long e = (g + 1) * seg;
     if (e >= nnz) return;                                  // nothing follows the last segment
@@ -168,23 +223,39 @@ spmm_fixup_kernel(int nnz, int f, int seg, long nseg, const int32_t *__restrict_
     const long s = g * seg;
     if (s > 0 && erow[s - 1] == r) return;                 // the row began earlier: its first segment owns it
     const long g_end = ((long)rowptr[r + 1] - 1) / seg;
-    float a[VEC];
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) a[i] = part[(size_t)(2 * g + 1) * f + c + i];
-    for (long x = g + 1; x <= g_end; ++x)
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) a[i] += part[(size_t)(2 * x) * f + c + i];
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) C[(size_t)r * f + c + i] = epilogue(a[i], bias, c + i, relu);
-}
 
-// Rows without stored entries receive the epilogue of zero.
-__global__ void __launch_bounds__(256)
-spmm_empty_rows_kernel(int n, int f, const int32_t *__restrict__ rowptr, float *__restrict__ C,
-                       const float *__restrict__ bias, int relu) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= n || rowptr[i] != rowptr[i + 1]) return;
-    for (int c = 0; c < f; ++c) C[(size_t)i * f + c] = epilogue(0.f, bias, c, relu);
+    const int fc = f / VEC;                                // VEC-wide chunks of one row
+    const int slots = kWave / lpf, slot = lane / lpf, l = lane % lpf;
+    for (int cb = 0; cb < fc; cb += lpf) {
+        const int c = (cb + l) * VEC;
+        const bool ok = cb + l < fc;
+        float a[4][VEC];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) a[j][i] = 0.f;
+        if (ok) {
+            long x = g + 1 + slot;
+            for (; x + 3L * slots <= g_end; x += 4L * slots)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) a[j][i] += part[(size_t)(2 * (x + (long)j * slots)) * f + c + i];
+            for (; x <= g_end; x += slots)                   // fewer than four left
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) a[0][i] += part[(size_t)(2 * x) * f + c + i];
+        }
+        float t[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) t[i] = (a[0][i] + a[1][i]) + (a[2][i] + a[3][i]);
+        for (int d = lpf; d < kWave; d <<= 1)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) t[i] += __shfl_xor(t[i], d, kWave);
+        if (ok && slot == 0)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i)
+                C[(size_t)r * f + c + i] = epilogue(part[(size_t)(2 * g + 1) * f + c + i] + t[i], bias, c + i, relu);
+    }
 }
 
 // One wavefront per row, lanes stride over the features.
@@ -236,14 +307,16 @@ Shape pick_shape(int f, bool vec4) {
 }  // namespace
 
 // Segment length: as long as possible (fewer partials) while still giving the chip
-// about eight wavefronts per SIMD (256 CUs x 4 SIMDs x 8 = 8192 wavefronts).
+// about eight wavefronts per SIMD (256 CUs x 4 SIMDs x 8 = 8192 wavefronts), and short
+// enough that the index data of a block's segments fits a 24 KB LDS staging area.
 int spmm_segment_len(int64_t nnz, int f) {
     const Shape sh = pick_shape(f, f % 4 == 0);
     const int64_t groups_per_wave = kWave / sh.lpe;
     const int64_t want_groups = 8192 * groups_per_wave;
-    int64_t seg = nnz / (want_groups > 0 ? want_groups : 1);
+    const int64_t seg = nnz / (want_groups > 0 ? want_groups : 1);
+    const int cap = 8 * sh.lpe < 256 ? 8 * sh.lpe : 256;   // (256 / lpe) groups x seg entries <= 2048
     int p = 16;
-    while (p * 2 <= seg && p < 256) p <<= 1;
+    while (p * 2 <= seg && p * 2 <= cap) p <<= 1;
     return p;
 }
 
@@ -256,12 +329,13 @@ size_t spmm_workspace_bytes(int64_t nnz, int f) {
 #define SPMM_CASE(VEC_, LPE_, NT_, U_)                                                                       \
     if (sh.vec == VEC_ && sh.lpe == LPE_ && sh.nt == NT_) {                                                  \
         dim3 grid((unsigned)ceil_div(nseg, 256 / LPE_), (unsigned)sh.tiles_y);                               \
+        const size_t lds = (size_t)3 * (256 / LPE_) * seg * sizeof(int32_t);                                 \
         if (heads)                                                                                           \
-            hipLaunchKernelGGL((spmm_seg_kernel<VEC_, LPE_, NT_, U_, true>), grid, dim3(256), 0, st, nnz, f, \
-                               seg, nseg, erow, col, w, B, C, part, bias, relu);                             \
+            hipLaunchKernelGGL((spmm_seg_kernel<VEC_, LPE_, NT_, U_, true>), grid, dim3(256), lds, st, nnz,  \
+                               f, seg, nseg, erow, col, w, B, C, part, bias, relu);                          \
         else                                                                                                 \
-            hipLaunchKernelGGL((spmm_seg_kernel<VEC_, LPE_, NT_, U_, false>), grid, dim3(256), 0, st, nnz, f,\
-                               seg, nseg, erow, col, w, B, C, part, bias, relu);                             \
+            hipLaunchKernelGGL((spmm_seg_kernel<VEC_, LPE_, NT_, U_, false>), grid, dim3(256), lds, st, nnz, \
+                               f, seg, nseg, erow, col, w, B, C, part, bias, relu);                          \
         launched = true;                                                                                     \
     }
 
@@ -297,17 +371,16 @@ gnn_status_t spmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *c
     if (g_prof_stop) (void)hipEventRecord(g_prof_stop, st);
     GNN_TRY(launch_status());
 
-    const int vec = sh.vec;
-    const long threads = nseg * (f / vec);
-    if (vec == 4)
-        hipLaunchKernelGGL(spmm_fixup_kernel<4>, dim3((unsigned)ceil_div(threads, 256)), dim3(256), 0, st, nnz, f, seg,
-                           nseg, erow, rowptr, part, C, bias, relu);
+    // lanes per slot of the second pass: one per VEC-wide chunk of a row, at most a wavefront
+    int lpf = pow2_at_least(f / sh.vec);
+    if (lpf > kWave) lpf = kWave;
+    const long waves = nseg > ceil_div(n, kWave) ? nseg : ceil_div(n, kWave);
+    if (sh.vec == 4)
+        hipLaunchKernelGGL(spmm_fixup_kernel<4>, dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, st, n, nnz, f, seg,
+                           nseg, lpf, erow, rowptr, part, C, bias, relu);
     else
-        hipLaunchKernelGGL(spmm_fixup_kernel<1>, dim3((unsigned)ceil_div(threads, 256)), dim3(256), 0, st, nnz, f, seg,
-                           nseg, erow, rowptr, part, C, bias, relu);
-    GNN_TRY(launch_status());
-    hipLaunchKernelGGL(spmm_empty_rows_kernel, dim3((unsigned)ceil_div(n, 256)), dim3(256), 0, st, n, f, rowptr, C,
-                       bias, relu);
+        hipLaunchKernelGGL(spmm_fixup_kernel<1>, dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, st, n, nnz, f, seg,
+                           nseg, lpf, erow, rowptr, part, C, bias, relu);
     return launch_status();
 }
 

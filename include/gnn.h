@@ -74,7 +74,7 @@ typedef enum {
  * A graph: host struct of device arrays.
  *   csr_*      the matrix by rows (always required).  csr_val may be NULL for GAT
  *              (attention ignores edge weights, Sec. 3.2) - never for GCN.
- *   csr_erow   optional: row index of every stored entry (erow[e] = i for
+ *   csr_erow   optional for GCN, required for GAT: row index of every stored entry (erow[e] = i for
  *              rowptr[i] <= e < rowptr[i+1]), as written by gnn_expand_ptr.  With it
  *              the sparse kernels split work by equal numbers of entries, which
  *              keeps hub rows from serialising; without it they fall back to one
@@ -83,7 +83,8 @@ typedef enum {
  *              colptr[n+1], row[nnz] ascending inside a column, perm[nnz] mapping a
  *              CSC slot to the CSR slot of the same entry, val = csr_val[perm]
  *              (may be NULL: then values are fetched through perm), ecol = the
- *              expanded column index per CSC slot (optional, like csr_erow).
+ *              expanded column index per CSC slot (like csr_erow: optional for GCN,
+ *              required by gat_layer_bwd).
  *              Needed by every backward pass unless `symmetric` is set.
  *   symmetric  nonzero promises A'^T == A' (pattern and values); the CSC arrays
  *              are then ignored and may be NULL.  Only meaningful for GCN.
@@ -261,9 +262,11 @@ void gnn_profile_spmm_events(void *start_event, void *stop_event);
 /*
  * gnn_sddmm_csr - D_e = val_e * <B_i, Ct_j> for every stored entry e = (i, j) (App. E.2),
  *   batched over `heads` with the head as the middle axis: B, Ct [n][heads][f], D [nnz][heads].
- *   val NULL = all ones.
+ *   Ct is the transpose of the paper's C (row j = column j of C).  val NULL = all ones.
+ *   erow [nnz]: the row i of every entry (gnn_expand_ptr of the row pointers); the kernel is
+ *   one thread per (entry, head), so it needs no row pointers.
  */
-gnn_status_t gnn_sddmm_csr(int32_t n, int32_t nnz, const int32_t *rowptr, const int32_t *col, const float *val,
+gnn_status_t gnn_sddmm_csr(int32_t n, int32_t nnz, const int32_t *erow, const int32_t *col, const float *val,
                            const float *B, const float *Ct, int32_t heads, int32_t f, float *D,
                            void *hip_stream);
 
@@ -273,7 +276,8 @@ gnn_status_t gnn_sddmm_csr(int32_t n, int32_t nnz, const int32_t *rowptr, const 
  *   the product is split along K and reduced in a fixed order; deterministic).
  *   trans_b == 0: B is [K, N] else B is [N, K].  C is [M, N].  All row-major, dense (ld = columns).
  *   bias [N] or NULL, relu: fused epilogue.  Supported: (0,0), (0,1), (1,0).
- *   workspace: gnn_gemm_workspace_bytes(trans_a, trans_b, M, N, K).
+ *   workspace: gnn_gemm_workspace_bytes(trans_a, trans_b, M, N, K); required for (0,0) (holds B^T)
+ *   and (1,0) (holds the partial products); (0,1) needs none.
  */
 gnn_status_t gnn_gemm(int32_t trans_a, int32_t trans_b, int64_t M, int64_t N, int64_t K,
                       const float *A, const float *B, float *C, const float *bias, int32_t relu,

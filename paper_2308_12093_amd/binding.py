@@ -247,8 +247,8 @@ def gnn_profile_spmm_events(start_event, stop_event):
     lib.gnn_profile_spmm_events(start_event, stop_event)
 
 
-def gnn_sddmm_csr(n, nnz, rowptr, col, val, B, Ct, heads, f, D):
-    _check(lib.gnn_sddmm_csr(n, nnz, _ptr(rowptr), _ptr(col), _ptr(val), _ptr(B), _ptr(Ct), heads, f, _ptr(D),
+def gnn_sddmm_csr(n, nnz, erow, col, val, B, Ct, heads, f, D):
+    _check(lib.gnn_sddmm_csr(n, nnz, _ptr(erow), _ptr(col), _ptr(val), _ptr(B), _ptr(Ct), heads, f, _ptr(D),
                              _stream()), "gnn_sddmm_csr")
 
 

@@ -200,12 +200,12 @@ gnn_status_t gnn_spmm_csr(int32_t n, int32_t nnz, const int32_t *rowptr, const i
                        as_stream(hip_stream));
 }
 
-gnn_status_t gnn_sddmm_csr(int32_t n, int32_t nnz, const int32_t *rowptr, const int32_t *col, const float *val,
+gnn_status_t gnn_sddmm_csr(int32_t n, int32_t nnz, const int32_t *erow, const int32_t *col, const float *val,
                            const float *B, const float *Ct, int32_t heads, int32_t f, float *D,
                            void *hip_stream) {
-    if (n < 0 || nnz < 0 || f <= 0 || heads <= 0 || !rowptr) return GNN_ERR_INVALID_ARG;
-    if (nnz > 0 && (!col || !B || !Ct || !D)) return GNN_ERR_INVALID_ARG;
-    return sddmm_launch(n, nnz, rowptr, col, val, B, Ct, heads, f, D, as_stream(hip_stream));
+    if (n < 0 || nnz < 0 || f <= 0 || heads <= 0) return GNN_ERR_INVALID_ARG;
+    if (nnz > 0 && (!erow || !col || !B || !Ct || !D)) return GNN_ERR_INVALID_ARG;
+    return sddmm_launch(n, nnz, erow, col, val, B, Ct, heads, f, D, as_stream(hip_stream));
 }
 
 void gnn_profile_spmm_events(void *start_event, void *stop_event) {
@@ -225,7 +225,7 @@ gnn_status_t gnn_gemm(int32_t trans_a, int32_t trans_b, int64_t M, int64_t N, in
     if (!C || (K > 0 && (!A || !B))) return GNN_ERR_INVALID_ARG;
     if (trans_a && trans_b) return GNN_ERR_UNSUPPORTED;
     const size_t need = gnn_gemm_workspace_bytes(trans_a, trans_b, M, N, K);
-    if (need > kAlign) {
+    if (trans_a || !trans_b) {                          // only the A B^T form needs no scratch
         if (!workspace || bad_align(workspace)) return GNN_ERR_INVALID_ARG;
         if (workspace_bytes < need) return GNN_ERR_BUFFER_TOO_SMALL;
     }

@@ -82,26 +82,25 @@ gnn_status_t expand_ptr_launch(int n, int nnz, const int32_t *ptr, int32_t *out,
 gnn_status_t gather_f32_launch(int64_t count, const float *in, const int32_t *perm, float *out, hipStream_t st);
 
 // ---- GAT kernels (gat.hip) -----------------------------------------------------------
+int gat_segment_len(int64_t nnz, int h);
+size_t gat_walker_workspace_bytes(int64_t nnz, int h);
 gnn_status_t gat_node_attention_launch(int n, int h, int k, const float *M, const float *a_src, const float *a_dst,
                                        float *s, float *d, hipStream_t st);
-// alpha [nnz][h] (= softmax over each row of LeakyReLU(s_i + d_j)); mask [nnz][h] or NULL
-gnn_status_t gat_edge_softmax_launch(int n, int nnz, int h, const int32_t *rowptr, const int32_t *col,
-                                     const float *s, const float *d, float slope, float *alpha, uint8_t *mask,
-                                     hipStream_t st);
-// gy [nnz][h], ds [n][h]; mask NULL: the sign is recomputed from s, d
-gnn_status_t gat_edge_backward_launch(int n, int nnz, int h, int k, const int32_t *rowptr, const int32_t *col,
-                                      const float *G, const float *M, const float *alpha, const uint8_t *mask,
-                                      const float *s, const float *d, float slope, float *gy, float *ds,
-                                      hipStream_t st);
-// dd[j][p] = sum over column j of gy (through perm);  dM_j = ds_j a_src + dd_j a_dst + agg_j (agg already in dM)
-gnn_status_t gat_column_sums_launch(int n, int h, const int32_t *colptr, const int32_t *perm, const float *gy,
-                                    float *dd, hipStream_t st);
+// stat [n][h][2] (row max, sum of exponentials), alpha [nnz][h], mask [nnz][h] or NULL
+gnn_status_t gat_edge_softmax_launch(int n, int nnz, int h, const int32_t *rowptr, const int32_t *erow,
+                                     const int32_t *col, const float *s, const float *d, float slope, float *stat,
+                                     float *alpha, uint8_t *mask, void *workspace, hipStream_t st);
+// gy [nnz][h]: g_alpha on entry, g_y on exit; sums [n][h][3] scratch; ds [n][h]; mask NULL: sign from s, d
+gnn_status_t gat_edge_backward_launch(int n, int nnz, int h, const int32_t *rowptr, const int32_t *erow,
+                                      const int32_t *col, const float *alpha, const uint8_t *mask, const float *s,
+                                      const float *d, float slope, float *gy, float *sums, float *ds,
+                                      void *workspace, hipStream_t st);
 gnn_status_t gat_add_rank1_launch(int n, int h, int k, const float *ds, const float *dd, const float *a_src,
                                   const float *a_dst, float *dM, hipStream_t st);
 // da[p][c] = sum_i w[i][p] M[i][p][c]; workspace colsum_workspace_bytes(n, h*k)
 gnn_status_t gat_attention_grad_launch(int n, int h, int k, const float *w, const float *M, float *da,
                                        void *workspace, hipStream_t st);
-gnn_status_t sddmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *col, const float *val,
+gnn_status_t sddmm_launch(int n, int nnz, const int32_t *erow, const int32_t *col, const float *val,
                           const float *B, const float *Ct, int heads, int f, float *D, hipStream_t st);
 
 }  // namespace gnn

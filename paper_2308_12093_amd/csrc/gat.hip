@@ -1,0 +1,369 @@
+// GAT kernels (Sec. "GAT Forward Pass", "GAT Backward Pass", App. B) for gfx950.
+//
+// All per-edge tensors are [nnz][heads] and all per-node tensors [n][heads] or
+// [n][heads][dim]: the head is the last / middle axis, so the `heads` values of one
+// edge or node sit in one cache line and are handled by neighbouring lanes (Sec. 3.2).
+//
+// Two kernel shapes cover every step:
+//   * entry-parallel kernels, one thread per (entry, head): logits -> alpha, the SDDMM
+//     dot products, the chain rule through softmax and LeakyReLU.  They need the row
+//     of each entry, hence the expanded row index `erow`.
+//   * an entry-balanced row reduction (head_walker_kernel): like the SpMM it cuts the
+//     entry list into equal segments, one group of lanes (one lane per head) per
+//     segment, keeps a running reduction per row and leaves partials for rows that a
+//     segment boundary cuts; a second kernel combines the partials in segment order.
+//     It computes the softmax statistics (running max and sum of exponentials) and
+//     the three row sums the backward pass needs.
+#include "common.h"
+
+namespace gnn {
+namespace {
+
+__device__ __forceinline__ float leaky(float y, float slope) { return y > 0.f ? y : slope * y; }
+
+// ---- s_i = <a_src, m_i>, d_i = <a_dst, m_i> per head (App. B) ------------------------
+__global__ void __launch_bounds__(256)
+node_attention_kernel(long count, int h, int k, const float *__restrict__ M, const float *__restrict__ a_src,
+                      const float *__restrict__ a_dst, float *__restrict__ s, float *__restrict__ d) {
+    const long t = (long)blockIdx.x * 256 + threadIdx.x;      // t = i * h + p
+    if (t >= count) return;
+    const int p = (int)(t % h);
+    const float *m = M + (size_t)t * k;
+    const float *as = a_src + (size_t)p * k, *ad = a_dst + (size_t)p * k;
+    float ss = 0.f, dd = 0.f;
+    for (int c = 0; c < k; ++c) {
+        const float v = m[c];
+        ss = fmaf(as[c], v, ss);
+        dd = fmaf(ad[c], v, dd);
+    }
+    s[t] = ss;
+    d[t] = dd;
+}
+
+// ---- entry-balanced reduction over the rows, one lane per head -----------------------
+// Op::NACC floats per (row, head).  Softmax statistics keep (max, sum of exp(w - max)).
+struct StatsOp {
+    static constexpr int NACC = 2;
+    const float *s, *d;
+    float slope;
+    __device__ void init(float (&a)[2]) const { a[0] = -INFINITY; a[1] = 0.f; }
+    __device__ void load(long e, int r, int c, int h, int p, float (&v)[3]) const {
+        (void)e;
+        v[0] = s[(size_t)r * h + p];
+        v[1] = d[(size_t)c * h + p];
+    }
+    __device__ void fold(float (&a)[2], const float (&v)[3]) const {
+        const float w = leaky(v[0] + v[1], slope);
+        if (w > a[0]) { a[1] = a[1] * __expf(a[0] - w) + 1.f; a[0] = w; }
+        else a[1] += __expf(w - a[0]);
+    }
+    __device__ static void combine(float (&a)[2], const float (&b)[2]) {
+        if (b[0] == -INFINITY) return;
+        const float m = fmaxf(a[0], b[0]);
+        a[1] = a[1] * __expf(a[0] - m) + b[1] * __expf(b[0] - m);
+        a[0] = m;
+    }
+};
+
+// Row sums for the backward pass: t = sum alpha*ga, P = sum over y>0 of alpha*ga, Q = sum over y>0 of alpha.
+struct SumsOp {
+    static constexpr int NACC = 3;
+    const float *alpha, *ga;
+    const uint8_t *mask;          // NULL: the sign is recomputed from s, d
+    const float *s, *d;
+    __device__ void init(float (&a)[3]) const { a[0] = a[1] = a[2] = 0.f; }
+    __device__ void load(long e, int r, int c, int h, int p, float (&v)[3]) const {
+        v[0] = alpha[(size_t)e * h + p];
+        v[1] = ga[(size_t)e * h + p];
+        if (mask) v[2] = mask[(size_t)e * h + p] ? 1.f : 0.f;
+        else v[2] = (s[(size_t)r * h + p] + d[(size_t)c * h + p]) > 0.f ? 1.f : 0.f;
+    }
+    __device__ void fold(float (&a)[3], const float (&v)[3]) const {
+        const float x = v[0] * v[1];
+        a[0] += x;
+        a[1] += v[2] * x;
+        a[2] += v[2] * v[0];
+    }
+    __device__ static void combine(float (&a)[3], const float (&b)[3]) {
+        a[0] += b[0]; a[1] += b[1]; a[2] += b[2];
+    }
+};
+
+template <class Op, int HP, int U>
+__global__ void __launch_bounds__(256)
+head_walker_kernel(int nnz, int h, int seg, long nseg, const int32_t *__restrict__ erow,
+                   const int32_t *__restrict__ col, Op op, float *__restrict__ out, float *__restrict__ part) {
+    extern __shared__ __align__(16) int32_t smem[];
+    constexpr int GPB = 256 / HP, NA = Op::NACC;
+    const int span = GPB * seg;
+    int32_t *s_row = smem, *s_col = smem + span;
+    const long blk_first = (long)blockIdx.x * span;
+    for (int i = threadIdx.x; i < span; i += 256) {
+        const long x = blk_first + i;
+        if (x < nnz) { s_row[i] = erow[x]; s_col[i] = col[x]; }
+    }
+    __syncthreads();
+    const int p = threadIdx.x % HP, gl = threadIdx.x / HP;
+    const long g = (long)blockIdx.x * GPB + gl;
+    if (g >= nseg || p >= h) return;
+    const int lb = gl * seg;
+    const long s0 = g * seg;
+    const int cnt = (int)min((long)seg, (long)nnz - s0);
+    const int first = s_row[lb];
+    const int before = gl > 0 ? s_row[lb - 1] : (s0 > 0 ? erow[s0 - 1] : -1);
+    const bool head_open = before == first;
+    float acc[NA];
+    op.init(acc);
+    int cur = first;
+    auto flush = [&](int row, int slot) {             // slot 0: head partial, 1: tail partial, 2: the row itself
+        float *dst = slot == 2 ? out + ((size_t)row * h + p) * NA : part + (((size_t)(2 * g + slot)) * h + p) * NA;
+#pragma unroll
+        for (int a = 0; a < NA; ++a) dst[a] = acc[a];
+    };
+    for (int x = 0; x < cnt; x += U) {
+        int r[U], c[U];
+        float v[U][3];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int i = lb + min(x + u, cnt - 1);
+            r[u] = s_row[i];
+            c[u] = s_col[i];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) op.load(s0 + min(x + u, cnt - 1), r[u], c[u], h, p, v[u]);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (x + u < cnt) {
+                if (r[u] != cur) {
+                    flush(cur, (cur == first && head_open) ? 0 : 2);
+                    op.init(acc);
+                    cur = r[u];
+                }
+                op.fold(acc, v[u]);
+            }
+        }
+    }
+    const long e = s0 + cnt;
+    const int after = e >= nnz ? -1 : (gl + 1 < GPB ? s_row[lb + seg] : erow[e]);
+    const bool in_head = cur == first && head_open;
+    flush(cur, in_head ? 0 : (after == cur ? 1 : 2));
+}
+
+// Combines the partials of every row cut by a segment boundary, in segment order;
+// one thread per (segment, head).
+template <class Op>
+__global__ void __launch_bounds__(256)
+head_fixup_kernel(int nnz, int h, int seg, long nseg, const int32_t *__restrict__ erow,
+                  const int32_t *__restrict__ rowptr, const float *__restrict__ part, float *__restrict__ out) {
+    constexpr int NA = Op::NACC;
+    const long t = (long)blockIdx.x * 256 + threadIdx.x;
+    const long g = t / h;
+    const int p = (int)(t % h);
+    if (g >= nseg) return;
+    const long e = (g + 1) * seg;
+    if (e >= nnz) return;
+    const int r = erow[e - 1];
+    if (erow[e] != r) return;
+    const long s0 = g * seg;
+    if (s0 > 0 && erow[s0 - 1] == r) return;
+    const long g_end = ((long)rowptr[r + 1] - 1) / seg;
+    float acc[NA], b[NA];
+    const float *src = part + (((size_t)(2 * g + 1)) * h + p) * NA;
+#pragma unroll
+    for (int a = 0; a < NA; ++a) acc[a] = src[a];
+    for (long x = g + 1; x <= g_end; ++x) {
+        src = part + (((size_t)(2 * x)) * h + p) * NA;
+#pragma unroll
+        for (int a = 0; a < NA; ++a) b[a] = src[a];
+        Op::combine(acc, b);
+    }
+    float *dst = out + ((size_t)r * h + p) * NA;
+#pragma unroll
+    for (int a = 0; a < NA; ++a) dst[a] = acc[a];
+}
+
+// ---- entry-parallel kernels, thread t = e * h + p --------------------------------------
+// alpha_e = exp(w_e - max_i) / sum_i, mask_e = (y_e > 0)
+__global__ void __launch_bounds__(256)
+edge_alpha_kernel(long count, int h, const int32_t *__restrict__ erow, const int32_t *__restrict__ col,
+                  const float *__restrict__ s, const float *__restrict__ d, const float *__restrict__ stat,
+                  float slope, float *__restrict__ alpha, uint8_t *__restrict__ mask) {
+    const long t = (long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= count) return;
+    const long e = t / h;
+    const int p = (int)(t % h);
+    const int r = erow[e], c = col[e];
+    const float y = s[(size_t)r * h + p] + d[(size_t)c * h + p];
+    const float2 ml = reinterpret_cast<const float2 *>(stat)[(size_t)r * h + p];
+    alpha[t] = __expf(leaky(y, slope) - ml.x) / ml.y;
+    if (mask) mask[t] = y > 0.f;
+}
+
+// D_e = val_e * <B_i, Ct_j> per head (App. E.2)
+__global__ void __launch_bounds__(256)
+sddmm_edge_kernel(long count, int h, int k, const int32_t *__restrict__ erow, const int32_t *__restrict__ col,
+                  const float *__restrict__ val, const float *__restrict__ Bm, const float *__restrict__ Ct,
+                  float *__restrict__ D, int vec) {
+    const long t = (long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= count) return;
+    const long e = t / h;
+    const int p = (int)(t % h);
+    const float *b = Bm + ((size_t)erow[e] * h + p) * k;
+    const float *c = Ct + ((size_t)col[e] * h + p) * k;
+    float acc = 0.f;
+    if (vec) {
+        for (int x = 0; x < k; x += 4) {
+            const float4 u = *reinterpret_cast<const float4 *>(b + x), v = *reinterpret_cast<const float4 *>(c + x);
+            acc = fmaf(u.x, v.x, acc); acc = fmaf(u.y, v.y, acc); acc = fmaf(u.z, v.z, acc); acc = fmaf(u.w, v.w, acc);
+        }
+    } else {
+        for (int x = 0; x < k; ++x) acc = fmaf(b[x], c[x], acc);
+    }
+    D[t] = val ? val[e] * acc : acc;
+}
+
+// g_y_e = alpha_e (g_alpha_e - t_i) * (y_e > 0 ? 1 : beta); gy holds g_alpha on entry
+__global__ void __launch_bounds__(256)
+edge_gy_kernel(long count, int h, const int32_t *__restrict__ erow, const int32_t *__restrict__ col,
+               const float *__restrict__ alpha, const uint8_t *__restrict__ mask, const float *__restrict__ s,
+               const float *__restrict__ d, const float *__restrict__ sums, float slope, float *__restrict__ gy) {
+    const long t = (long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= count) return;
+    const long e = t / h;
+    const int p = (int)(t % h);
+    const int r = erow[e];
+    bool pos;
+    if (mask) pos = mask[t] != 0;
+    else pos = (s[(size_t)r * h + p] + d[(size_t)col[e] * h + p]) > 0.f;
+    const float ti = sums[((size_t)r * h + p) * 3];
+    gy[t] = alpha[t] * (gy[t] - ti) * (pos ? 1.f : slope);
+}
+
+// ds_i = sum_e g_y_e = (1 - beta) (P_i - t_i Q_i): the softmax gradient sums to zero over a row,
+// so only the entries with a positive logit (factor 1 instead of beta) leave a remainder.
+__global__ void __launch_bounds__(256)
+node_ds_kernel(long count, const float *__restrict__ sums, float slope, float *__restrict__ ds) {
+    const long t = (long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= count) return;
+    const float ti = sums[t * 3], P = sums[t * 3 + 1], Q = sums[t * 3 + 2];
+    ds[t] = (1.f - slope) * (P - ti * Q);
+}
+
+// dM_{i,p,c} += ds_{i,p} a_src_{p,c} + dd_{i,p} a_dst_{p,c}
+__global__ void __launch_bounds__(256)
+add_rank1_kernel(long count, int h, int k, const float *__restrict__ ds, const float *__restrict__ dd,
+                 const float *__restrict__ a_src, const float *__restrict__ a_dst, float *__restrict__ dM) {
+    const long t = (long)blockIdx.x * 256 + threadIdx.x;      // t = (i * h + p) * k + c
+    if (t >= count) return;
+    const int f = h * k;
+    const int pc = (int)(t % f);
+    const long ip = t / k;
+    dM[t] += ds[ip] * a_src[pc] + dd[ip] * a_dst[pc];
+}
+
+int pow2_at_least(int x) {
+    int p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+template <class Op>
+gnn_status_t run_head_walker(int nnz, int h, const int32_t *rowptr, const int32_t *erow, const int32_t *col, Op op,
+                             float *out, float *part, hipStream_t st) {
+    const int hp = pow2_at_least(h);
+    const int seg = gat_segment_len(nnz, h);
+    const long nseg = ceil_div(nnz, seg);
+    const int gpb = 256 / hp;
+    const size_t lds = (size_t)2 * gpb * seg * sizeof(int32_t);
+    dim3 grid((unsigned)ceil_div(nseg, gpb));
+#define WALK_CASE(HP_)                                                                                            \
+    if (hp == HP_)                                                                                                \
+        hipLaunchKernelGGL((head_walker_kernel<Op, HP_, 8>), grid, dim3(256), lds, st, nnz, h, seg, nseg, erow,   \
+                           col, op, out, part);
+    WALK_CASE(1) WALK_CASE(2) WALK_CASE(4) WALK_CASE(8) WALK_CASE(16) WALK_CASE(32) WALK_CASE(64)
+#undef WALK_CASE
+    GNN_TRY(launch_status());
+    hipLaunchKernelGGL(head_fixup_kernel<Op>, dim3((unsigned)ceil_div(nseg * h, 256)), dim3(256), 0, st, nnz, h, seg,
+                       nseg, erow, rowptr, part, out);
+    return launch_status();
+}
+
+}  // namespace
+
+// segment length of the head walker: GPB * seg <= 2048 staged entries, at least 16
+int gat_segment_len(int64_t nnz, int h) {
+    const int hp = pow2_at_least(h);
+    const int64_t want_groups = 8192 * (kWave / hp);
+    const int64_t seg = nnz / (want_groups > 0 ? want_groups : 1);
+    const int cap = 8 * hp < 256 ? 8 * hp : 256;
+    int p = 16;
+    while (p * 2 <= seg && p * 2 <= cap) p <<= 1;
+    return p;
+}
+
+size_t gat_walker_workspace_bytes(int64_t nnz, int h) {
+    if (nnz <= 0) return kAlign;
+    const int64_t nseg = ceil_div(nnz, gat_segment_len(nnz, h));
+    return align_up((size_t)(2 * nseg) * h * 3 * sizeof(float));
+}
+
+gnn_status_t gat_node_attention_launch(int n, int h, int k, const float *M, const float *a_src, const float *a_dst,
+                                       float *s, float *d, hipStream_t st) {
+    const long count = (long)n * h;
+    if (count <= 0) return GNN_OK;
+    hipLaunchKernelGGL(node_attention_kernel, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count, h, k, M,
+                       a_src, a_dst, s, d);
+    return launch_status();
+}
+
+// stat [n][h][2] = (row max of the LeakyReLU'd logits, sum of exp(. - max)); then alpha, mask
+gnn_status_t gat_edge_softmax_launch(int n, int nnz, int h, const int32_t *rowptr, const int32_t *erow,
+                                     const int32_t *col, const float *s, const float *d, float slope, float *stat,
+                                     float *alpha, uint8_t *mask, void *workspace, hipStream_t st) {
+    (void)n;
+    if (nnz <= 0) return GNN_OK;
+    StatsOp op{s, d, slope};
+    GNN_TRY(run_head_walker<StatsOp>(nnz, h, rowptr, erow, col, op, stat, static_cast<float *>(workspace), st));
+    const long count = (long)nnz * h;
+    hipLaunchKernelGGL(edge_alpha_kernel, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count, h, erow, col,
+                       s, d, stat, slope, alpha, mask);
+    return launch_status();
+}
+
+gnn_status_t sddmm_launch(int n, int nnz, const int32_t *erow, const int32_t *col, const float *val,
+                          const float *B, const float *Ct, int heads, int f, float *D, hipStream_t st) {
+    (void)n;
+    const long count = (long)nnz * heads;
+    if (count <= 0) return GNN_OK;
+    const int vec = f % 4 == 0 && aligned16(B) && aligned16(Ct);
+    hipLaunchKernelGGL(sddmm_edge_kernel, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count, heads, f,
+                       erow, col, val, B, Ct, D, vec);
+    return launch_status();
+}
+
+// gy [nnz][h]: g_alpha on entry, g_y on exit; sums [n][h][3] scratch; ds [n][h]
+gnn_status_t gat_edge_backward_launch(int n, int nnz, int h, const int32_t *rowptr, const int32_t *erow,
+                                      const int32_t *col, const float *alpha, const uint8_t *mask, const float *s,
+                                      const float *d, float slope, float *gy, float *sums, float *ds,
+                                      void *workspace, hipStream_t st) {
+    if (nnz <= 0 || n <= 0) return GNN_OK;
+    SumsOp op{alpha, gy, mask, s, d};
+    GNN_TRY(run_head_walker<SumsOp>(nnz, h, rowptr, erow, col, op, sums, static_cast<float *>(workspace), st));
+    const long ecount = (long)nnz * h, ncount = (long)n * h;
+    hipLaunchKernelGGL(edge_gy_kernel, dim3((unsigned)ceil_div(ecount, 256)), dim3(256), 0, st, ecount, h, erow, col,
+                       alpha, mask, s, d, sums, slope, gy);
+    GNN_TRY(launch_status());
+    hipLaunchKernelGGL(node_ds_kernel, dim3((unsigned)ceil_div(ncount, 256)), dim3(256), 0, st, ncount, sums, slope, ds);
+    return launch_status();
+}
+
+gnn_status_t gat_add_rank1_launch(int n, int h, int k, const float *ds, const float *dd, const float *a_src,
+                                  const float *a_dst, float *dM, hipStream_t st) {
+    const long count = (long)n * h * k;
+    if (count <= 0) return GNN_OK;
+    hipLaunchKernelGGL(add_rank1_kernel, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count, h, k, ds, dd,
+                       a_src, a_dst, dM);
+    return launch_status();
+}
+
+}  // namespace gnn

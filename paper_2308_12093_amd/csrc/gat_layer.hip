@@ -1,21 +1,99 @@
-// GAT layer forward / backward (placeholder until the kernels land).
+// GAT layer forward / backward (Sec. "GAT Forward Pass", "GAT Backward Pass") as a
+// sequence of kernel launches, with the caching variants of Table "GAT caching":
+// whatever the plan's variant keeps (M; M, s, d; M, alpha, mask) is written to the
+// cache by forward and read by backward, everything else is rebuilt in backward with
+// the forward kernels.  Host code: it only carves buffers and enqueues kernels.
 #include "plan.h"
 
 namespace gnn {
 
-gnn_status_t gat_forward(Plan &, const gnn_graph_t &, const float *, const float *, const float *, const float *,
-                         const float *, float *, void *, void *, hipStream_t) {
-    return GNN_ERR_UNSUPPORTED;
+namespace {
+
+struct Buffers {
+    float *M, *s, *d, *alpha, *stat;
+    uint8_t *mask;                 // NULL unless the variant caches it
+};
+
+template <typename T> T *at(void *base, size_t off) {
+    return off == (size_t)-1 ? nullptr : reinterpret_cast<T *>(static_cast<char *>(base) + off);
 }
 
-gnn_status_t gat_backward(Plan &, const gnn_graph_t &, const float *, const float *, const float *, const float *,
-                          const float *, float *, float *, float *, float *, float *, void *, void *, hipStream_t) {
-    return GNN_ERR_UNSUPPORTED;
+Buffers pick_buffers(const GatLayout &L, void *cache, void *ws) {
+    Buffers b;
+    b.M = L.c_M != (size_t)-1 ? at<float>(cache, L.c_M) : at<float>(ws, L.w_M);
+    b.s = L.c_s != (size_t)-1 ? at<float>(cache, L.c_s) : at<float>(ws, L.w_s);
+    b.d = L.c_d != (size_t)-1 ? at<float>(cache, L.c_d) : at<float>(ws, L.w_d);
+    b.alpha = L.c_alpha != (size_t)-1 ? at<float>(cache, L.c_alpha) : at<float>(ws, L.w_alpha);
+    b.mask = at<uint8_t>(cache, L.c_mask);
+    b.stat = at<float>(ws, L.w_stat);
+    return b;
 }
 
-gnn_status_t sddmm_launch(int, int, const int32_t *, const int32_t *, const float *, const float *, const float *, int,
-                          int, float *, hipStream_t) {
-    return GNN_ERR_UNSUPPORTED;
+}  // namespace
+
+gnn_status_t gat_forward(Plan &p, const gnn_graph_t &g, const float *X, const float *W, const float *a_src,
+                         const float *a_dst, const float *b, float *Y, void *cache, void *workspace, hipStream_t st) {
+    const gnn_plan_desc_t &d = p.desc;
+    const int n = d.n, q = d.nnz, m = d.f_in, h = d.heads, k = d.f_out, f = h * k;
+    if (!g.csr_erow && q > 0) return GNN_ERR_BAD_GRAPH;
+    const GatLayout L = gat_layout(p);
+    const Buffers B = pick_buffers(L, cache, workspace);
+
+    // M = X Theta; s, d per node and head (App. B)
+    GNN_TRY(gemm_launch(0, 0, n, f, m, X, W, B.M, nullptr, 0, at<char>(workspace, L.w_gemm_nn), st));
+    GNN_TRY(gat_node_attention_launch(n, h, k, B.M, a_src, a_dst, B.s, B.d, st));
+    // alpha = row softmax of LeakyReLU(s_i + d_j)
+    GNN_TRY(gat_edge_softmax_launch(n, q, h, g.csr_rowptr, g.csr_erow, g.csr_col, B.s, B.d, d.leaky_slope, B.stat,
+                                    B.alpha, B.mask, at<char>(workspace, L.w_walk), st));
+    // Y_i = sum_e alpha_e M_j (+ b): SpMM with one weight per entry and head
+    GNN_TRY(spmm_launch(n, q, g.csr_rowptr, g.csr_col, g.csr_erow, EdgeWeights{B.alpha, nullptr, h, k}, B.M, f, Y,
+                        d.has_bias ? b : nullptr, 0, at<char>(workspace, L.w_spmm), st));
+    p.cache_filled = true;
+    return GNN_OK;
+}
+
+gnn_status_t gat_backward(Plan &p, const gnn_graph_t &g, const float *X, const float *W, const float *a_src,
+                          const float *a_dst, const float *dY, float *dW, float *da_src, float *da_dst, float *db,
+                          float *dX, void *cache, void *workspace, hipStream_t st) {
+    const gnn_plan_desc_t &d = p.desc;
+    const int n = d.n, q = d.nnz, m = d.f_in, h = d.heads, k = d.f_out, f = h * k;
+    if ((!g.csr_erow || !g.csc_ecol) && q > 0) return GNN_ERR_BAD_GRAPH;
+    const GatLayout L = gat_layout(p);
+    const Buffers B = pick_buffers(L, cache, workspace);
+    const gnn_cache_t variant = p.info.cache;
+
+    // rebuild what the variant did not keep
+    if (variant == GNN_CACHE_NONE)
+        GNN_TRY(gemm_launch(0, 0, n, f, m, X, W, B.M, nullptr, 0, at<char>(workspace, L.w_gemm_nn), st));
+    if (variant == GNN_CACHE_NONE || variant == GNN_CACHE_GAT_FEAT)
+        GNN_TRY(gat_node_attention_launch(n, h, k, B.M, a_src, a_dst, B.s, B.d, st));
+    if (variant != GNN_CACHE_GAT_FEAT_EDGE)
+        GNN_TRY(gat_edge_softmax_launch(n, q, h, g.csr_rowptr, g.csr_erow, g.csr_col, B.s, B.d, d.leaky_slope, B.stat,
+                                        B.alpha, nullptr, at<char>(workspace, L.w_walk), st));
+
+    float *gy = at<float>(workspace, L.w_gy), *sums = at<float>(workspace, L.w_sums);
+    float *ds = at<float>(workspace, L.w_ds), *dd = at<float>(workspace, L.w_dd), *dM = at<float>(workspace, L.w_dM);
+
+    if (d.has_bias) GNN_TRY(colsum_launch(n, f, dY, db, at<char>(workspace, L.w_red), st));
+    // dL/dalpha on the pattern: g_alpha_e = <G_i, M_j> per head (SDDMM)
+    GNN_TRY(sddmm_launch(n, q, g.csr_erow, g.csr_col, nullptr, dY, B.M, h, k, gy, st));
+    // softmax and LeakyReLU backward: g_y per entry, ds per node
+    GNN_TRY(gat_edge_backward_launch(n, q, h, g.csr_rowptr, g.csr_erow, g.csr_col, B.alpha, B.mask, B.s, B.d,
+                                     d.leaky_slope, gy, sums, ds, at<char>(workspace, L.w_walk), st));
+    // dd_j = sum over column j of g_y: a row sum over the CSC arrays, gathering g_y rows through perm
+    GNN_TRY(spmm_launch(n, q, g.csc_colptr, g.csc_perm, g.csc_ecol, EdgeWeights{nullptr, nullptr, 1, h}, gy, h, dd,
+                        nullptr, 0, at<char>(workspace, L.w_spmm_h), st));
+    // dM = A^T G (weights alpha through perm) + ds a_src + dd a_dst
+    GNN_TRY(spmm_launch(n, q, g.csc_colptr, g.csc_row, g.csc_ecol, EdgeWeights{B.alpha, g.csc_perm, h, k}, dY, f, dM,
+                        nullptr, 0, at<char>(workspace, L.w_spmm), st));
+    GNN_TRY(gat_add_rank1_launch(n, h, k, ds, dd, a_src, a_dst, dM, st));
+    // da_src = M^T ds, da_dst = M^T dd
+    GNN_TRY(gat_attention_grad_launch(n, h, k, ds, B.M, da_src, at<char>(workspace, L.w_red), st));
+    GNN_TRY(gat_attention_grad_launch(n, h, k, dd, B.M, da_dst, at<char>(workspace, L.w_red), st));
+    // dTheta = X^T dM, dX = dM Theta^T
+    GNN_TRY(gemm_launch(1, 0, m, f, n, X, dM, dW, nullptr, 0, at<char>(workspace, L.w_gemm_tn), st));
+    if (d.need_input_grad) GNN_TRY(gemm_launch(0, 1, n, m, f, dM, W, dX, nullptr, 0, nullptr, st));
+    return GNN_OK;
 }
 
 }  // namespace gnn

@@ -41,15 +41,17 @@ gnn_status_t gcn_forward(Plan &p, const gnn_graph_t &g, const float *X, const fl
         // T = X W, then Y = A' T (+ b, ReLU) fused into the SpMM write
         float *T = ws.take<float>((size_t)n * k);
         void *sp = ws.take<char>(spmm_workspace_bytes(d.nnz, k));
-        GNN_TRY(gemm_launch(0, 0, n, k, m, X, W, T, nullptr, 0, nullptr, st));
+        void *wt = ws.take<char>(gemm_workspace_bytes(0, 0, n, k, m));
+        GNN_TRY(gemm_launch(0, 0, n, k, m, X, W, T, nullptr, 0, wt, st));
         GNN_TRY(spmm(g, forward_view(g, k), T, k, Y, bias, d.fuse_relu, sp, st));
     } else {
         // P = A' X (kept in the cache slot when the plan caches it), then Y = P W (+ b, ReLU)
         const bool cached = p.info.cache == GNN_CACHE_AX;
         float *P = cached ? static_cast<float *>(cache) : ws.take<float>((size_t)n * m);
         void *sp = ws.take<char>(spmm_workspace_bytes(d.nnz, m));
+        void *wt = ws.take<char>(gemm_workspace_bytes(0, 0, n, k, m));
         GNN_TRY(spmm(g, forward_view(g, m), X, m, P, nullptr, 0, sp, st));
-        GNN_TRY(gemm_launch(0, 0, n, k, m, P, W, Y, bias, d.fuse_relu, nullptr, st));
+        GNN_TRY(gemm_launch(0, 0, n, k, m, P, W, Y, bias, d.fuse_relu, wt, st));
         if (cached) p.cache_filled = true;
     }
     return GNN_OK;

@@ -238,6 +238,151 @@ gemm_kernel(int M, int N, long K, const float *__restrict__ A, const float *__re
         }
 }
 
+// ---- fp32: C[M][N] = A[M][K] * Bt[N][K]^T (+ bias, ReLU) --------------------------------
+// Both operands have the reduction index contiguous in memory, so tiles go to LDS as they
+// are ([rows][BK + 4], float4 in, float4 out).  One v_mfma_f32_32x32x2 multiplies a 32 x 2
+// by a 2 x 32 slice; which two reduction indices those are is free as long as both operands
+// agree, so the lower lane half takes k = 0..15 of the tile and the upper half k = 16..31:
+// each lane then reads its 16 operand values of a tile row with four ds_read_b128 and the
+// 16 matrix instructions of the k-tile run back to back.
+template <int WM, int WN, int TM, int TN>
+__global__ void __launch_bounds__(256)
+gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *__restrict__ Bt,
+                float *__restrict__ C, const float *__restrict__ bias, int relu, int tiles_m, int tiles_n,
+                int vec_a, int vec_b) {
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32, LD = BK + 4;
+    constexpr int GA = BM * BK / 4 / 256, GB = BN * BK / 4 / 256;
+    __shared__ __align__(16) float As[BM][LD];
+    __shared__ __align__(16) float Bs[BN][LD];
+
+    const long total = (long)tiles_m * tiles_n;
+    const long per_xcd = (total + 7) / 8;
+    const long logical = (long)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (logical >= total) return;
+    const int m0 = (int)(logical / tiles_n) * BM;
+    const int n0 = (int)(logical % tiles_n) * BN;
+
+    const int t = threadIdx.x;
+    const int wave = t / 64, lane = t % 64;
+    const int wm = wave / WN, wn = wave % WN;
+    const int l32 = lane % 32, half = lane / 32;
+
+    float4 ra[GA], rb[GB];
+    auto load_rows = [&](const float *__restrict__ src, int rows_total, int row0, int vec, int k0, float4 *reg,
+                         int granules) {
+#pragma unroll
+        for (int p = 0; p < granules; ++p) {
+            const int j = t + 256 * p;
+            const int row = j / (BK / 4), kq = (j % (BK / 4)) * 4;
+            const long gr = row0 + row;
+            const int gk = k0 + kq;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (gr < rows_total) {
+                const float *q = src + gr * K + gk;
+                if (vec && gk + 3 < K) v = *reinterpret_cast<const float4 *>(q);
+                else {
+                    if (gk < K) v.x = q[0];
+                    if (gk + 1 < K) v.y = q[1];
+                    if (gk + 2 < K) v.z = q[2];
+                    if (gk + 3 < K) v.w = q[3];
+                }
+            }
+            reg[p] = v;
+        }
+    };
+    auto fetch = [&](int k0) {
+        load_rows(A, M, m0, vec_a, k0, ra, GA);
+        load_rows(Bt, N, n0, vec_b, k0, rb, GB);
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int p = 0; p < GA; ++p) {
+            const int j = t + 256 * p;
+            *reinterpret_cast<float4 *>(&As[j / (BK / 4)][(j % (BK / 4)) * 4]) = ra[p];
+        }
+#pragma unroll
+        for (int p = 0; p < GB; ++p) {
+            const int j = t + 256 * p;
+            *reinterpret_cast<float4 *>(&Bs[j / (BK / 4)][(j % (BK / 4)) * 4]) = rb[p];
+        }
+    };
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    fetch(0);
+    stage();
+    __syncthreads();
+    for (int k0 = 0; k0 < K; k0 += BK) {
+        const bool more = k0 + BK < K;
+        if (more) fetch(k0 + BK);
+        float4 a[TM][4], b[TN][4];
+#pragma unroll
+        for (int x = 0; x < TM; ++x)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                a[x][j] = *reinterpret_cast<const float4 *>(&As[(wm * TM + x) * 32 + l32][half * 16 + 4 * j]);
+#pragma unroll
+        for (int y = 0; y < TN; ++y)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                b[y][j] = *reinterpret_cast<const float4 *>(&Bs[(wn * TN + y) * 32 + l32][half * 16 + 4 * j]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int x = 0; x < TM; ++x)
+#pragma unroll
+                    for (int y = 0; y < TN; ++y) {
+                        const float av = c == 0 ? a[x][j].x : c == 1 ? a[x][j].y : c == 2 ? a[x][j].z : a[x][j].w;
+                        const float bv = c == 0 ? b[y][j].x : c == 1 ? b[y][j].y : c == 2 ? b[y][j].z : b[y][j].w;
+                        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[x][y], 0, 0, 0);
+                    }
+        __syncthreads();
+        if (more) {
+            stage();
+            __syncthreads();
+        }
+    }
+
+    // accumulator register v of lane (half, l32): row 8*(v/4) + 4*half + v%4, column l32 of its tile
+#pragma unroll
+    for (int x = 0; x < TM; ++x)
+#pragma unroll
+        for (int y = 0; y < TN; ++y) {
+            const int gj = n0 + (wn * TN + y) * 32 + l32;
+            if (gj >= N) continue;
+            const float bj = bias ? bias[gj] : 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int gi = m0 + (wm * TM + x) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                if (gi >= M) continue;
+                float o = acc[x][y][v] + bj;
+                if (relu) o = fmaxf(o, 0.f);
+                C[(size_t)gi * N + gj] = o;
+            }
+        }
+}
+
+// out[c][r] = in[r][c] for a small weight matrix (rows x cols), through a 32 x 33 LDS tile.
+__global__ void __launch_bounds__(256)
+transpose_kernel(int rows, int cols, const float *__restrict__ in, float *__restrict__ out) {
+    __shared__ float tile[32][33];
+    const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+    const int tx = threadIdx.x % 32, ty = threadIdx.x / 32;
+    for (int i = ty; i < 32; i += 8)
+        if (r0 + i < rows && c0 + tx < cols) tile[i][tx] = in[(size_t)(r0 + i) * cols + c0 + tx];
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8)
+        if (c0 + i < cols && r0 + tx < rows) out[(size_t)(c0 + i) * rows + r0 + tx] = tile[tx][i];
+}
+
 // C[i] = sum over chunks of part[chunk][i].  A block covers 16 consecutive outputs with
 // 16 chunk lanes each (lane j takes chunks j, j+16, ... into four rotating accumulators);
 // the lanes are then added in lane order, so the association is fixed.
@@ -305,57 +450,67 @@ int pick_splits(int ta, int64_t M, int64_t N, int64_t K) {
 }  // namespace
 
 size_t gemm_workspace_bytes(int ta, int tb, int64_t M, int64_t N, int64_t K) {
-    (void)tb;
-    if (!ta) return kAlign;
+    if (!ta) return tb ? kAlign : align_up((size_t)(N > 0 ? N : 1) * (K > 0 ? K : 1) * sizeof(float));   // B^T
     return align_up((size_t)pick_splits(ta, M, N, K) * M * N * sizeof(double));
 }
 
-#define GEMM_CASE(F64_, TB_, WM_, WN_, TM_, TN_)                                                                  \
-    if (f64 == F64_ && tbb == TB_ && tl.wm == WM_ && tl.wn == WN_ && tl.tm == TM_ && tl.tn == TN_) {              \
-        hipLaunchKernelGGL((gemm_kernel<F64_, TB_, WM_, WN_, TM_, TN_>), grid, dim3(256), 0, st, (int)M, (int)N,  \
-                           (long)K, A, B, out, bias, relu, k_chunk, tiles_m, tiles_n, splits, vec_a, vec_b);      \
-        launched = true;                                                                                          \
+#define GEMM_F32_CASE(WM_, WN_, TM_, TN_)                                                                   \
+    if (tl.wm == WM_ && tl.wn == WN_ && tl.tm == TM_ && tl.tn == TN_) {                                     \
+        hipLaunchKernelGGL((gemm_f32_kernel<WM_, WN_, TM_, TN_>), grid, dim3(256), 0, st, (int)M, (int)N,   \
+                           (int)K, A, Bt, C, bias, relu, tiles_m, tiles_n, vec_a, vec_b);                   \
+        launched = true;                                                                                    \
     }
-#define GEMM_F32_TILINGS(TB_)                                                                                 \
-    GEMM_CASE(false, TB_, 2, 2, 1, 1) GEMM_CASE(false, TB_, 2, 2, 1, 2) GEMM_CASE(false, TB_, 4, 1, 1, 1)     \
-    GEMM_CASE(false, TB_, 4, 1, 1, 2) GEMM_CASE(false, TB_, 2, 2, 2, 2)
+#define GEMM_F64_CASE(WM_, WN_, TM_, TN_)                                                                        \
+    if (tl.wm == WM_ && tl.wn == WN_ && tl.tm == TM_ && tl.tn == TN_) {                                          \
+        hipLaunchKernelGGL((gemm_kernel<true, false, WM_, WN_, TM_, TN_>), grid, dim3(256), 0, st, (int)M,       \
+                           (int)N, (long)K, A, B, workspace, nullptr, 0, k_chunk, tiles_m, tiles_n, splits,      \
+                           vec_a, vec_b);                                                                        \
+        launched = true;                                                                                         \
+    }
 
 gnn_status_t gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A, const float *B,
                          float *C, const float *bias, int relu, void *workspace, hipStream_t st) {
     if (M <= 0 || N <= 0) return GNN_OK;
     if (ta && tb) return GNN_ERR_UNSUPPORTED;
-    if (M > INT32_MAX / 2 || N > INT32_MAX / 2) return GNN_ERR_UNSUPPORTED;
-    const bool f64 = ta != 0, tbb = tb != 0;
+    if (M > INT32_MAX / 2 || N > INT32_MAX / 2 || (!ta && K > INT32_MAX / 2)) return GNN_ERR_UNSUPPORTED;
+    const bool f64 = ta != 0;
     const Tiling tl = pick_tiling(f64, M, N);
     const int tiles_m = (int)ceil_div(M, tile_m(f64, tl)), tiles_n = (int)ceil_div(N, tile_n(f64, tl));
-    int splits = pick_splits(ta, M, N, K);
-    long k_chunk = K;
-    if (f64) {
-        k_chunk = ceil_div(ceil_div(K > 0 ? K : 1, splits), BK) * BK;
-        splits = (int)ceil_div(K > 0 ? K : 1, k_chunk);
-    }
-    void *out = f64 ? workspace : static_cast<void *>(C);
-    // a float4 may be read only if every granule start is 16-byte aligned
-    const int vec_a = aligned16(A) && (ta ? M % 4 == 0 : K % 4 == 0);
-    const int vec_b = aligned16(B) && (tb ? K % 4 == 0 : N % 4 == 0);
-    const long total = (long)tiles_m * tiles_n * splits;
-    dim3 grid((unsigned)(8 * ceil_div(total, 8)));
     bool launched = false;
     if (!f64) {
-        if (!tbb) { GEMM_F32_TILINGS(false) } else { GEMM_F32_TILINGS(true) }
-    } else {
-        GEMM_CASE(true, false, 4, 1, 1, 1) GEMM_CASE(true, false, 4, 1, 1, 2)
-        GEMM_CASE(true, false, 2, 2, 2, 2) GEMM_CASE(true, false, 2, 2, 4, 4)
+        // the kernel wants B with the reduction index contiguous: B[N][K]; transpose a [K][N] weight first
+        const float *Bt = B;
+        if (!tb && K > 0) {
+            float *wt = static_cast<float *>(workspace);
+            hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)ceil_div(N, 32), (unsigned)ceil_div(K, 32)), dim3(256),
+                               0, st, (int)K, (int)N, B, wt);
+            GNN_TRY(launch_status());
+            Bt = wt;
+        }
+        const int vec_a = aligned16(A) && K % 4 == 0;
+        const int vec_b = aligned16(Bt) && K % 4 == 0;
+        const long total = (long)tiles_m * tiles_n;
+        dim3 grid((unsigned)(8 * ceil_div(total, 8)));
+        GEMM_F32_CASE(2, 2, 1, 1) GEMM_F32_CASE(2, 2, 1, 2) GEMM_F32_CASE(4, 1, 1, 1)
+        GEMM_F32_CASE(4, 1, 1, 2) GEMM_F32_CASE(2, 2, 2, 2)
+        if (!launched) return GNN_ERR_UNSUPPORTED;
+        return launch_status();
     }
+    int splits = pick_splits(ta, M, N, K);
+    const long k_chunk = ceil_div(ceil_div(K > 0 ? K : 1, splits), BK) * BK;
+    splits = (int)ceil_div(K > 0 ? K : 1, k_chunk);
+    // a float4 may be read only if every granule start is 16-byte aligned
+    const int vec_a = aligned16(A) && M % 4 == 0;
+    const int vec_b = aligned16(B) && N % 4 == 0;
+    const long total = (long)tiles_m * tiles_n * splits;
+    dim3 grid((unsigned)(8 * ceil_div(total, 8)));
+    GEMM_F64_CASE(4, 1, 1, 1) GEMM_F64_CASE(4, 1, 1, 2) GEMM_F64_CASE(2, 2, 2, 2) GEMM_F64_CASE(2, 2, 4, 4)
     if (!launched) return GNN_ERR_UNSUPPORTED;
     GNN_TRY(launch_status());
-    if (f64) {
-        const long count = (long)M * N;
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)ceil_div(count, 16)), dim3(256), 0, st, count, splits,
-                           static_cast<const double *>(workspace), C);
-        GNN_TRY(launch_status());
-    }
-    return GNN_OK;
+    const long count = (long)M * N;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)ceil_div(count, 16)), dim3(256), 0, st, count, splits,
+                       static_cast<const double *>(workspace), C);
+    return launch_status();
 }
 
 }  // namespace gnn

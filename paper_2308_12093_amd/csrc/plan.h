@@ -18,7 +18,9 @@ using Plan = ::gnn_plan;
 // (size_t)-1 marks a block that does not exist in this variant.
 struct GatLayout {
     size_t c_M, c_s, c_d, c_alpha, c_mask, cache_bytes;
-    size_t w_M, w_s, w_d, w_alpha, w_stat, w_spmm, w_gy, w_ds, w_dd, w_t, w_dM, w_red, w_gemm, workspace_bytes;
+    size_t w_M, w_s, w_d, w_alpha, w_stat, w_walk, w_spmm, w_gemm_nn;          // used by forward (and backward)
+    size_t w_gy, w_sums, w_ds, w_dd, w_spmm_h, w_dM, w_red, w_gemm_tn;         // backward only
+    size_t workspace_bytes;
 };
 
 GatLayout gat_layout(const Plan &p);

@@ -60,7 +60,7 @@ void size_gcn(Plan &p) {
     p.info.cache_bytes = cached ? align_up((size_t)n * m * fl) : 0;
 
     // forward
-    size_t fwd = 0;
+    size_t fwd = gemm_workspace_bytes(0, 0, n, k, m);
     if (tf) {
         fwd += align_up((size_t)n * k * fl) + spmm_workspace_bytes(q, (int)k);
         p.info.transient_fwd = n * k;
@@ -128,16 +128,17 @@ GatLayout gat_layout(const Plan &p) {
     if (L.c_s == (size_t)-1) { L.w_s = take(n * h * fl); L.w_d = take(n * h * fl); }
     if (L.c_alpha == (size_t)-1) L.w_alpha = take(q * h * fl);
     L.w_stat = take(n * h * 2 * fl);
-    L.w_spmm = take(spmm_workspace_bytes(q, (int)f) + spmm_workspace_bytes(q, (int)(2 * h)));
-    const size_t fwd_end = off;
+    L.w_walk = take(gat_walker_workspace_bytes(q, (int)h));
+    L.w_spmm = take(spmm_workspace_bytes(q, (int)f));
+    L.w_gemm_nn = take(gemm_workspace_bytes(0, 0, n, f, m));
     L.w_gy = take(q * h * fl);
+    L.w_sums = take(n * h * 3 * fl);
     L.w_ds = take(n * h * fl);
     L.w_dd = take(n * h * fl);
-    L.w_t = take(n * h * fl);
+    L.w_spmm_h = take(spmm_workspace_bytes(q, (int)h));
     L.w_dM = take(n * f * fl);
     L.w_red = take(colsum_workspace_bytes(n, (int)f));
-    L.w_gemm = take(gemm_workspace_bytes(1, 0, m, f, n));
-    (void)fwd_end;
+    L.w_gemm_tn = take(gemm_workspace_bytes(1, 0, m, f, n));
     L.workspace_bytes = off + kAlign;
     return L;
 }

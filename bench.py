@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--no-input-grad", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also print per-F_out / per-scheme timings to stderr")
+    ap.add_argument("--copy-reference", action="store_true",
+                    help="only run three plain 256 MiB device copies (known bytes, to scale rocprofv3 byte counters)")
     return ap.parse_args()
 
 
@@ -80,6 +82,14 @@ def main():
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    if args.copy_reference:
+        x = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
+        y = torch.empty_like(x)
+        for _ in range(3):
+            y.copy_(x)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_reference": {"bytes_read": x.numel() * 4, "bytes_written": x.numel() * 4, "copies": 3}}))
+        return
     from paper_2308_12093_amd import binding as B, graphs, synth
 
     if args.workload == "cfg1":

@@ -8,15 +8,22 @@
 // Entry-balanced kernel (used when the expanded row index `erow` is given):
 //   the entry list is cut into segments of `seg` consecutive entries; one group
 //   of LPE lanes owns one segment, the lanes of the group spanning the feature
-//   axis (VEC floats per lane and tile).  The group walks its entries U at a
-//   time: it first issues the U index loads and the U dense-row gathers, none
-//   of which depends on where rows begin or end, and only then folds them into
-//   the accumulator, flushing it whenever erow changes.  Rows that lie inside
-//   one segment are written straight to C.  A row cut by a segment boundary
-//   leaves one partial per segment it touches in `part` (slot 2g: the row that
-//   began before segment g; slot 2g+1: the row that continues after it), and a
-//   second kernel adds the partials of each such row in segment order, so the
-//   result does not depend on scheduling.
+//   axis (VEC floats per lane and tile); a 256-thread block owns GPB = 256 / LPE
+//   consecutive segments (its "span").
+//   1. The block copies erow, col and the weights of its span into LDS with
+//      coalesced loads.
+//   2. Each group walks its segment U entries at a time: wide LDS reads for the
+//      indices, then U dense-row gathers issued back to back (they do not depend on
+//      where rows begin or end), then the fold into the accumulator, which is
+//      flushed whenever erow changes.  Rows that lie inside one segment are written
+//      straight to C (bias / ReLU fused).
+//   3. A row cut by a segment boundary leaves a partial in LDS (the row that began
+//      before the segment: "head"; the row that continues after it: "tail").  After
+//      a barrier the group that holds the tail of a row adds the heads of the
+//      following segments of the block, in segment order, and writes the row.
+//   4. Only rows that cross the block's span go to global memory: one head and one
+//      tail partial per block, added in block order by spmm_fixup_kernel.
+//   Every sum has a fixed association, so results are reproducible.
 //
 // Row kernel (no `erow`): one wavefront per row; same results, no balancing.
 #include "common.h"
@@ -28,15 +35,6 @@ __device__ __forceinline__ float epilogue(float x, const float *bias, int c, int
     if (bias) x += bias[c];
     if (relu) x = fmaxf(x, 0.f);
     return x;
-}
-
-template <int VEC>
-__device__ __forceinline__ void store_row(float *dst, const float (&a)[VEC]) {
-    if constexpr (VEC == 4) {
-        *reinterpret_cast<float4 *>(dst) = make_float4(a[0], a[1], a[2], a[3]);
-    } else {
-        dst[0] = a[0];
-    }
 }
 
 template <int N> struct IntVec;
@@ -53,10 +51,14 @@ __device__ __forceinline__ IntVec<N> lds_read(const int32_t *p) {
     return v;
 }
 
-// The block first copies the index data of all its segments (erow, col and the weight
-// or weight slot of span = GPB * seg consecutive entries) into LDS with coalesced
-// loads; the gather loop then takes U entries at a time from LDS with wide reads,
-// so no global index load sits between two batches of dense-row gathers.
+// per-segment bookkeeping kept in LDS for step 3
+struct SegInfo {
+    int32_t tail_row;      // row whose tail partial this segment holds, or -1
+    int32_t has_head;      // the segment's first row began before it
+    int32_t whole;         // ... and also continues after it (the segment is one slice of that row)
+    int32_t active;        // the segment exists
+};
+
 template <int VEC, int LPE, int NT, int U, bool HEADS>
 __global__ void __launch_bounds__(256)
 spmm_seg_kernel(int nnz, int f, int seg, long nseg, const int32_t *__restrict__ erow,
@@ -64,8 +66,13 @@ spmm_seg_kernel(int nnz, int f, int seg, long nseg, const int32_t *__restrict__ 
                 float *__restrict__ C, float *__restrict__ part, const float *__restrict__ bias, int relu) {
     extern __shared__ __align__(16) int32_t smem[];
     constexpr int GPB = 256 / LPE;
+    constexpr int FT = LPE * VEC * NT;                     // features handled by one block (blockIdx.y picks the tile)
     const int span = GPB * seg;
     int32_t *s_row = smem, *s_col = smem + span, *s_w = smem + 2 * span;
+    float *s_head = reinterpret_cast<float *>(smem + 3 * span);          // [GPB][FT]
+    float *s_tail = s_head + GPB * FT;                                  // [GPB][FT]
+    SegInfo *s_info = reinterpret_cast<SegInfo *>(s_tail + GPB * FT);    // [GPB]
+
     const long blk_first = (long)blockIdx.x * span;
     for (int i = threadIdx.x; i < span; i += 256) {
         const long x = blk_first + i;
@@ -82,130 +89,192 @@ spmm_seg_kernel(int nnz, int f, int seg, long nseg, const int32_t *__restrict__ 
     const int l = threadIdx.x % LPE;
     const int gl = threadIdx.x / LPE;                      // group inside the block
     const long g = (long)blockIdx.x * GPB + gl;
-    if (g >= nseg) return;
+    const bool active = g < nseg;
 
-    const int fbase = blockIdx.y * (LPE * VEC * NT);
-    int foff[NT];
+    const int fbase = blockIdx.y * FT;
+    int foff[NT], loff[NT];
     bool fok[NT];
     int head[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        foff[t] = fbase + (t * LPE + l) * VEC;
+        loff[t] = (t * LPE + l) * VEC;                     // offset inside the block's feature tile
+        foff[t] = fbase + loff[t];
         fok[t] = foff[t] < f;
         head[t] = HEADS ? (fok[t] ? foff[t] / w.head_dim : 0) : 0;
     }
-
-    const int lb = gl * seg;                               // first LDS slot of this segment
-    const long s = g * seg;
-    const int cnt = (int)min((long)seg, (long)nnz - s);
-    const int first = s_row[lb];
-    const int before = gl > 0 ? s_row[lb - 1] : (s > 0 ? erow[s - 1] : -1);
-    const bool head_open = before == first;
 
     float acc[NT][VEC];
 #pragma unroll
     for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[t][i] = 0.f;
-    int cur = first;
 
-    auto flush = [&](int row, bool to_head_slot, bool to_tail_slot) {
-        float *dst;
-        bool direct = false;
-        if (to_head_slot) dst = part + (size_t)(2 * g) * f;
-        else if (to_tail_slot) dst = part + (size_t)(2 * g + 1) * f;
-        else { dst = C + (size_t)row * f; direct = true; }
+    auto store_lds = [&](float *dst) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            if constexpr (VEC == 4)
+                *reinterpret_cast<float4 *>(dst + loff[t]) = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
+            else dst[loff[t]] = acc[t][0];
+        }
+    };
+    auto add_lds = [&](const float *src, bool overwrite) {   // acc (+)= src
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            float q[VEC];
+            if constexpr (VEC == 4) {
+                const float4 v = *reinterpret_cast<const float4 *>(src + loff[t]);
+                q[0] = v.x; q[1] = v.y; q[2] = v.z; q[3] = v.w;
+            } else q[0] = src[loff[t]];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[t][i] = overwrite ? q[i] : acc[t][i] + q[i];
+        }
+    };
+    auto store_global = [&](float *dst, bool with_epilogue) {
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             if (!fok[t]) continue;
-            float o[VEC];
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) o[i] = direct ? epilogue(acc[t][i], bias, foff[t] + i, relu) : acc[t][i];
-            store_row<VEC>(dst + foff[t], o);
+            if constexpr (VEC == 4) {
+                float4 o;
+                o.x = with_epilogue ? epilogue(acc[t][0], bias, foff[t] + 0, relu) : acc[t][0];
+                o.y = with_epilogue ? epilogue(acc[t][1], bias, foff[t] + 1, relu) : acc[t][1];
+                o.z = with_epilogue ? epilogue(acc[t][2], bias, foff[t] + 2, relu) : acc[t][2];
+                o.w = with_epilogue ? epilogue(acc[t][3], bias, foff[t] + 3, relu) : acc[t][3];
+                *reinterpret_cast<float4 *>(dst + foff[t]) = o;
+            } else {
+                dst[foff[t]] = with_epilogue ? epilogue(acc[t][0], bias, foff[t], relu) : acc[t][0];
+            }
         }
     };
+    auto clear = [&]() {
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[t][i] = 0.f;
+    };
 
-    auto batch = [&](const int (&r)[U], const int (&c)[U], const int (&wv)[U], int valid) {
-        float v[U][NT];
+    SegInfo info{-1, 0, 0, active ? 1 : 0};
+    if (active) {
+        const int lb = gl * seg;                           // first LDS slot of this segment
+        const long s = g * seg;
+        const int cnt = (int)min((long)seg, (long)nnz - s);
+        const int first = s_row[lb];
+        const int before = gl > 0 ? s_row[lb - 1] : (s > 0 ? erow[s - 1] : -1);
+        const bool head_open = before == first;
+        int cur = first;
+
+        auto batch = [&](const int (&r)[U], const int (&c)[U], const int (&wv)[U], int valid) {
+            float v[U][NT];
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+            for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                if constexpr (HEADS) v[u][t] = w.val[(size_t)wv[u] * w.heads + head[t]];
-                else v[u][t] = __int_as_float(wv[u]);
-            }
-        float b[U][NT][VEC];
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                if (fok[t]) {
-                    const float *src = B + (size_t)c[u] * f + foff[t];
-                    if constexpr (VEC == 4) {
-                        const float4 q = *reinterpret_cast<const float4 *>(src);
-                        b[u][t][0] = q.x; b[u][t][1] = q.y; b[u][t][2] = q.z; b[u][t][3] = q.w;
-                    } else {
-                        b[u][t][0] = *src;
-                    }
-                } else {
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) b[u][t][i] = 0.f;
+                for (int t = 0; t < NT; ++t) {
+                    if constexpr (HEADS) v[u][t] = w.val[(size_t)wv[u] * w.heads + head[t]];
+                    else v[u][t] = __int_as_float(wv[u]);
                 }
-            }
+            float b[U][NT][VEC];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (u < valid) {
-                if (r[u] != cur) {
-                    flush(cur, cur == first && head_open, false);
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    if (fok[t]) {
+                        const float *src = B + (size_t)c[u] * f + foff[t];
+                        if constexpr (VEC == 4) {
+                            const float4 q = *reinterpret_cast<const float4 *>(src);
+                            b[u][t][0] = q.x; b[u][t][1] = q.y; b[u][t][2] = q.z; b[u][t][3] = q.w;
+                        } else {
+                            b[u][t][0] = *src;
+                        }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) b[u][t][i] = 0.f;
+                    }
+                }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (u < valid) {
+                    if (r[u] != cur) {                     // the row `cur` ends here
+                        if (cur == first && head_open) store_lds(s_head + gl * FT);
+                        else store_global(C + (size_t)cur * f, true);
+                        clear();
+                        cur = r[u];
+                    }
 #pragma unroll
                     for (int t = 0; t < NT; ++t)
 #pragma unroll
-                        for (int i = 0; i < VEC; ++i) acc[t][i] = 0.f;
-                    cur = r[u];
+                        for (int i = 0; i < VEC; ++i) acc[t][i] = fmaf(v[u][t], b[u][t][i], acc[t][i]);
                 }
-#pragma unroll
-                for (int t = 0; t < NT; ++t)
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) acc[t][i] = fmaf(v[u][t], b[u][t][i], acc[t][i]);
             }
-        }
-    };
+        };
 
-    int x = 0;
-    for (; x + U <= cnt; x += U) {                         // full batches: wide LDS reads
-        const IntVec<U> vr = lds_read<U>(s_row + lb + x), vc = lds_read<U>(s_col + lb + x),
-                        vw = lds_read<U>(s_w + lb + x);
-        int r[U], c[U], wv[U];
+        int x = 0;
+        for (; x + U <= cnt; x += U) {                     // full batches: wide LDS reads
+            const IntVec<U> vr = lds_read<U>(s_row + lb + x), vc = lds_read<U>(s_col + lb + x),
+                            vw = lds_read<U>(s_w + lb + x);
+            int r[U], c[U], wv[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) { r[u] = vr.get(u); c[u] = vc.get(u); wv[u] = vw.get(u); }
-        batch(r, c, wv, U);
-    }
-    if (x < cnt) {                                         // ragged end of the entry list
-        int r[U], c[U], wv[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int i = lb + min(x + u, cnt - 1);
-            r[u] = s_row[i]; c[u] = s_col[i]; wv[u] = s_w[i];
+            for (int u = 0; u < U; ++u) { r[u] = vr.get(u); c[u] = vc.get(u); wv[u] = vw.get(u); }
+            batch(r, c, wv, U);
         }
-        batch(r, c, wv, cnt - x);
+        if (x < cnt) {                                     // ragged end of the entry list
+            int r[U], c[U], wv[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = lb + min(x + u, cnt - 1);
+                r[u] = s_row[i]; c[u] = s_col[i]; wv[u] = s_w[i];
+            }
+            batch(r, c, wv, cnt - x);
+        }
+        // the last row of the segment
+        const long e = s + cnt;
+        const int after = e >= nnz ? -1 : (gl + 1 < GPB ? s_row[lb + seg] : erow[e]);
+        const bool in_head = cur == first && head_open;
+        info.has_head = head_open ? 1 : 0;
+        if (in_head) {
+            store_lds(s_head + gl * FT);
+            info.whole = after == cur ? 1 : 0;
+        } else if (after == cur) {
+            store_lds(s_tail + gl * FT);
+            info.tail_row = cur;
+        } else {
+            store_global(C + (size_t)cur * f, true);
+        }
     }
-    const long e = s + cnt;
-    const int after = e >= nnz ? -1 : (gl + 1 < GPB ? s_row[lb + seg] : erow[e]);
-    const bool in_head = cur == first && head_open;
-    flush(cur, in_head, !in_head && after == cur);
+    if (l == 0) s_info[gl] = info;
+    __syncthreads();
+    if (!active) return;
+
+    // a row whose tail this segment holds: add the heads of the following segments of the block
+    if (info.tail_row >= 0) {
+        add_lds(s_tail + gl * FT, true);
+        int x = gl + 1;
+        bool open = true;                                  // the row still continues
+        for (; x < GPB && s_info[x].active; ++x) {
+            add_lds(s_head + x * FT, false);
+            if (!s_info[x].whole) { open = false; break; }
+        }
+        if (open) store_global(part + (size_t)(2 * blockIdx.x + 1) * f, false);   // crosses the block's end
+        else store_global(C + (size_t)info.tail_row * f, true);
+    }
+    // the row that began before the block: its slices inside this block, for the second kernel
+    if (gl == 0 && info.has_head) {
+        add_lds(s_head, true);
+        for (int x = 0; s_info[x].whole && x + 1 < GPB && s_info[x + 1].active; ++x)
+            add_lds(s_head + (x + 1) * FT, false);
+        store_global(part + (size_t)(2 * blockIdx.x) * f, false);
+    }
 }
 
-// Second pass of the entry-balanced SpMM, one wavefront per segment g:
-//  (1) if a row starts in segment g and continues past its end, add that row's
-//      partials (slot 2g+1, then slot 2x of every later segment x it reaches) and
+// Second kernel of the entry-balanced SpMM, one wavefront per block span b of the first:
+//  (1) if a row starts in span b and continues past its end, add that row's
+//      partials (slot 2b+1, then slot 2x of every later span x it reaches) and
 //      write the row.  The 64 lanes form 64/LPF slots of LPF lanes; slot s takes the
-//      partials g+1+s, g+1+s+slots, ... into four rotating accumulators, the slots
+//      partials b+1+s, b+1+s+slots, ... into four rotating accumulators, the slots
 //      are then combined by a fixed shuffle tree: a hub row that spans hundreds of
-//      segments is summed in parallel, and always in the same order.
+//      blocks is summed in parallel, and always in the same order.
 //  (2) lane i of wavefront w gives row 64 w + i the epilogue of zero if it is empty.
 template <int VEC>
 __global__ void __launch_bounds__(256)
-spmm_fixup_kernel(int n, int nnz, int f, int seg, long nseg, int lpf, const int32_t *__restrict__ erow,
+spmm_fixup_kernel(int n, int nnz, int f, int span, long nspan, int lpf, const int32_t *__restrict__ erow,
                   const int32_t *__restrict__ rowptr, const float *__restrict__ part, float *__restrict__ C,
                   const float *__restrict__ bias, int relu) {
     const int lane = threadIdx.x % kWave;
@@ -215,14 +284,14 @@ spmm_fixup_kernel(int n, int nnz, int f, int seg, long nseg, int lpf, const int3
     if (row < n && rowptr[row] == rowptr[row + 1])
         for (int c = 0; c < f; ++c) C[(size_t)row * f + c] = epilogue(0.f, bias, c, relu);
 
-    if (g >= nseg) return;
-    const long e = (g + 1) * seg;
-    if (e >= nnz) return;                                  // nothing follows the last segment
+    if (g >= nspan) return;
+    const long e = (g + 1) * span;
+    if (e >= nnz) return;                                  // nothing follows the last span
     const int r = erow[e - 1];
     if (erow[e] != r) return;                              // the boundary falls between two rows
-    const long s = g * seg;
-    if (s > 0 && erow[s - 1] == r) return;                 // the row began earlier: its first segment owns it
-    const long g_end = ((long)rowptr[r + 1] - 1) / seg;
+    const long s = g * span;
+    if (s > 0 && erow[s - 1] == r) return;                 // the row began earlier: its first span owns it
+    const long g_end = ((long)rowptr[r + 1] - 1) / span;
 
     const int fc = f / VEC;                                // VEC-wide chunks of one row
     const int slots = kWave / lpf, slot = lane / lpf, l = lane % lpf;
@@ -306,7 +375,7 @@ Shape pick_shape(int f, bool vec4) {
 
 }  // namespace
 
-// Segment length: as long as possible (fewer partials) while still giving the chip
+// Segment length: as long as possible (fewer row cuts) while still giving the chip
 // about eight wavefronts per SIMD (256 CUs x 4 SIMDs x 8 = 8192 wavefronts), and short
 // enough that the index data of a block's segments fits a 24 KB LDS staging area.
 int spmm_segment_len(int64_t nnz, int f) {
@@ -320,16 +389,23 @@ int spmm_segment_len(int64_t nnz, int f) {
     return p;
 }
 
+// Two partial rows per block of the first kernel.  The block count depends on whether the
+// float4 path can be taken (pointer alignment is only known at launch): size for the larger.
 size_t spmm_workspace_bytes(int64_t nnz, int f) {
     if (nnz <= 0) return kAlign;
-    const int64_t nseg = ceil_div(nnz, spmm_segment_len(nnz, f));
-    return align_up((size_t)(2 * nseg) * (size_t)f * sizeof(float));
+    const int seg = spmm_segment_len(nnz, f);
+    const int64_t span4 = (int64_t)(256 / pick_shape(f, f % 4 == 0).lpe) * seg;
+    const int64_t span1 = (int64_t)(256 / pick_shape(f, false).lpe) * seg;
+    const int64_t span = span4 < span1 ? span4 : span1;
+    return align_up((size_t)(2 * ceil_div(nnz, span)) * (size_t)f * sizeof(float));
 }
 
 #define SPMM_CASE(VEC_, LPE_, NT_, U_)                                                                       \
     if (sh.vec == VEC_ && sh.lpe == LPE_ && sh.nt == NT_) {                                                  \
-        dim3 grid((unsigned)ceil_div(nseg, 256 / LPE_), (unsigned)sh.tiles_y);                               \
-        const size_t lds = (size_t)3 * (256 / LPE_) * seg * sizeof(int32_t);                                 \
+        constexpr int GPB_ = 256 / LPE_;                                                                     \
+        dim3 grid((unsigned)ceil_div(nseg, GPB_), (unsigned)sh.tiles_y);                                     \
+        const size_t lds = (size_t)3 * GPB_ * seg * sizeof(int32_t) +                                        \
+                           (size_t)2 * GPB_ * (LPE_ * VEC_ * NT_) * sizeof(float) + GPB_ * sizeof(SegInfo);  \
         if (heads)                                                                                           \
             hipLaunchKernelGGL((spmm_seg_kernel<VEC_, LPE_, NT_, U_, true>), grid, dim3(256), lds, st, nnz,  \
                                f, seg, nseg, erow, col, w, B, C, part, bias, relu);                          \
@@ -371,16 +447,18 @@ gnn_status_t spmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *c
     if (g_prof_stop) (void)hipEventRecord(g_prof_stop, st);
     GNN_TRY(launch_status());
 
-    // lanes per slot of the second pass: one per VEC-wide chunk of a row, at most a wavefront
-    int lpf = pow2_at_least(f / sh.vec);
+    // second kernel: one wavefront per block span of the first, and per 64 rows for the empty-row fill
+    const int span = (256 / sh.lpe) * seg;
+    const long nspan = ceil_div(nnz, span);
+    int lpf = pow2_at_least(f / sh.vec);                   // lanes per slot: one per VEC-wide chunk of a row
     if (lpf > kWave) lpf = kWave;
-    const long waves = nseg > ceil_div(n, kWave) ? nseg : ceil_div(n, kWave);
+    const long waves = nspan > ceil_div(n, kWave) ? nspan : ceil_div(n, kWave);
     if (sh.vec == 4)
-        hipLaunchKernelGGL(spmm_fixup_kernel<4>, dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, st, n, nnz, f, seg,
-                           nseg, lpf, erow, rowptr, part, C, bias, relu);
+        hipLaunchKernelGGL(spmm_fixup_kernel<4>, dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, st, n, nnz, f, span,
+                           nspan, lpf, erow, rowptr, part, C, bias, relu);
     else
-        hipLaunchKernelGGL(spmm_fixup_kernel<1>, dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, st, n, nnz, f, seg,
-                           nseg, lpf, erow, rowptr, part, C, bias, relu);
+        hipLaunchKernelGGL(spmm_fixup_kernel<1>, dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, st, n, nnz, f, span,
+                           nspan, lpf, erow, rowptr, part, C, bias, relu);
     return launch_status();
 }
 

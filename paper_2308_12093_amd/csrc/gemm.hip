@@ -245,66 +245,112 @@ gemm_kernel(int M, int N, long K, const float *__restrict__ A, const float *__re
 // agree, so the lower lane half takes k = 0..15 of the tile and the upper half k = 16..31:
 // each lane then reads its 16 operand values of a tile row with four ds_read_b128 and the
 // 16 matrix instructions of the k-tile run back to back.
-template <int WM, int WN, int TM, int TN>
+//
+// The layer products are tall and skinny (K is 16..512: a handful of k-tiles per output
+// tile), so prologue and epilogue would dominate a one-tile-per-block kernel.  Blocks are
+// persistent instead: each owns a contiguous range of output tiles and runs one software
+// pipeline over all (tile, k-tile) steps of the range.  LDS is double-buffered; the global
+// loads of step i+1 are issued before the matrix instructions of step i and written to the
+// other buffer after them (one barrier per step), so the first loads of the next output
+// tile are already in flight while the current tile is finished and stored.
+template <int WM, int WN, int TM, int TN, int BKT>
 __global__ void __launch_bounds__(256)
 gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *__restrict__ Bt,
                 float *__restrict__ C, const float *__restrict__ bias, int relu, int tiles_m, int tiles_n,
-                int vec_a, int vec_b) {
-    constexpr int BM = WM * TM * 32, BN = WN * TN * 32, LD = BK + 4;
-    constexpr int GA = BM * BK / 4 / 256, GB = BN * BK / 4 / 256;
-    __shared__ __align__(16) float As[BM][LD];
-    __shared__ __align__(16) float Bs[BN][LD];
+                int tiles_per_block, int vec_a, int vec_b) {
+    constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = BKT, LD = BK + 4;
+    constexpr int RPP = 256 / (BK / 4);                   // tile rows covered by one pass of the 256 threads
+    constexpr int NJ = BK / 8;                            // float4 operand reads per tile row and lane
+    constexpr int GA = (BM + RPP - 1) / RPP, GB = (BN + RPP - 1) / RPP;
+    extern __shared__ __align__(16) float lds[];
+    float (*As)[BM][LD] = reinterpret_cast<float (*)[BM][LD]>(lds);                    // [2][BM][LD]
+    float (*Bs)[BN][LD] = reinterpret_cast<float (*)[BN][LD]>(lds + 2 * BM * LD);      // [2][BN][LD]
 
+    // XCD-aware ownership: block ids are dealt round-robin to the 8 XCDs; give each XCD a
+    // contiguous range of tiles, and each of its blocks a contiguous sub-range
     const long total = (long)tiles_m * tiles_n;
     const long per_xcd = (total + 7) / 8;
-    const long logical = (long)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    if (logical >= total) return;
-    const int m0 = (int)(logical / tiles_n) * BM;
-    const int n0 = (int)(logical % tiles_n) * BN;
+    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    const long xcd_first = xcd * per_xcd;
+    const long xcd_last = min(total, xcd_first + per_xcd);
+    const long first_tile = xcd_first + (long)slot * tiles_per_block;
+    const long last_tile = min(xcd_last, first_tile + tiles_per_block);
+    if (first_tile >= last_tile) return;
 
     const int t = threadIdx.x;
-    const int wave = t / 64, lane = t % 64;
+    const int wave = __builtin_amdgcn_readfirstlane(t / 64), lane = t % 64;   // wave id as a scalar
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane % 32, half = lane / 32;
+    const int ktiles = K > 0 ? (K + BK - 1) / BK : 1;
+    const int lrow = t / (BK / 4), lkq = (t % (BK / 4)) * 4;      // this thread's granule: row (+32 per p), k offset
+    // per-lane parts of the fast-path addresses, in bytes: address = wave-uniform base + 32-bit lane offset
+    const unsigned lane_ld = ((unsigned)lrow * (unsigned)K + lkq) * 4u;
+    const unsigned lane_st = ((unsigned)(4 * half) * (unsigned)N + l32) * 4u;
+    const bool vec = vec_a && vec_b;
 
-    float4 ra[GA], rb[GB];
-    auto load_rows = [&](const float *__restrict__ src, int rows_total, int row0, int vec, int k0, float4 *reg,
-                         int granules) {
+    // the loads of one (tile, k-tile) step.  Fast form: the tile lies inside the matrices and
+    // the k-tile inside K, so every granule is one unguarded float4 at a precomputed address.
+    // Two register sets alternate, so the loads of step i+2 are issued before step i is
+    // multiplied and have two steps of matrix work to arrive.
+    float4 ra0[GA], rb0[GB], ra1[GA], rb1[GB];
+    const float *pa = nullptr, *pb = nullptr;              // uniform bases of the tile being fetched
+    bool full = false;
+    int m0 = 0, n0 = 0;
+    long ftile = first_tile;                               // fetch cursor
+    int fkt = 0;
+    auto fetch = [&](float4 (&ra)[GA], float4 (&rb)[GB]) {
+        if (fkt == 0) {
+            m0 = (int)(ftile / tiles_n) * BM;
+            n0 = (int)(ftile % tiles_n) * BN;
+            full = vec && m0 + BM <= M && n0 + BN <= N && (size_t)(BM > BN ? BM : BN) * K < (1u << 30) &&
+                   (size_t)BM * N < (1u << 30);
+            pa = A + (size_t)m0 * K;
+            pb = Bt + (size_t)n0 * K;
+        }
+        const int k0 = fkt * BK;
+        if (++fkt == ktiles) { fkt = 0; ++ftile; }
+        if (full && k0 + BK <= K) {
 #pragma unroll
-        for (int p = 0; p < granules; ++p) {
-            const int j = t + 256 * p;
-            const int row = j / (BK / 4), kq = (j % (BK / 4)) * 4;
-            const long gr = row0 + row;
-            const int gk = k0 + kq;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (gr < rows_total) {
-                const float *q = src + gr * K + gk;
-                if (vec && gk + 3 < K) v = *reinterpret_cast<const float4 *>(q);
-                else {
-                    if (gk < K) v.x = q[0];
-                    if (gk + 1 < K) v.y = q[1];
-                    if (gk + 2 < K) v.z = q[2];
-                    if (gk + 3 < K) v.w = q[3];
+            for (int p = 0; p < GA; ++p)
+                if (BM % RPP == 0 || lrow + RPP * p < BM)
+                    ra[p] = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(pa + (size_t)p * RPP * K + k0) + lane_ld);
+#pragma unroll
+            for (int p = 0; p < GB; ++p)
+                if (BN % RPP == 0 || lrow + RPP * p < BN)
+                    rb[p] = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(pb + (size_t)p * RPP * K + k0) + lane_ld);
+            return;
+        }
+        auto guarded = [&](const float *__restrict__ src, int rows_total, int row0, int v4, float4 *reg, int granules,
+                           int tile_rows) {
+#pragma unroll
+            for (int p = 0; p < granules; ++p) {
+                if (lrow + RPP * p >= tile_rows) continue;
+                const long gr = row0 + lrow + RPP * p;
+                const int gk = k0 + lkq;
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (gr < rows_total) {
+                    const float *q = src + gr * K + gk;
+                    if (v4 && gk + 3 < K) v = *reinterpret_cast<const float4 *>(q);
+                    else {
+                        if (gk < K) v.x = q[0];
+                        if (gk + 1 < K) v.y = q[1];
+                        if (gk + 2 < K) v.z = q[2];
+                        if (gk + 3 < K) v.w = q[3];
+                    }
                 }
+                reg[p] = v;
             }
-            reg[p] = v;
-        }
+        };
+        guarded(A, M, m0, vec_a, ra, GA, BM);
+        guarded(Bt, N, n0, vec_b, rb, GB, BN);
     };
-    auto fetch = [&](int k0) {
-        load_rows(A, M, m0, vec_a, k0, ra, GA);
-        load_rows(Bt, N, n0, vec_b, k0, rb, GB);
-    };
-    auto stage = [&]() {
+    auto stage = [&](int buf, const float4 (&ra)[GA], const float4 (&rb)[GB]) {
 #pragma unroll
-        for (int p = 0; p < GA; ++p) {
-            const int j = t + 256 * p;
-            *reinterpret_cast<float4 *>(&As[j / (BK / 4)][(j % (BK / 4)) * 4]) = ra[p];
-        }
+        for (int p = 0; p < GA; ++p)
+            if (BM % RPP == 0 || lrow + RPP * p < BM) *reinterpret_cast<float4 *>(&As[buf][lrow + RPP * p][lkq]) = ra[p];
 #pragma unroll
-        for (int p = 0; p < GB; ++p) {
-            const int j = t + 256 * p;
-            *reinterpret_cast<float4 *>(&Bs[j / (BK / 4)][(j % (BK / 4)) * 4]) = rb[p];
-        }
+        for (int p = 0; p < GB; ++p)
+            if (BN % RPP == 0 || lrow + RPP * p < BN) *reinterpret_cast<float4 *>(&Bs[buf][lrow + RPP * p][lkq]) = rb[p];
     };
 
     floatx16 acc[TM][TN];
@@ -315,25 +361,21 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    fetch(0);
-    stage();
-    __syncthreads();
-    for (int k0 = 0; k0 < K; k0 += BK) {
-        const bool more = k0 + BK < K;
-        if (more) fetch(k0 + BK);
-        float4 a[TM][4], b[TN][4];
+    auto multiply = [&](int buf) {
+        if (K <= 0) return;
+        float4 a[TM][NJ], b[TN][NJ];
 #pragma unroll
         for (int x = 0; x < TM; ++x)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                a[x][j] = *reinterpret_cast<const float4 *>(&As[(wm * TM + x) * 32 + l32][half * 16 + 4 * j]);
+            for (int j = 0; j < NJ; ++j)
+                a[x][j] = *reinterpret_cast<const float4 *>(&As[buf][(wm * TM + x) * 32 + l32][half * (BK / 2) + 4 * j]);
 #pragma unroll
         for (int y = 0; y < TN; ++y)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                b[y][j] = *reinterpret_cast<const float4 *>(&Bs[(wn * TN + y) * 32 + l32][half * 16 + 4 * j]);
+            for (int j = 0; j < NJ; ++j)
+                b[y][j] = *reinterpret_cast<const float4 *>(&Bs[buf][(wn * TN + y) * 32 + l32][half * (BK / 2) + 4 * j]);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int c = 0; c < 4; ++c)
 #pragma unroll
@@ -344,30 +386,69 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
                         const float bv = c == 0 ? b[y][j].x : c == 1 ? b[y][j].y : c == 2 ? b[y][j].z : b[y][j].w;
                         acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[x][y], 0, 0, 0);
                     }
-        __syncthreads();
-        if (more) {
-            stage();
-            __syncthreads();
-        }
-    }
+    };
 
-    // accumulator register v of lane (half, l32): row 8*(v/4) + 4*half + v%4, column l32 of its tile
+    // write a finished output tile and clear the accumulators.
+    // Accumulator register v of lane (half, l32): row 8*(v/4) + 4*half + v%4, column l32 of its 32 x 32 tile.
+    auto finish_tile = [&](long tile) {
+        const int cm0 = (int)(tile / tiles_n) * BM, cn0 = (int)(tile % tiles_n) * BN;
+        const bool cfull = cm0 + BM <= M && cn0 + BN <= N && (size_t)BM * N < (1u << 30);
+        if (cfull) {
+            float *c0 = C + (size_t)(cm0 + wm * TM * 32) * N + cn0 + wn * TN * 32;     // uniform per wavefront
 #pragma unroll
-    for (int x = 0; x < TM; ++x)
+            for (int y = 0; y < TN; ++y) {
+                const float bj = bias ? bias[cn0 + (wn * TN + y) * 32 + l32] : 0.f;
 #pragma unroll
-        for (int y = 0; y < TN; ++y) {
-            const int gj = n0 + (wn * TN + y) * 32 + l32;
-            if (gj >= N) continue;
-            const float bj = bias ? bias[gj] : 0.f;
+                for (int x = 0; x < TM; ++x)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int gi = m0 + (wm * TM + x) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-                if (gi >= M) continue;
-                float o = acc[x][y][v] + bj;
-                if (relu) o = fmaxf(o, 0.f);
-                C[(size_t)gi * N + gj] = o;
+                    for (int v = 0; v < 16; ++v) {
+                        float o = acc[x][y][v] + bj;
+                        if (relu) o = fmaxf(o, 0.f);
+                        *reinterpret_cast<float *>(reinterpret_cast<char *>(c0 + (size_t)(x * 32 + 8 * (v / 4) + (v % 4)) * N + y * 32) + lane_st) = o;
+                        acc[x][y][v] = 0.f;
+                    }
             }
+        } else {
+#pragma unroll
+            for (int x = 0; x < TM; ++x)
+#pragma unroll
+                for (int y = 0; y < TN; ++y) {
+                    const int gj = cn0 + (wn * TN + y) * 32 + l32;
+                    const float bj = (bias && gj < N) ? bias[gj] : 0.f;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int gi = cm0 + (wm * TM + x) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+                        if (gj < N && gi < M) {
+                            float o = acc[x][y][v] + bj;
+                            if (relu) o = fmaxf(o, 0.f);
+                            C[(size_t)gi * N + gj] = o;
+                        }
+                        acc[x][y][v] = 0.f;
+                    }
+                }
         }
+    };
+
+    const long steps = (last_tile - first_tile) * ktiles;
+    fetch(ra0, rb0);                                       // step 0
+    stage(0, ra0, rb0);
+    if (steps > 1) fetch(ra0, rb0);                        // step 1 stays in registers for now
+    __syncthreads();
+    for (long step = 0; step < steps; step += 2) {
+        // even step: multiply buffer 0; step+1 is in set 0, fetch step+2 into set 1
+        if (step + 2 < steps) fetch(ra1, rb1);
+        multiply(0);
+        if (step + 1 < steps) stage(1, ra0, rb0);
+        __syncthreads();
+        if ((step + 1) % ktiles == 0) finish_tile(first_tile + step / ktiles);
+        if (step + 1 >= steps) break;
+        // odd step: multiply buffer 1; step+2 is in set 1, fetch step+3 into set 0
+        if (step + 3 < steps) fetch(ra0, rb0);
+        multiply(1);
+        if (step + 2 < steps) stage(0, ra1, rb1);
+        __syncthreads();
+        if ((step + 2) % ktiles == 0) finish_tile(first_tile + (step + 1) / ktiles);
+    }
 }
 
 // out[c][r] = in[r][c] for a small weight matrix (rows x cols), through a 32 x 33 LDS tile.
@@ -456,8 +537,17 @@ size_t gemm_workspace_bytes(int ta, int tb, int64_t M, int64_t N, int64_t K) {
 
 #define GEMM_F32_CASE(WM_, WN_, TM_, TN_)                                                                   \
     if (tl.wm == WM_ && tl.wn == WN_ && tl.tm == TM_ && tl.tn == TN_) {                                     \
-        hipLaunchKernelGGL((gemm_f32_kernel<WM_, WN_, TM_, TN_>), grid, dim3(256), 0, st, (int)M, (int)N,   \
-                           (int)K, A, Bt, C, bias, relu, tiles_m, tiles_n, vec_a, vec_b);                   \
+        if (bk == 16) {                                                                                     \
+            const size_t lds = (size_t)2 * ((WM_ * TM_ + WN_ * TN_) * 32) * (16 + 4) * sizeof(float);       \
+            hipLaunchKernelGGL((gemm_f32_kernel<WM_, WN_, TM_, TN_, 16>), grid, dim3(256), lds, st, (int)M, \
+                               (int)N, (int)K, A, Bt, C, bias, relu, tiles_m, tiles_n, tiles_per_block,     \
+                               vec_a, vec_b);                                                               \
+        } else {                                                                                            \
+            const size_t lds = (size_t)2 * ((WM_ * TM_ + WN_ * TN_) * 32) * (32 + 4) * sizeof(float);       \
+            hipLaunchKernelGGL((gemm_f32_kernel<WM_, WN_, TM_, TN_, 32>), grid, dim3(256), lds, st, (int)M, \
+                               (int)N, (int)K, A, Bt, C, bias, relu, tiles_m, tiles_n, tiles_per_block,     \
+                               vec_a, vec_b);                                                               \
+        }                                                                                                   \
         launched = true;                                                                                    \
     }
 #define GEMM_F64_CASE(WM_, WN_, TM_, TN_)                                                                        \
@@ -489,8 +579,13 @@ gnn_status_t gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const 
         }
         const int vec_a = aligned16(A) && K % 4 == 0;
         const int vec_b = aligned16(Bt) && K % 4 == 0;
+        // persistent blocks: 64 per XCD (2 per CU), each owning a contiguous range of tiles
         const long total = (long)tiles_m * tiles_n;
-        dim3 grid((unsigned)(8 * ceil_div(total, 8)));
+        const long per_xcd = ceil_div(total, 8);
+        const int bk = 32;                                 // k-tile depth (16 was measured slower on every layer shape)
+        const int blocks_per_xcd = (int)(per_xcd < 64 ? per_xcd : 64);
+        const int tiles_per_block = (int)ceil_div(per_xcd, blocks_per_xcd);
+        dim3 grid((unsigned)(8 * blocks_per_xcd));
         GEMM_F32_CASE(2, 2, 1, 1) GEMM_F32_CASE(2, 2, 1, 2) GEMM_F32_CASE(4, 1, 1, 1)
         GEMM_F32_CASE(4, 1, 1, 2) GEMM_F32_CASE(2, 2, 2, 2)
         if (!launched) return GNN_ERR_UNSUPPORTED;

@@ -32,9 +32,11 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg4", "cfg5"])
     ap.add_argument("--scale", type=int, default=None, help="override the R-MAT scale (debug)")
     ap.add_argument("--scheme", default="auto", choices=["auto", "tf_fp", "pf_sp_nocache", "pf_sp_cache"])
+    ap.add_argument("--gat-cache", default="auto", choices=["auto", "none", "feat", "nodeatt", "edge"],
+                    help="cfg4 only: GAT caching variant")
     ap.add_argument("--no-input-grad", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also print per-F_out / per-scheme timings to stderr")
@@ -74,6 +76,54 @@ def spmm_bytes(n, q, f):
     return 12 * q + 8 * n * f
 
 
+def bench_gat(args, torch, B, graphs, synth):
+    """GAT layer workload (R-MAT 2^17 directed, 8 heads x 8, F_in = 256): fwd + bwd of one layer."""
+    w = synth.config4(scale=args.scale or 17)
+    t, h, k, m = w.tensors, w.dims["heads"], w.dims["f_out"], w.dims["f_in"]
+    g = graphs.gat_graph(w.rowptr, w.col, "cuda")
+    n, q, f = g.n, g.nnz, h * k
+    variant = {"auto": B.GNN_CACHE_AUTO, "none": B.GNN_CACHE_NONE, "feat": B.GNN_CACHE_GAT_FEAT,
+               "nodeatt": B.GNN_CACHE_GAT_FEAT_NODEATT, "edge": B.GNN_CACHE_GAT_FEAT_EDGE}[args.gat_cache]
+    need_dx = not args.no_input_grad
+    plan = B.Plan(B.GNN_LAYER_GAT, n, q, m, k, heads=h, need_input_grad=need_dx, has_bias=True, leaky_slope=0.2,
+                  cache=variant)
+    d = {key: torch.from_numpy(v).cuda() for key, v in t.items()}
+    e = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
+    Y, dW, das, dad, db = e(n, f), e(m, f), e(h, k), e(h, k), e(f)
+    dX = e(n, m) if need_dx else None
+    ws = B.alloc(plan.info.workspace_bytes)
+    cache = B.alloc(plan.info.cache_bytes) if plan.info.cache_bytes else None
+
+    def fwd():
+        B.gat_layer_fwd(plan, g, d["X"], d["W"], d["a_src"], d["a_dst"], d["b"], Y, cache, ws)
+
+    def bwd():
+        B.gat_layer_bwd(plan, g, d["X"], d["W"], d["a_src"], d["a_dst"], d["dY"], dW, das, dad, db, dX, cache, ws)
+
+    def timed(fn, reps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / reps
+
+    for _ in range(args.warmup):
+        fwd(); bwd()
+    ms = timed(lambda: (fwd(), bwd()), args.steps)
+    ms_f, ms_b = timed(fwd, args.steps), timed(bwd, args.steps)
+    edge_feat = q * (m + f)
+    out = {"metric": "GAT layer fwd+bwd edge-feat/s", "value": edge_feat / (ms * 1e-3), "unit": "edge*feat/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"{w.name}: R-MAT directed n={n}, nnz={q} (self-loops incl.), F_in={m}, heads={h}, "
+                                  f"F_out={k}, GAT single layer fwd+bwd, cache variant={int(plan.info.cache)}, "
+                                  f"input_grad={need_dx}",
+                      "ms_fwd": ms_f, "ms_bwd": ms_b, "cache_bytes": int(plan.info.cache_bytes)},
+           "roofline": None, "cpu_baseline": None}
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -92,6 +142,8 @@ def main():
         return
     from paper_2308_12093_amd import binding as B, graphs, synth
 
+    if args.workload == "cfg4":
+        return bench_gat(args, torch, B, graphs, synth)
     if args.workload == "cfg1":
         w = synth.config1()
     elif args.workload == "cfg2":

@@ -55,13 +55,32 @@ colsum_partial_kernel(long n, int f, int fp, long rows_per_block, const float *_
     }
 }
 
+// out[c] = sum over blocks of part[block][c].  A block of 256 threads covers 16 columns with
+// 16 lanes each (lane j takes partials j, j+16, ... into four rotating accumulators); the
+// lanes are then added in lane order, so the association is fixed.
 __global__ void __launch_bounds__(256)
 colsum_final_kernel(int f, int blocks, const double *__restrict__ part, float *__restrict__ out) {
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= f) return;
-    double s = 0.0;
-    for (int b = 0; b < blocks; ++b) s += part[(size_t)b * f + c];
-    out[c] = (float)s;
+    __shared__ double red[16][17];
+    const int o = threadIdx.x % 16, sl = threadIdx.x / 16;
+    const int c = blockIdx.x * 16 + o;
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+    if (c < f) {
+        int b = sl;
+        for (; b + 48 < blocks; b += 64) {
+            a0 += part[(size_t)b * f + c];
+            a1 += part[(size_t)(b + 16) * f + c];
+            a2 += part[(size_t)(b + 32) * f + c];
+            a3 += part[(size_t)(b + 48) * f + c];
+        }
+        for (; b < blocks; b += 16) a0 += part[(size_t)b * f + c];
+    }
+    red[sl][o] = (a0 + a1) + (a2 + a3);
+    __syncthreads();
+    if (sl == 0 && c < f) {
+        double t = 0.0;
+        for (int k = 0; k < 16; ++k) t += red[k][o];
+        out[c] = (float)t;
+    }
 }
 
 // One thread per node: stable softmax, loss term, dZ = softmax - onehot.
@@ -131,7 +150,7 @@ static gnn_status_t colsum_weighted(int64_t n, int f, const float *G, const floa
     hipLaunchKernelGGL(colsum_partial_kernel, dim3(blocks), dim3(256), 0, st, (long)n, f, fp, rpb, G, wgt, heads,
                        head_dim, part);
     GNN_TRY(launch_status());
-    hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)ceil_div(f, 256)), dim3(256), 0, st, f, blocks, part, out);
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)ceil_div(f, 16)), dim3(256), 0, st, f, blocks, part, out);
     return launch_status();
 }
 

@@ -89,6 +89,19 @@ struct SumsOp {
     }
 };
 
+struct WalkInfo {
+    int32_t tail_row;      // row whose tail partial this segment holds, or -1
+    int32_t has_head;      // the segment's first row began before it
+    int32_t whole;         // ... and also continues after it
+    int32_t active;        // the segment exists
+};
+
+// One group of HP lanes (lane = head) per segment of `seg` entries, GPB groups per block.
+// Rows inside a segment are written directly; rows cut by a segment boundary inside the
+// block are stitched through LDS after a barrier (the group holding the tail of a row
+// combines the heads of the following segments in order); only rows that cross the block's
+// span leave partials in global memory (slot 2b: began before block b, slot 2b+1: continues
+// after it) for head_fixup_kernel.
 template <class Op, int HP, int U>
 __global__ void __launch_bounds__(256)
 head_walker_kernel(int nnz, int h, int seg, long nseg, const int32_t *__restrict__ erow,
@@ -97,6 +110,9 @@ head_walker_kernel(int nnz, int h, int seg, long nseg, const int32_t *__restrict
     constexpr int GPB = 256 / HP, NA = Op::NACC;
     const int span = GPB * seg;
     int32_t *s_row = smem, *s_col = smem + span;
+    float *s_head = reinterpret_cast<float *>(smem + 2 * span);        // [GPB][HP][NA]
+    float *s_tail = s_head + GPB * HP * NA;
+    WalkInfo *s_info = reinterpret_cast<WalkInfo *>(s_tail + GPB * HP * NA);
     const long blk_first = (long)blockIdx.x * span;
     for (int i = threadIdx.x; i < span; i += 256) {
         const long x = blk_first + i;
@@ -105,81 +121,142 @@ head_walker_kernel(int nnz, int h, int seg, long nseg, const int32_t *__restrict
     __syncthreads();
     const int p = threadIdx.x % HP, gl = threadIdx.x / HP;
     const long g = (long)blockIdx.x * GPB + gl;
-    if (g >= nseg || p >= h) return;
-    const int lb = gl * seg;
-    const long s0 = g * seg;
-    const int cnt = (int)min((long)seg, (long)nnz - s0);
-    const int first = s_row[lb];
-    const int before = gl > 0 ? s_row[lb - 1] : (s0 > 0 ? erow[s0 - 1] : -1);
-    const bool head_open = before == first;
+    const bool active = g < nseg;
+    const bool lane_on = p < h;
     float acc[NA];
     op.init(acc);
-    int cur = first;
-    auto flush = [&](int row, int slot) {             // slot 0: head partial, 1: tail partial, 2: the row itself
-        float *dst = slot == 2 ? out + ((size_t)row * h + p) * NA : part + (((size_t)(2 * g + slot)) * h + p) * NA;
+    float *my_head = s_head + (gl * HP + p) * NA, *my_tail = s_tail + (gl * HP + p) * NA;
+    WalkInfo info{-1, 0, 0, active ? 1 : 0};
+    if (active) {
+        const int lb = gl * seg;
+        const long s0 = g * seg;
+        const int cnt = (int)min((long)seg, (long)nnz - s0);
+        const int first = s_row[lb];
+        const int before = gl > 0 ? s_row[lb - 1] : (s0 > 0 ? erow[s0 - 1] : -1);
+        const bool head_open = before == first;
+        int cur = first;
+        for (int x = 0; x < cnt; x += U) {
+            int r[U], c[U];
+            float v[U][3];
 #pragma unroll
-        for (int a = 0; a < NA; ++a) dst[a] = acc[a];
-    };
-    for (int x = 0; x < cnt; x += U) {
-        int r[U], c[U];
-        float v[U][3];
+            for (int u = 0; u < U; ++u) {
+                const int i = lb + min(x + u, cnt - 1);
+                r[u] = s_row[i];
+                c[u] = s_col[i];
+            }
+            if (lane_on) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int i = lb + min(x + u, cnt - 1);
-            r[u] = s_row[i];
-            c[u] = s_col[i];
-        }
+                for (int u = 0; u < U; ++u) op.load(s0 + min(x + u, cnt - 1), r[u], c[u], h, p, v[u]);
+            }
 #pragma unroll
-        for (int u = 0; u < U; ++u) op.load(s0 + min(x + u, cnt - 1), r[u], c[u], h, p, v[u]);
+            for (int u = 0; u < U; ++u) {
+                if (x + u < cnt) {
+                    if (r[u] != cur) {
+                        if (lane_on) {
+                            float *dst = (cur == first && head_open) ? my_head : out + ((size_t)cur * h + p) * NA;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (x + u < cnt) {
-                if (r[u] != cur) {
-                    flush(cur, (cur == first && head_open) ? 0 : 2);
-                    op.init(acc);
-                    cur = r[u];
+                            for (int a = 0; a < NA; ++a) dst[a] = acc[a];
+                        }
+                        op.init(acc);
+                        cur = r[u];
+                    }
+                    if (lane_on) op.fold(acc, v[u]);
                 }
-                op.fold(acc, v[u]);
             }
         }
+        const long e = s0 + cnt;
+        const int after = e >= nnz ? -1 : (gl + 1 < GPB ? s_row[lb + seg] : erow[e]);
+        const bool in_head = cur == first && head_open;
+        info.has_head = head_open ? 1 : 0;
+        float *dst;
+        if (in_head) { dst = my_head; info.whole = after == cur ? 1 : 0; }
+        else if (after == cur) { dst = my_tail; info.tail_row = cur; }
+        else dst = out + ((size_t)cur * h + p) * NA;
+        if (lane_on) {
+#pragma unroll
+            for (int a = 0; a < NA; ++a) dst[a] = acc[a];
+        }
     }
-    const long e = s0 + cnt;
-    const int after = e >= nnz ? -1 : (gl + 1 < GPB ? s_row[lb + seg] : erow[e]);
-    const bool in_head = cur == first && head_open;
-    flush(cur, in_head ? 0 : (after == cur ? 1 : 2));
+    if (p == 0) s_info[gl] = info;
+    __syncthreads();
+    if (!active || !lane_on) return;
+
+    float b[NA];
+    if (info.tail_row >= 0) {
+#pragma unroll
+        for (int a = 0; a < NA; ++a) acc[a] = my_tail[a];
+        bool open = true;
+        for (int x = gl + 1; x < GPB && s_info[x].active; ++x) {
+#pragma unroll
+            for (int a = 0; a < NA; ++a) b[a] = s_head[(x * HP + p) * NA + a];
+            Op::combine(acc, b);
+            if (!s_info[x].whole) { open = false; break; }
+        }
+        float *dst = open ? part + (((size_t)(2 * blockIdx.x + 1)) * h + p) * NA
+                          : out + ((size_t)info.tail_row * h + p) * NA;
+#pragma unroll
+        for (int a = 0; a < NA; ++a) dst[a] = acc[a];
+    }
+    if (gl == 0 && info.has_head) {
+#pragma unroll
+        for (int a = 0; a < NA; ++a) acc[a] = s_head[p * NA + a];
+        for (int x = 0; s_info[x].whole && x + 1 < GPB && s_info[x + 1].active; ++x) {
+#pragma unroll
+            for (int a = 0; a < NA; ++a) b[a] = s_head[((x + 1) * HP + p) * NA + a];
+            Op::combine(acc, b);
+        }
+        float *dst = part + (((size_t)(2 * blockIdx.x)) * h + p) * NA;
+#pragma unroll
+        for (int a = 0; a < NA; ++a) dst[a] = acc[a];
+    }
 }
 
-// Combines the partials of every row cut by a segment boundary, in segment order;
-// one thread per (segment, head).
-template <class Op>
+// Combines the partials of every row that crosses a block span of the walker, one
+// wavefront per span b: the 64 lanes form 64 / HP slots of HP lanes (lane = head); slot s
+// combines the partials of spans b+1+s, b+1+s+slots, ... in order, the slots are then
+// combined by a fixed shuffle tree, and the result joins the tail partial of span b.
+template <class Op, int HP>
 __global__ void __launch_bounds__(256)
-head_fixup_kernel(int nnz, int h, int seg, long nseg, const int32_t *__restrict__ erow,
+head_fixup_kernel(int nnz, int h, int span, long nspan, const int32_t *__restrict__ erow,
                   const int32_t *__restrict__ rowptr, const float *__restrict__ part, float *__restrict__ out) {
-    constexpr int NA = Op::NACC;
-    const long t = (long)blockIdx.x * 256 + threadIdx.x;
-    const long g = t / h;
-    const int p = (int)(t % h);
-    if (g >= nseg) return;
-    const long e = (g + 1) * seg;
+    constexpr int NA = Op::NACC, SLOTS = kWave / HP;
+    const int lane = threadIdx.x % kWave;
+    const long g = (long)blockIdx.x * 4 + threadIdx.x / kWave;
+    if (g >= nspan) return;
+    const long e = (g + 1) * span;
     if (e >= nnz) return;
     const int r = erow[e - 1];
     if (erow[e] != r) return;
-    const long s0 = g * seg;
+    const long s0 = g * span;
     if (s0 > 0 && erow[s0 - 1] == r) return;
-    const long g_end = ((long)rowptr[r + 1] - 1) / seg;
+    const long g_end = ((long)rowptr[r + 1] - 1) / span;
+    const int p = lane % HP, slot = lane / HP;
+    const bool lane_on = p < h;
+    Op op{};
     float acc[NA], b[NA];
-    const float *src = part + (((size_t)(2 * g + 1)) * h + p) * NA;
+    op.init(acc);
+    if (lane_on)
+        for (long x = g + 1 + slot; x <= g_end; x += SLOTS) {
+            const float *src = part + (((size_t)(2 * x)) * h + p) * NA;
 #pragma unroll
-    for (int a = 0; a < NA; ++a) acc[a] = src[a];
-    for (long x = g + 1; x <= g_end; ++x) {
-        src = part + (((size_t)(2 * x)) * h + p) * NA;
+            for (int a = 0; a < NA; ++a) b[a] = src[a];
+            Op::combine(acc, b);
+        }
+    for (int d = HP; d < kWave; d <<= 1) {
 #pragma unroll
-        for (int a = 0; a < NA; ++a) b[a] = src[a];
+        for (int a = 0; a < NA; ++a) b[a] = __shfl_xor(acc[a], d, kWave);
         Op::combine(acc, b);
     }
-    float *dst = out + ((size_t)r * h + p) * NA;
+    if (lane_on && slot == 0) {
+        const float *src = part + (((size_t)(2 * g + 1)) * h + p) * NA;
+        float t[NA];
 #pragma unroll
-    for (int a = 0; a < NA; ++a) dst[a] = acc[a];
+        for (int a = 0; a < NA; ++a) t[a] = src[a];
+        Op::combine(t, acc);
+        float *dst = out + ((size_t)r * h + p) * NA;
+#pragma unroll
+        for (int a = 0; a < NA; ++a) dst[a] = t[a];
+    }
 }
 
 // ---- entry-parallel kernels, thread t = e * h + p --------------------------------------
@@ -274,17 +351,21 @@ gnn_status_t run_head_walker(int nnz, int h, const int32_t *rowptr, const int32_
     const int seg = gat_segment_len(nnz, h);
     const long nseg = ceil_div(nnz, seg);
     const int gpb = 256 / hp;
-    const size_t lds = (size_t)2 * gpb * seg * sizeof(int32_t);
-    dim3 grid((unsigned)ceil_div(nseg, gpb));
+    const int span = gpb * seg;
+    const long nspan = ceil_div(nnz, span);
+    const size_t lds = (size_t)2 * span * sizeof(int32_t) + (size_t)2 * 256 * Op::NACC * sizeof(float) +
+                       (size_t)gpb * sizeof(WalkInfo);
+    dim3 grid((unsigned)ceil_div(nseg, gpb)), fgrid((unsigned)ceil_div(nspan, 4));
 #define WALK_CASE(HP_)                                                                                            \
-    if (hp == HP_)                                                                                                \
+    if (hp == HP_) {                                                                                              \
         hipLaunchKernelGGL((head_walker_kernel<Op, HP_, 8>), grid, dim3(256), lds, st, nnz, h, seg, nseg, erow,   \
-                           col, op, out, part);
+                           col, op, out, part);                                                                   \
+        GNN_TRY(launch_status());                                                                                 \
+        hipLaunchKernelGGL((head_fixup_kernel<Op, HP_>), fgrid, dim3(256), 0, st, nnz, h, span, nspan, erow,      \
+                           rowptr, part, out);                                                                    \
+    }
     WALK_CASE(1) WALK_CASE(2) WALK_CASE(4) WALK_CASE(8) WALK_CASE(16) WALK_CASE(32) WALK_CASE(64)
 #undef WALK_CASE
-    GNN_TRY(launch_status());
-    hipLaunchKernelGGL(head_fixup_kernel<Op>, dim3((unsigned)ceil_div(nseg * h, 256)), dim3(256), 0, st, nnz, h, seg,
-                       nseg, erow, rowptr, part, out);
     return launch_status();
 }
 
@@ -303,8 +384,8 @@ int gat_segment_len(int64_t nnz, int h) {
 
 size_t gat_walker_workspace_bytes(int64_t nnz, int h) {
     if (nnz <= 0) return kAlign;
-    const int64_t nseg = ceil_div(nnz, gat_segment_len(nnz, h));
-    return align_up((size_t)(2 * nseg) * h * 3 * sizeof(float));
+    const int64_t span = (int64_t)(256 / pow2_at_least(h)) * gat_segment_len(nnz, h);
+    return align_up((size_t)(2 * ceil_div(nnz, span)) * h * 3 * sizeof(float));
 }
 
 gnn_status_t gat_node_attention_launch(int n, int h, int k, const float *M, const float *a_src, const float *a_dst,

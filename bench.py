@@ -54,11 +54,15 @@ class HipEvents:
         self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
         self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
         self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
 
     def create(self):
         e = ctypes.c_void_p()
         assert self.hip.hipEventCreate(ctypes.byref(e)) == 0
         return e
+
+    def record(self, e, stream):
+        assert self.hip.hipEventRecord(e, ctypes.c_void_p(stream)) == 0
 
     def elapsed_ms(self, a, b):
         assert self.hip.hipEventSynchronize(b) == 0
@@ -74,6 +78,26 @@ def spmm_bytes(n, q, f):
     once (4 n f) and the result written once (4 n f).  Re-reads of dense rows
     that miss the caches are not counted: they are what a better kernel avoids."""
     return 12 * q + 8 * n * f
+
+
+def measured_traffic(workload, launch_widths):
+    """HBM-side bytes per SpMM launch from the committed rocprofv3 counter summary, or None.
+
+    The summary holds FETCH_SIZE and WRITE_SIZE of the kernel, scaled by a plain copy of
+    known size, for the default workload only; the figure is the average over the
+    launches of one step, weighted like `achieved`."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "spmm_cfg2_hbm_traffic.txt")
+    if not workload.startswith("cfg2-rmat17") or not os.path.exists(path):
+        return None
+    per_width = {}
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch"):
+            for item in line.split()[1:]:
+                f, b = item.split("=")
+                per_width[int(f[1:])] = int(b)
+    if any(f not in per_width for f in launch_widths):
+        return None
+    return round(sum(per_width[f] for f in launch_widths) / len(launch_widths))
 
 
 def bench_gat(args, torch, B, graphs, synth):
@@ -204,7 +228,7 @@ def main():
     # ---- per-kernel timing of the dominant kernel: the entry-balanced SpMM ----
     ev = HipEvents()
     e0, e1 = ev.create(), ev.create()
-    B.gnn_profile_spmm_events(e0, e1)
+    stream = torch.cuda.current_stream().cuda_stream          # the stream the binding launches on
     launch_widths = []                       # dense width of every SpMM launch of one step
     for L in layers:
         info = L["plan"].info
@@ -222,10 +246,14 @@ def main():
         C = torch.empty((n, f), dtype=torch.float32, device=dev)
         ws = B.alloc(B.gnn_spmm_workspace_bytes(n, q, f))
         times = []
-        for it in range(5 + max(10, args.steps)):
-            B.gnn_spmm_csr(n, q, g.rowptr, g.col, g.val, g.erow, Bm, f, C, None, False, ws)
-            ms = ev.elapsed_ms(e0, e1)
-            if it >= 5:
+        batch = 20                               # launches between the two events: back to back, as inside a step
+        for it in range(2 + 10):
+            ev.record(e0, stream)
+            for _ in range(batch):
+                B.gnn_spmm_csr(n, q, g.rowptr, g.col, g.val, g.erow, Bm, f, C, None, False, ws)
+            ev.record(e1, stream)
+            ms = ev.elapsed_ms(e0, e1) / batch
+            if it >= 2:
                 times.append(ms)
         avg = float(np.mean(times))
         per_width[f] = dict(avg_ms=avg, min_ms=float(np.min(times)), bytes=spmm_bytes(n, q, f),
@@ -236,10 +264,10 @@ def main():
         tot_bytes += cnt * spmm_bytes(n, q, f)
         tot_ms += cnt * avg
         launches += cnt
-    B.gnn_profile_spmm_events(None, None)
     achieved = tot_bytes / tot_ms / 1e6          # GB/s over all SpMM launches of one step
     roofline = {"bound": "hbm", "kernel": "spmm_seg_kernel", "achieved": round(achieved, 1), "peak": 8000.0,
-                "unit": "GB/s", "frac": round(achieved / 8000.0, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / 8000.0, 4),
+                "traffic": measured_traffic(w.name, launch_widths),
                 "launches_per_step": launches,
                 "bytes_per_launch": {str(f): per_width[f]["bytes"] for f in widths},
                 "avg_ms_per_launch": {str(f): round(per_width[f]["avg_ms"], 5) for f in widths},

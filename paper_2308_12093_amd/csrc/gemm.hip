@@ -31,6 +31,7 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef double doublex4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));   // a native vector: loads and stores stay typed
 
 constexpr int BK = 32;
 
@@ -45,7 +46,9 @@ gemm_kernel(int M, int N, long K, const float *__restrict__ A, const float *__re
     constexpr int UNIT = F64 ? 16 : 32;                 // edge of one matrix-instruction tile
     constexpr int KSTEP = F64 ? 4 : 2;                  // reduction depth of one instruction
     constexpr int BM = WM * TM * UNIT, BN = WN * TN * UNIT;
-    constexpr int PA = TA ? 4 : 1, PB = TB ? 1 : 4;
+    // row padding: the four k-rows read by one fp64 matrix instruction (16 consecutive words each) must
+    // fall into four different groups of 16 LDS banks: row length = 16 mod 64 words
+    constexpr int PA = TA ? (F64 ? (80 - BM % 64) % 64 : 4) : 1, PB = TB ? 1 : (F64 ? (80 - BN % 64) % 64 : 4);
     constexpr int NA = BM * BK / 4, NB = BN * BK / 4;   // float4 granules per tile
     constexpr int GA = (NA + 255) / 256, GB = (NB + 255) / 256;
     __shared__ float As[BK][BM + PA];
@@ -189,22 +192,36 @@ gemm_kernel(int M, int N, long K, const float *__restrict__ A, const float *__re
         for (long k0 = kbeg; k0 < kend; k0 += BK) {
             const bool more = k0 + BK < kend;
             if (more) fetch(k0 + BK);
+            // operands of k-step s+1 are read (and widened) before the matrix instructions of step s
+            float a[2][TM], b[2][TN];
+            auto read = [&](int kk, float (&av)[TM], float (&bv)[TN]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int kk = 0; kk < BK; kk += KSTEP) {
-                float a[TM], b[TN];
+                for (int x = 0; x < TM; ++x) av[x] = As[kk + lk][(wm * TM + x) * UNIT + lu];
 #pragma unroll
-                for (int x = 0; x < TM; ++x) a[x] = As[kk + lk][(wm * TM + x) * UNIT + lu];
-#pragma unroll
-                for (int y = 0; y < TN; ++y) b[y] = Bs[kk + lk][(wn * TN + y) * UNIT + lu];
+                for (int y = 0; y < TN; ++y) bv[y] = Bs[kk + lk][(wn * TN + y) * UNIT + lu];
+            };
+            auto mma = [&](const float (&av)[TM], const float (&bv)[TN]) __attribute__((always_inline)) {
 #pragma unroll
                 for (int x = 0; x < TM; ++x)
 #pragma unroll
                     for (int y = 0; y < TN; ++y) {
                         if constexpr (F64)
-                            acc[x][y] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a[x], (double)b[y], acc[x][y], 0, 0, 0);
+                            acc[x][y] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)av[x], (double)bv[y], acc[x][y], 0, 0, 0);
                         else
-                            acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[x], b[y], acc[x][y], 0, 0, 0);
+                            acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[x], bv[y], acc[x][y], 0, 0, 0);
                     }
+            };
+            read(0, a[0], b[0]);
+#pragma unroll
+            for (int s2 = 0; s2 < BK / KSTEP; s2 += 2) {
+                read((s2 + 1) * KSTEP, a[1], b[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                mma(a[0], b[0]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (s2 + 2 < BK / KSTEP) read((s2 + 2) * KSTEP, a[0], b[0]);
+                __builtin_amdgcn_sched_barrier(0);
+                mma(a[1], b[1]);
+                __builtin_amdgcn_sched_barrier(0);
             }
             __syncthreads();
             if (more) {
@@ -243,24 +260,29 @@ gemm_kernel(int M, int N, long K, const float *__restrict__ A, const float *__re
 // are ([rows][BK + 4], float4 in, float4 out).  One v_mfma_f32_32x32x2 multiplies a 32 x 2
 // by a 2 x 32 slice; which two reduction indices those are is free as long as both operands
 // agree, so the lower lane half takes k = 0..15 of the tile and the upper half k = 16..31:
-// each lane then reads its 16 operand values of a tile row with four ds_read_b128 and the
-// 16 matrix instructions of the k-tile run back to back.
+// each lane then reads its 16 operand values of a tile row with four ds_read_b128.
 //
 // The layer products are tall and skinny (K is 16..512: a handful of k-tiles per output
 // tile), so prologue and epilogue would dominate a one-tile-per-block kernel.  Blocks are
 // persistent instead: each owns a contiguous range of output tiles and runs one software
 // pipeline over all (tile, k-tile) steps of the range.  LDS is double-buffered; the global
-// loads of step i+1 are issued before the matrix instructions of step i and written to the
-// other buffer after them (one barrier per step), so the first loads of the next output
-// tile are already in flight while the current tile is finished and stored.
-template <int WM, int WN, int TM, int TN, int BKT>
+// loads of step i+2 are issued before the matrix instructions of step i and written to LDS
+// after those of step i+1 (one barrier per step), so the loads of the next output tile are
+// in flight while the current tile is finished and stored.
+//
+// FAST: every tile is full, K is a multiple of the k-tile and all rows are 16-byte aligned.
+// The step loop then has no branch around a load: the fetch cursor stops at the last step
+// instead of being switched off (the last k-tile is simply read again), which lets the
+// compiler count outstanding loads exactly and wait only for the older of the two register
+// sets.  The general form guards every access and takes whatever waits that needs.
+template <int WM, int WN, int TM, int TN, int BKT, bool FAST>
 __global__ void __launch_bounds__(256)
 gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *__restrict__ Bt,
                 float *__restrict__ C, const float *__restrict__ bias, int relu, int tiles_m, int tiles_n,
                 int tiles_per_block, int vec_a, int vec_b) {
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = BKT, LD = BK + 4;
     constexpr int RPP = 256 / (BK / 4);                   // tile rows covered by one pass of the 256 threads
-    constexpr int NJ = BK / 8;                            // float4 operand reads per tile row and lane
+    constexpr int NJ = BK / 8;                            // 16-byte operand reads per tile row and lane
     constexpr int GA = (BM + RPP - 1) / RPP, GB = (BN + RPP - 1) / RPP;
     extern __shared__ __align__(16) float lds[];
     float (*As)[BM][LD] = reinterpret_cast<float (*)[BM][LD]>(lds);                    // [2][BM][LD]
@@ -268,13 +290,13 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
 
     // XCD-aware ownership: block ids are dealt round-robin to the 8 XCDs; give each XCD a
     // contiguous range of tiles, and each of its blocks a contiguous sub-range
-    const long total = (long)tiles_m * tiles_n;
-    const long per_xcd = (total + 7) / 8;
+    const int total = tiles_m * tiles_n;
+    const int per_xcd = (total + 7) / 8;
     const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
-    const long xcd_first = xcd * per_xcd;
-    const long xcd_last = min(total, xcd_first + per_xcd);
-    const long first_tile = xcd_first + (long)slot * tiles_per_block;
-    const long last_tile = min(xcd_last, first_tile + tiles_per_block);
+    const int xcd_first = xcd * per_xcd;
+    const int xcd_last = min(total, xcd_first + per_xcd);
+    const int first_tile = xcd_first + slot * tiles_per_block;
+    const int last_tile = min(xcd_last, first_tile + tiles_per_block);
     if (first_tile >= last_tile) return;
 
     const int t = threadIdx.x;
@@ -282,75 +304,85 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane % 32, half = lane / 32;
     const int ktiles = K > 0 ? (K + BK - 1) / BK : 1;
-    const int lrow = t / (BK / 4), lkq = (t % (BK / 4)) * 4;      // this thread's granule: row (+32 per p), k offset
-    // per-lane parts of the fast-path addresses, in bytes: address = wave-uniform base + 32-bit lane offset
+    const int steps = (last_tile - first_tile) * ktiles;
+    const int lrow = t / (BK / 4), lkq = (t % (BK / 4)) * 4;      // this thread's granule: row (+RPP per p), k offset
+    // per-lane parts of the fast addresses, in bytes: address = wave-uniform base + 32-bit lane offset
     const unsigned lane_ld = ((unsigned)lrow * (unsigned)K + lkq) * 4u;
     const unsigned lane_st = ((unsigned)(4 * half) * (unsigned)N + l32) * 4u;
-    const bool vec = vec_a && vec_b;
 
-    // the loads of one (tile, k-tile) step.  Fast form: the tile lies inside the matrices and
-    // the k-tile inside K, so every granule is one unguarded float4 at a precomputed address.
+    // the loads of one (tile, k-tile) step, at a cursor that walks the block's steps in order.
     // Two register sets alternate, so the loads of step i+2 are issued before step i is
     // multiplied and have two steps of matrix work to arrive.
-    float4 ra0[GA], rb0[GB], ra1[GA], rb1[GB];
-    const float *pa = nullptr, *pb = nullptr;              // uniform bases of the tile being fetched
-    bool full = false;
-    int m0 = 0, n0 = 0;
-    long ftile = first_tile;                               // fetch cursor
-    int fkt = 0;
-    auto fetch = [&](float4 (&ra)[GA], float4 (&rb)[GB]) {
-        if (fkt == 0) {
-            m0 = (int)(ftile / tiles_n) * BM;
-            n0 = (int)(ftile % tiles_n) * BN;
-            full = vec && m0 + BM <= M && n0 + BN <= N && (size_t)(BM > BN ? BM : BN) * K < (1u << 30) &&
-                   (size_t)BM * N < (1u << 30);
-            pa = A + (size_t)m0 * K;
-            pb = Bt + (size_t)n0 * K;
+    floatx4 ra0[GA], rb0[GB], ra1[GA], rb1[GB];
+    int ftm = first_tile / tiles_n, ftn = first_tile % tiles_n, fkt = 0, fstep = 0;
+    auto guarded = [&](const float *__restrict__ src, int rows_total, int row0, int k0, int v4, floatx4 *reg,
+                       int granules, int tile_rows) __attribute__((always_inline)) {
+#pragma unroll
+        for (int p = 0; p < granules; ++p) {
+            if (lrow + RPP * p >= tile_rows) continue;
+            const long gr = row0 + lrow + RPP * p;
+            const int gk = k0 + lkq;
+            floatx4 v = {0.f, 0.f, 0.f, 0.f};
+            if (gr < rows_total) {
+                const float *q = src + gr * K + gk;
+                if (v4 && gk + 3 < K) v = *reinterpret_cast<const floatx4 *>(q);
+                else {
+                    if (gk < K) v.x = q[0];
+                    if (gk + 1 < K) v.y = q[1];
+                    if (gk + 2 < K) v.z = q[2];
+                    if (gk + 3 < K) v.w = q[3];
+                }
+            }
+            reg[p] = v;
         }
-        const int k0 = fkt * BK;
-        if (++fkt == ktiles) { fkt = 0; ++ftile; }
-        if (full && k0 + BK <= K) {
+    };
+    auto fetch = [&](floatx4 (&ra)[GA], floatx4 (&rb)[GB]) __attribute__((always_inline)) {
+        const int m0 = ftm * BM, n0 = ftn * BN, k0 = fkt * BK;
+        const float *pa = A + (size_t)m0 * K + k0;         // uniform bases of the tile being fetched
+        const float *pb = Bt + (size_t)n0 * K + k0;
+        if constexpr (FAST) {
 #pragma unroll
             for (int p = 0; p < GA; ++p)
                 if (BM % RPP == 0 || lrow + RPP * p < BM)
-                    ra[p] = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(pa + (size_t)p * RPP * K + k0) + lane_ld);
+                    ra[p] = *reinterpret_cast<const floatx4 *>(reinterpret_cast<const char *>(pa + (size_t)p * RPP * K) + lane_ld);
 #pragma unroll
             for (int p = 0; p < GB; ++p)
                 if (BN % RPP == 0 || lrow + RPP * p < BN)
-                    rb[p] = *reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(pb + (size_t)p * RPP * K + k0) + lane_ld);
-            return;
-        }
-        auto guarded = [&](const float *__restrict__ src, int rows_total, int row0, int v4, float4 *reg, int granules,
-                           int tile_rows) {
+                    rb[p] = *reinterpret_cast<const floatx4 *>(reinterpret_cast<const char *>(pb + (size_t)p * RPP * K) + lane_ld);
+        } else {
+            const bool kfull = k0 + BK <= K;
+            if (kfull && vec_a && m0 + BM <= M && (size_t)BM * K < (1u << 30)) {
 #pragma unroll
-            for (int p = 0; p < granules; ++p) {
-                if (lrow + RPP * p >= tile_rows) continue;
-                const long gr = row0 + lrow + RPP * p;
-                const int gk = k0 + lkq;
-                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (gr < rows_total) {
-                    const float *q = src + gr * K + gk;
-                    if (v4 && gk + 3 < K) v = *reinterpret_cast<const float4 *>(q);
-                    else {
-                        if (gk < K) v.x = q[0];
-                        if (gk + 1 < K) v.y = q[1];
-                        if (gk + 2 < K) v.z = q[2];
-                        if (gk + 3 < K) v.w = q[3];
-                    }
-                }
-                reg[p] = v;
+                for (int p = 0; p < GA; ++p)
+                    if (BM % RPP == 0 || lrow + RPP * p < BM)
+                        ra[p] = *reinterpret_cast<const floatx4 *>(reinterpret_cast<const char *>(pa + (size_t)p * RPP * K) + lane_ld);
+            } else {
+                guarded(A, M, m0, k0, vec_a, ra, GA, BM);
             }
-        };
-        guarded(A, M, m0, vec_a, ra, GA, BM);
-        guarded(Bt, N, n0, vec_b, rb, GB, BN);
+            if (kfull && vec_b && n0 + BN <= N && (size_t)BN * K < (1u << 30)) {
+#pragma unroll
+                for (int p = 0; p < GB; ++p)
+                    if (BN % RPP == 0 || lrow + RPP * p < BN)
+                        rb[p] = *reinterpret_cast<const floatx4 *>(reinterpret_cast<const char *>(pb + (size_t)p * RPP * K) + lane_ld);
+            } else {
+                guarded(Bt, N, n0, k0, vec_b, rb, GB, BN);
+            }
+        }
+        if (fstep + 1 < steps) {                           // the cursor stops at the last step
+            ++fstep;
+            if (++fkt == ktiles) {
+                fkt = 0;
+                if (++ftn == tiles_n) { ftn = 0; ++ftm; }
+            }
+        }
     };
-    auto stage = [&](int buf, const float4 (&ra)[GA], const float4 (&rb)[GB]) {
+    auto stage = [&](int buf, const floatx4 (&ra)[GA], const floatx4 (&rb)[GB]) __attribute__((always_inline)) {
 #pragma unroll
         for (int p = 0; p < GA; ++p)
-            if (BM % RPP == 0 || lrow + RPP * p < BM) *reinterpret_cast<float4 *>(&As[buf][lrow + RPP * p][lkq]) = ra[p];
+            if (BM % RPP == 0 || lrow + RPP * p < BM) *reinterpret_cast<floatx4 *>(&As[buf][lrow + RPP * p][lkq]) = ra[p];
 #pragma unroll
         for (int p = 0; p < GB; ++p)
-            if (BN % RPP == 0 || lrow + RPP * p < BN) *reinterpret_cast<float4 *>(&Bs[buf][lrow + RPP * p][lkq]) = rb[p];
+            if (BN % RPP == 0 || lrow + RPP * p < BN) *reinterpret_cast<floatx4 *>(&Bs[buf][lrow + RPP * p][lkq]) = rb[p];
     };
 
     floatx16 acc[TM][TN];
@@ -361,52 +393,93 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    auto multiply = [&](int buf) {
-        if (K <= 0) return;
-        float4 a[TM][NJ], b[TN][NJ];
+    // one k-tile in four quarters of eight reduction indices (four per lane half): the operand
+    // reads of quarter j+1 are issued before the matrix instructions of quarter j (the scheduling
+    // barriers keep that order), so LDS latency hides behind them
+    static_assert(NJ == 4, "the quarter pipeline below is written for a k-tile of 32");
+    auto read = [&](int buf, int j, floatx4 (&a)[TM], floatx4 (&b)[TN]) __attribute__((always_inline)) {
 #pragma unroll
         for (int x = 0; x < TM; ++x)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-                a[x][j] = *reinterpret_cast<const float4 *>(&As[buf][(wm * TM + x) * 32 + l32][half * (BK / 2) + 4 * j]);
+            a[x] = *reinterpret_cast<const floatx4 *>(&As[buf][(wm * TM + x) * 32 + l32][half * (BK / 2) + 4 * j]);
 #pragma unroll
         for (int y = 0; y < TN; ++y)
+            b[y] = *reinterpret_cast<const floatx4 *>(&Bs[buf][(wn * TN + y) * 32 + l32][half * (BK / 2) + 4 * j]);
+    };
+    auto quarter = [&](const floatx4 (&a)[TM], const floatx4 (&b)[TN]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int j = 0; j < NJ; ++j)
-                b[y][j] = *reinterpret_cast<const float4 *>(&Bs[buf][(wn * TN + y) * 32 + l32][half * (BK / 2) + 4 * j]);
+        for (int c = 0; c < 4; ++c)
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
+            for (int x = 0; x < TM; ++x)
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-#pragma unroll
-                for (int x = 0; x < TM; ++x)
-#pragma unroll
-                    for (int y = 0; y < TN; ++y) {
-                        const float av = c == 0 ? a[x][j].x : c == 1 ? a[x][j].y : c == 2 ? a[x][j].z : a[x][j].w;
-                        const float bv = c == 0 ? b[y][j].x : c == 1 ? b[y][j].y : c == 2 ? b[y][j].z : b[y][j].w;
-                        acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[x][y], 0, 0, 0);
-                    }
+                for (int y = 0; y < TN; ++y) {
+                    const float av = c == 0 ? a[x].x : c == 1 ? a[x].y : c == 2 ? a[x].z : a[x].w;
+                    const float bv = c == 0 ? b[y].x : c == 1 ? b[y].y : c == 2 ? b[y].z : b[y].w;
+                    acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[x][y], 0, 0, 0);
+                }
+    };
+    auto multiply = [&](int buf) __attribute__((always_inline)) {
+        if (K <= 0) return;
+        floatx4 a0[TM], b0[TN], a1[TM], b1[TN];
+        read(buf, 0, a0, b0);
+        read(buf, 1, a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        quarter(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        read(buf, 2, a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        quarter(a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        read(buf, 3, a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+        quarter(a0, b0);
+        __builtin_amdgcn_sched_barrier(0);
+        quarter(a1, b1);
     };
 
     // write a finished output tile and clear the accumulators.
     // Accumulator register v of lane (half, l32): row 8*(v/4) + 4*half + v%4, column l32 of its 32 x 32 tile.
-    auto finish_tile = [&](long tile) {
-        const int cm0 = (int)(tile / tiles_n) * BM, cn0 = (int)(tile % tiles_n) * BN;
-        const bool cfull = cm0 + BM <= M && cn0 + BN <= N && (size_t)BM * N < (1u << 30);
+    int ctm = ftm, ctn = ftn, ckt = 0;                     // compute cursor
+    // FAST: the bias of the tile being multiplied is (re)loaded at every step, ahead of that step's
+    // operand loads and without a branch, so it has arrived by the time the step's LDS writes have
+    // waited for the older register set: storing a finished tile then waits for no load at all.
+    // (Without a bias any readable address serves; the value is discarded.)
+    float bcol[TN];
+    const float *bias_src = bias ? bias : Bt;
+    auto load_bias = [&]() __attribute__((always_inline)) {
+        if constexpr (FAST) {
+#pragma unroll
+            for (int y = 0; y < TN; ++y) bcol[y] = bias_src[ctn * BN + (wn * TN + y) * 32 + l32];
+        }
+    };
+    auto finish_tile = [&]() __attribute__((always_inline)) {
+        const int cm0 = ctm * BM, cn0 = ctn * BN;
+        const bool cfull = FAST || (cm0 + BM <= M && cn0 + BN <= N && (size_t)BM * N < (1u << 30));
         if (cfull) {
             float *c0 = C + (size_t)(cm0 + wm * TM * 32) * N + cn0 + wn * TN * 32;     // uniform per wavefront
+            auto put = [&](int x, int y, int v, float o) __attribute__((always_inline)) {
+                *reinterpret_cast<float *>(reinterpret_cast<char *>(c0 + (size_t)(x * 32 + 8 * (v / 4) + (v % 4)) * N + y * 32) + lane_st) = o;
+                acc[x][y][v] = 0.f;
+            };
+            if (!bias && !relu) {
 #pragma unroll
-            for (int y = 0; y < TN; ++y) {
-                const float bj = bias ? bias[cn0 + (wn * TN + y) * 32 + l32] : 0.f;
+                for (int y = 0; y < TN; ++y)
 #pragma unroll
-                for (int x = 0; x < TM; ++x)
+                    for (int x = 0; x < TM; ++x)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        float o = acc[x][y][v] + bj;
-                        if (relu) o = fmaxf(o, 0.f);
-                        *reinterpret_cast<float *>(reinterpret_cast<char *>(c0 + (size_t)(x * 32 + 8 * (v / 4) + (v % 4)) * N + y * 32) + lane_st) = o;
-                        acc[x][y][v] = 0.f;
-                    }
+                        for (int v = 0; v < 16; ++v) put(x, y, v, acc[x][y][v]);
+            } else {
+#pragma unroll
+                for (int y = 0; y < TN; ++y) {
+                    const float bj = FAST ? (bias ? bcol[y] : 0.f) : (bias ? bias[cn0 + (wn * TN + y) * 32 + l32] : 0.f);
+#pragma unroll
+                    for (int x = 0; x < TM; ++x)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            float o = acc[x][y][v] + bj;
+                            if (relu) o = fmaxf(o, 0.f);
+                            put(x, y, v, o);
+                        }
+                }
             }
         } else {
 #pragma unroll
@@ -427,27 +500,34 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
                     }
                 }
         }
+        if (++ctn == tiles_n) { ctn = 0; ++ctm; }
+    };
+    auto after_multiply = [&]() __attribute__((always_inline)) {
+        if (++ckt == ktiles) { ckt = 0; finish_tile(); }
     };
 
-    const long steps = (last_tile - first_tile) * ktiles;
-    fetch(ra0, rb0);                                       // step 0
-    stage(0, ra0, rb0);
-    if (steps > 1) fetch(ra0, rb0);                        // step 1 stays in registers for now
-    __syncthreads();
-    for (long step = 0; step < steps; step += 2) {
+    // The pipeline fills inside the loop (two idle passes, steps -2 and -1, that only load and
+    // stage), so the loop is entered with no load in flight and every pass sees the same state.
+#pragma unroll
+    for (int p = 0; p < GA; ++p) ra0[p] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int p = 0; p < GB; ++p) rb0[p] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int step = -2; step < steps; step += 2) {
         // even step: multiply buffer 0; step+1 is in set 0, fetch step+2 into set 1
-        if (step + 2 < steps) fetch(ra1, rb1);
-        multiply(0);
-        if (step + 1 < steps) stage(1, ra0, rb0);
+        load_bias();
+        fetch(ra1, rb1);
+        if (step >= 0) multiply(0);
+        stage(1, ra0, rb0);
         __syncthreads();
-        if ((step + 1) % ktiles == 0) finish_tile(first_tile + step / ktiles);
+        if (step >= 0) after_multiply();
         if (step + 1 >= steps) break;
         // odd step: multiply buffer 1; step+2 is in set 1, fetch step+3 into set 0
-        if (step + 3 < steps) fetch(ra0, rb0);
-        multiply(1);
-        if (step + 2 < steps) stage(0, ra1, rb1);
+        load_bias();
+        fetch(ra0, rb0);
+        if (step >= 0) multiply(1);
+        stage(0, ra1, rb1);
         __syncthreads();
-        if ((step + 2) % ktiles == 0) finish_tile(first_tile + (step + 1) / ktiles);
+        if (step >= 0) after_multiply();
     }
 }
 
@@ -537,17 +617,19 @@ size_t gemm_workspace_bytes(int ta, int tb, int64_t M, int64_t N, int64_t K) {
 
 #define GEMM_F32_CASE(WM_, WN_, TM_, TN_)                                                                   \
     if (tl.wm == WM_ && tl.wn == WN_ && tl.tm == TM_ && tl.tn == TN_) {                                     \
-        if (bk == 16) {                                                                                     \
-            const size_t lds = (size_t)2 * ((WM_ * TM_ + WN_ * TN_) * 32) * (16 + 4) * sizeof(float);       \
-            hipLaunchKernelGGL((gemm_f32_kernel<WM_, WN_, TM_, TN_, 16>), grid, dim3(256), lds, st, (int)M, \
-                               (int)N, (int)K, A, Bt, C, bias, relu, tiles_m, tiles_n, tiles_per_block,     \
-                               vec_a, vec_b);                                                               \
-        } else {                                                                                            \
-            const size_t lds = (size_t)2 * ((WM_ * TM_ + WN_ * TN_) * 32) * (32 + 4) * sizeof(float);       \
-            hipLaunchKernelGGL((gemm_f32_kernel<WM_, WN_, TM_, TN_, 32>), grid, dim3(256), lds, st, (int)M, \
-                               (int)N, (int)K, A, Bt, C, bias, relu, tiles_m, tiles_n, tiles_per_block,     \
-                               vec_a, vec_b);                                                               \
-        }                                                                                                   \
+        constexpr int BM_ = WM_ * TM_ * 32, BN_ = WN_ * TN_ * 32;                                           \
+        const size_t lds = (size_t)2 * (BM_ + BN_) * (32 + 4) * sizeof(float);                              \
+        const bool fast = vec_a && vec_b && K > 0 && M % BM_ == 0 && N % BN_ == 0 && K % 32 == 0 &&         \
+                          (size_t)BM_ * K < (1u << 30) && (size_t)BN_ * K < (1u << 30) &&                   \
+                          (size_t)BM_ * N < (1u << 30);                                                     \
+        if (fast)                                                                                           \
+            hipLaunchKernelGGL((gemm_f32_kernel<WM_, WN_, TM_, TN_, 32, true>), grid, dim3(256), lds, st,   \
+                               (int)M, (int)N, (int)K, A, Bt, C, bias, relu, tiles_m, tiles_n,              \
+                               tiles_per_block, vec_a, vec_b);                                              \
+        else                                                                                                \
+            hipLaunchKernelGGL((gemm_f32_kernel<WM_, WN_, TM_, TN_, 32, false>), grid, dim3(256), lds, st,  \
+                               (int)M, (int)N, (int)K, A, Bt, C, bias, relu, tiles_m, tiles_n,              \
+                               tiles_per_block, vec_a, vec_b);                                              \
         launched = true;                                                                                    \
     }
 #define GEMM_F64_CASE(WM_, WN_, TM_, TN_)                                                                        \
@@ -581,8 +663,8 @@ gnn_status_t gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const 
         const int vec_b = aligned16(Bt) && K % 4 == 0;
         // persistent blocks: 64 per XCD (2 per CU), each owning a contiguous range of tiles
         const long total = (long)tiles_m * tiles_n;
+        if (total > INT32_MAX / 2 || total * ceil_div(K > 0 ? K : 1, 32) > INT32_MAX / 2) return GNN_ERR_UNSUPPORTED;
         const long per_xcd = ceil_div(total, 8);
-        const int bk = 32;                                 // k-tile depth (16 was measured slower on every layer shape)
         const int blocks_per_xcd = (int)(per_xcd < 64 ? per_xcd : 64);
         const int tiles_per_block = (int)ceil_div(per_xcd, blocks_per_xcd);
         dim3 grid((unsigned)(8 * blocks_per_xcd));

@@ -46,6 +46,16 @@ typedef enum {
 
 typedef enum { GNN_LAYER_GCN = 0, GNN_LAYER_GAT = 1 } gnn_layer_t;
 
+/* How an AUTO order / backward scheme is chosen for GCN. */
+typedef enum {
+    GNN_SELECT_PAPER_RULE = 0,    /* the usage conditions of the tables of Sec. 3.1: SpMM cost is taken
+                                     to be proportional to the dense width                              */
+    GNN_SELECT_CALIBRATED = 1     /* same candidates, compared by gnn_spmm_time_model_us: the time of this
+                                     library's SpMM on an MI355X, which is flat below ~32 columns and has a
+                                     fixed launch cost (Sec. 4.1 reports that the proportional rule misses
+                                     the best scheme where the two widths are close)                    */
+} gnn_select_t;
+
 /* Order of the two products of X' = A' X Theta (Sec. 3.1, Table "GCN schemes"). */
 typedef enum {
     GNN_ORDER_AUTO = 0,
@@ -113,6 +123,14 @@ typedef struct {
     gnn_order_t order;        /* AUTO or a forced choice                                        */
     gnn_bwd_t bwd;
     gnn_cache_t cache;
+    gnn_select_t selection;   /* GCN: how AUTO decides                                          */
+    int32_t constant_input;   /* GCN with the A'X cache: the caller promises that X and the graph
+                                 are the same in every forward call until gnn_plan_reset_cache
+                                 (a first layer whose input features never change).  Forward then
+                                 computes A'X only while the cache is empty, and AUTO counts that
+                                 SpMM as free.  X itself is only read by that first call.          */
+    int32_t fuse_elu;         /* GAT only: forward applies ELU (alpha = 1) after the bias, backward
+                                 multiplies dY by its derivative taken from the output Y            */
 } gnn_plan_desc_t;
 
 typedef struct {
@@ -141,6 +159,9 @@ typedef struct gnn_plan gnn_plan_t;
  *     forward:  F_out < F_in -> transform-first, else propagate-first
  *     backward: with dX: F_out < 2 F_in -> fused-propagate, else split-propagate
  *               no dX:   F_out <   F_in -> fused-propagate, else split-propagate
+ * With selection = CALIBRATED the same candidate schemes are compared by the summed model time
+ * of their SpMMs instead (the GEMMs are the same in every scheme); ties go to the rule's choice.
+ * With constant_input (and caching allowed) the forward SpMM of the cached scheme costs nothing.
  * Forced `order` / `bwd` values override the rule; cache = AX needs order = PROPAGATE_FIRST
  * (else GNN_ERR_INVALID_ARG).  GAT: order is fixed (node-attention form, App. B);
  * cache AUTO -> GNN_CACHE_GAT_FEAT_EDGE, the fastest variant of Sec. 4.2.
@@ -149,6 +170,18 @@ typedef struct gnn_plan gnn_plan_t;
 gnn_status_t gnn_plan_create(const gnn_plan_desc_t *desc, gnn_plan_t **out);
 gnn_status_t gnn_plan_query(const gnn_plan_t *plan, gnn_plan_info_t *out);
 void gnn_plan_destroy(gnn_plan_t *plan);
+
+/* Forget that a forward pass has filled the cache (constant_input: the next forward recomputes A'X). */
+gnn_status_t gnn_plan_reset_cache(gnn_plan_t *plan);
+
+/*
+ * gnn_spmm_time_model_us - the time model behind GNN_SELECT_CALIBRATED (host only): microseconds of
+ * one SpMM of dense width f on a graph of n nodes and nnz entries with this library's kernels on an
+ * MI355X:  t = 12 + nnz * max(13, c * f) * 1e-6,  c = 0.32 ps per entry and column while the dense
+ * operand (D = 4 n f bytes) is below 70 MB, else 0.32 + 0.045 log2(D / 70 MB), at most 0.53.
+ * Fitted to measurements on R-MAT graphs of 2^11 .. 2^22 nodes; within about 20 % of them.
+ */
+double gnn_spmm_time_model_us(int64_t n, int64_t nnz, int32_t f);
 
 /*
  * gcn_layer_fwd - Y = A' X W + 1 b^T (Eq. gcn-fwd), optionally ReLU.
@@ -178,7 +211,8 @@ gnn_status_t gcn_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const flo
 /*
  * gat_layer_fwd - multi-head GAT forward (Eqs. gat-fwd, gat-fwd-att), heads concatenated.
  *   X [n, f_in], W [f_in, heads*f_out], a_src / a_dst [heads, f_out], b [heads*f_out] or NULL,
- *   Y [n, heads*f_out] laid out [n][head][f_out] (head is the middle axis, Sec. 3.2).
+ *   Y [n, heads*f_out] laid out [n][head][f_out] (head is the middle axis, Sec. 3.2);
+ *   with fuse_elu, Y = ELU(aggregate + b) (the activation of the paper's two-layer GAT, Sec. 4).
  *   a_src multiplies the features of the row (aggregating) node, a_dst those of
  *   the column (neighbour) node: logit(i, j) = <a_src, m_i> + <a_dst, m_j>.
  *   The softmax runs over the stored entries of row i; csr_val is ignored.
@@ -194,10 +228,11 @@ gnn_status_t gat_layer_fwd(gnn_plan_t *plan, const gnn_graph_t *graph, const flo
 /*
  * gat_layer_bwd - gradients of Sec. "GAT Backward Pass": dW [f_in, h*k], da_src / da_dst [h, k],
  *   db [h*k] (iff has_bias), dX [n, f_in] (iff need_input_grad).  Needs the CSC arrays and perm.
+ *   Y [n, h*k]: the forward output; required iff fuse_elu (ELU'(x) = 1 for x > 0, else Y + 1).
  *   Whatever the cache variant did not keep is recomputed with the forward kernels.
  */
 gnn_status_t gat_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W,
-                           const float *a_src, const float *a_dst, const float *dY,
+                           const float *a_src, const float *a_dst, const float *Y, const float *dY,
                            float *dW, float *da_src, float *da_dst, float *db, float *dX,
                            void *cache, void *workspace, void *hip_stream);
 
@@ -292,6 +327,14 @@ size_t gnn_gemm_workspace_bytes(int32_t trans_a, int32_t trans_b, int64_t M, int
  */
 gnn_status_t gnn_softmax_xent(int32_t n, int32_t c, const float *Z, const int32_t *labels, float *dZ,
                               float *loss_out, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * gnn_sum_squared_error - loss_out[0] = 1/2 sum (Z - T)^2 over `count` elements and dZ = Z - T
+ * (the squared-error loss of the paper's full-network runs, Sec. 4, sum-reduced so that the
+ * gradient entries are O(1)).  Deterministic two-stage sum.  workspace: 4096 bytes.
+ */
+gnn_status_t gnn_sum_squared_error(int64_t count, const float *Z, const float *T, float *dZ, float *loss_out,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
 const char *gnn_status_string(gnn_status_t status);
 

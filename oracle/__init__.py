@@ -328,6 +328,31 @@ def gat_backward_cached(rowptr, col, X, Theta, a_src, a_dst, G, M32, s32, d32, s
 
 
 # --------------------------------------------------------------------------
+# the pieces around the layers in the paper's two-layer GAT network (Sec. 4):
+# ELU between the layers, squared-error loss at the end
+# --------------------------------------------------------------------------
+def elu(x):
+    """ELU with alpha = 1: x for x > 0, exp(x) - 1 otherwise."""
+    x = np.asarray(x, np.float64)
+    return np.where(x > 0.0, x, np.expm1(np.minimum(x, 0.0)))
+
+
+def elu_grad_from_output(G, Y):
+    """G * ELU'(x) written with the output y = ELU(x): ELU'(x) = 1 for x > 0, exp(x) = y + 1 otherwise
+    (y > 0 exactly when x > 0).  Y may be a float32 array: its sign is then the decision both
+    sides of a comparison share."""
+    G = np.asarray(G, np.float64)
+    Y = np.asarray(Y)
+    return np.where(Y > 0, G, G * (Y.astype(np.float64) + 1.0))
+
+
+def sum_squared_error(Z, T):
+    """loss = 1/2 sum (Z - T)^2 and its gradient Z - T (sum reduction: gradient entries O(1))."""
+    E = np.asarray(Z, np.float64) - np.asarray(T, np.float64)
+    return 0.5 * float(np.sum(E * E)), E
+
+
+# --------------------------------------------------------------------------
 # the paper's operational-intensity model for SpMM (App. E.1, table)
 # --------------------------------------------------------------------------
 def spmm_operational_intensity(fmt: str, n: int, q: int, f: int, p: int = 0) -> float:

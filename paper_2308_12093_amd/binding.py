@@ -32,6 +32,7 @@ GNN_ORDER_AUTO, GNN_ORDER_TRANSFORM_FIRST, GNN_ORDER_PROPAGATE_FIRST = 0, 1, 2
 GNN_BWD_AUTO, GNN_BWD_FUSED_PROPAGATE, GNN_BWD_SPLIT_PROPAGATE = 0, 1, 2
 (GNN_CACHE_AUTO, GNN_CACHE_NONE, GNN_CACHE_AX, GNN_CACHE_GAT_FEAT, GNN_CACHE_GAT_FEAT_NODEATT,
  GNN_CACHE_GAT_FEAT_EDGE) = range(6)
+GNN_SELECT_PAPER_RULE, GNN_SELECT_CALIBRATED = 0, 1
 
 _vp = ctypes.c_void_p
 _i32 = ctypes.c_int32
@@ -50,7 +51,7 @@ class gnn_plan_desc_t(ctypes.Structure):
     _fields_ = [("layer", ctypes.c_int), ("n", _i32), ("nnz", _i32), ("f_in", _i32), ("f_out", _i32),
                 ("heads", _i32), ("need_input_grad", _i32), ("has_bias", _i32), ("fuse_relu", _i32),
                 ("leaky_slope", ctypes.c_float), ("order", ctypes.c_int), ("bwd", ctypes.c_int),
-                ("cache", ctypes.c_int)]
+                ("cache", ctypes.c_int), ("selection", ctypes.c_int), ("constant_input", _i32), ("fuse_elu", _i32)]
 
 
 class gnn_plan_info_t(ctypes.Structure):
@@ -66,10 +67,12 @@ _PROTOS = {
     "gnn_plan_create": (ctypes.c_int, [ctypes.POINTER(gnn_plan_desc_t), ctypes.POINTER(_vp)]),
     "gnn_plan_query": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_plan_info_t)]),
     "gnn_plan_destroy": (None, [_vp]),
+    "gnn_plan_reset_cache": (ctypes.c_int, [_vp]),
+    "gnn_spmm_time_model_us": (ctypes.c_double, [_i64, _i64, _i32]),
     "gcn_layer_fwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 7),
     "gcn_layer_bwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 10),
     "gat_layer_fwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 9),
-    "gat_layer_bwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 13),
+    "gat_layer_bwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 14),
     "gnn_add_self_loops_degree": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(_i32), _vp, _sz, _vp]),
     "gnn_scan_workspace_bytes": (_sz, [_i32]),
     "gnn_gcn_normalize": (ctypes.c_int, [_i32, _vp, _vp, _vp, _vp, _vp]),
@@ -84,6 +87,7 @@ _PROTOS = {
     "gnn_gemm": (ctypes.c_int, [_i32, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]),
     "gnn_gemm_workspace_bytes": (_sz, [_i32, _i32, _i64, _i64, _i64]),
     "gnn_softmax_xent": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "gnn_sum_squared_error": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
 }
 EXPORTS = tuple(_PROTOS)
 for _name, (_res, _args) in _PROTOS.items():
@@ -143,12 +147,17 @@ class Graph:
 # ---- plan --------------------------------------------------------------------
 class Plan:
     def __init__(self, layer, n, nnz, f_in, f_out, heads=1, need_input_grad=True, has_bias=False,
-                 fuse_relu=False, leaky_slope=0.2, order=GNN_ORDER_AUTO, bwd=GNN_BWD_AUTO, cache=GNN_CACHE_AUTO):
+                 fuse_relu=False, leaky_slope=0.2, order=GNN_ORDER_AUTO, bwd=GNN_BWD_AUTO, cache=GNN_CACHE_AUTO,
+                 selection=GNN_SELECT_PAPER_RULE, constant_input=False, fuse_elu=False):
         self.desc = gnn_plan_desc_t(layer, n, nnz, f_in, f_out, heads, int(need_input_grad), int(has_bias),
-                                    int(fuse_relu), leaky_slope, order, bwd, cache)
+                                    int(fuse_relu), leaky_slope, order, bwd, cache, selection,
+                                    int(constant_input), int(fuse_elu))
         self.handle = _vp()
         _check(gnn_plan_create(self.desc, self.handle), "gnn_plan_create")
         self.info = gnn_plan_query(self.handle)
+
+    def reset_cache(self):
+        _check(lib.gnn_plan_reset_cache(self.handle), "gnn_plan_reset_cache")
 
     def close(self):
         if self.handle:
@@ -192,9 +201,10 @@ def gat_layer_fwd(plan: Plan, graph: Graph, X, W, a_src, a_dst, b, Y, cache, wor
                              _ptr(b), _ptr(Y), _ptr(cache), _ptr(workspace), _stream()), "gat_layer_fwd")
 
 
-def gat_layer_bwd(plan: Plan, graph: Graph, X, W, a_src, a_dst, dY, dW, da_src, da_dst, db, dX, cache, workspace):
+def gat_layer_bwd(plan: Plan, graph: Graph, X, W, a_src, a_dst, dY, dW, da_src, da_dst, db, dX, cache, workspace,
+                  Y=None):
     _check(lib.gat_layer_bwd(plan.handle, ctypes.byref(graph.c), _ptr(X), _ptr(W), _ptr(a_src), _ptr(a_dst),
-                             _ptr(dY), _ptr(dW), _ptr(da_src), _ptr(da_dst), _ptr(db), _ptr(dX),
+                             _ptr(Y), _ptr(dY), _ptr(dW), _ptr(da_src), _ptr(da_dst), _ptr(db), _ptr(dX),
                              _ptr(cache), _ptr(workspace), _stream()), "gat_layer_bwd")
 
 
@@ -233,6 +243,10 @@ def gnn_gather_f32(count, src, perm, out):
     _check(lib.gnn_gather_f32(count, _ptr(src), _ptr(perm), _ptr(out), _stream()), "gnn_gather_f32")
 
 
+def gnn_spmm_time_model_us(n, nnz, f) -> float:
+    return float(lib.gnn_spmm_time_model_us(n, nnz, f))
+
+
 # ---- operators ----------------------------------------------------------------------
 def gnn_spmm_workspace_bytes(n, nnz, f):
     return lib.gnn_spmm_workspace_bytes(n, nnz, f)
@@ -259,6 +273,11 @@ def gnn_gemm_workspace_bytes(trans_a, trans_b, M, N, K):
 def gnn_gemm(trans_a, trans_b, M, N, K, A, B, C, bias=None, relu=False, workspace=None):
     _check(lib.gnn_gemm(int(trans_a), int(trans_b), M, N, K, _ptr(A), _ptr(B), _ptr(C), _ptr(bias), int(relu),
                         _ptr(workspace), _nbytes(workspace), _stream()), "gnn_gemm")
+
+
+def gnn_sum_squared_error(count, Z, T, dZ, loss_out, workspace):
+    _check(lib.gnn_sum_squared_error(count, _ptr(Z), _ptr(T), _ptr(dZ), _ptr(loss_out), _ptr(workspace),
+                                     _nbytes(workspace), _stream()), "gnn_sum_squared_error")
 
 
 def gnn_softmax_xent(n, c, Z, labels, dZ, loss_out, workspace):

@@ -50,6 +50,14 @@ gnn_status_t gnn_plan_query(const gnn_plan_t *plan, gnn_plan_info_t *out) {
 
 void gnn_plan_destroy(gnn_plan_t *plan) { delete plan; }
 
+gnn_status_t gnn_plan_reset_cache(gnn_plan_t *plan) {
+    if (!plan) return GNN_ERR_INVALID_ARG;
+    plan->cache_filled = false;
+    return GNN_OK;
+}
+
+double gnn_spmm_time_model_us(int64_t n, int64_t nnz, int32_t f) { return spmm_time_model_us(n, nnz, f); }
+
 gnn_status_t gcn_layer_fwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W,
                            const float *b, float *Y, void *cache, void *workspace, void *hip_stream) {
     if (!plan || plan->desc.layer != GNN_LAYER_GCN) return GNN_ERR_INVALID_ARG;
@@ -104,13 +112,14 @@ gnn_status_t gat_layer_fwd(gnn_plan_t *plan, const gnn_graph_t *graph, const flo
 }
 
 gnn_status_t gat_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W,
-                           const float *a_src, const float *a_dst, const float *dY,
+                           const float *a_src, const float *a_dst, const float *Y, const float *dY,
                            float *dW, float *da_src, float *da_dst, float *db, float *dX,
                            void *cache, void *workspace, void *hip_stream) {
     if (!plan || plan->desc.layer != GNN_LAYER_GAT) return GNN_ERR_INVALID_ARG;
     GNN_TRY(check_graph(plan, graph, false, true, true));
     if (!X || !W || !a_src || !a_dst || !dY || !dW || !da_src || !da_dst || !workspace) return GNN_ERR_INVALID_ARG;
     if (plan->desc.has_bias && !db) return GNN_ERR_INVALID_ARG;
+    if (plan->desc.fuse_elu && !Y) return GNN_ERR_INVALID_ARG;
     if (plan->desc.need_input_grad && !dX) return GNN_ERR_INVALID_ARG;
     if (plan->info.cache != GNN_CACHE_NONE && !cache) return GNN_ERR_INVALID_ARG;
     if (bad_align(workspace) || (cache && bad_align(cache))) return GNN_ERR_INVALID_ARG;
@@ -124,7 +133,7 @@ gnn_status_t gat_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const flo
         if (plan->desc.has_bias && hipMemsetAsync(db, 0, sizeof(float) * f, st) != hipSuccess) return GNN_ERR_HIP;
         return GNN_OK;
     }
-    return gat_backward(*plan, *graph, X, W, a_src, a_dst, dY, dW, da_src, da_dst, db, dX, cache, workspace,
+    return gat_backward(*plan, *graph, X, W, a_src, a_dst, Y, dY, dW, da_src, da_dst, db, dX, cache, workspace,
                         as_stream(hip_stream));
 }
 
@@ -239,6 +248,14 @@ gnn_status_t gnn_softmax_xent(int32_t n, int32_t c, const float *Z, const int32_
     if (n > 0 && (!Z || !labels || !dZ || !workspace)) return GNN_ERR_INVALID_ARG;
     if (workspace_bytes < sizeof(float) * (size_t)ceil_div(n > 0 ? n : 1, 256)) return GNN_ERR_BUFFER_TOO_SMALL;
     return softmax_xent_launch(n, c, Z, labels, dZ, loss_out, workspace, as_stream(hip_stream));
+}
+
+gnn_status_t gnn_sum_squared_error(int64_t count, const float *Z, const float *T, float *dZ, float *loss_out,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (count < 0 || !loss_out || !workspace) return GNN_ERR_INVALID_ARG;
+    if (count > 0 && (!Z || !T || !dZ)) return GNN_ERR_INVALID_ARG;
+    if (workspace_bytes < 4096) return GNN_ERR_BUFFER_TOO_SMALL;
+    return squared_error_launch(count, Z, T, dZ, loss_out, workspace, as_stream(hip_stream));
 }
 
 }  // extern "C"

@@ -12,6 +12,9 @@ namespace gnn {
 constexpr int kWave = 64;            // CDNA wavefront width
 constexpr size_t kAlign = 256;       // alignment of every carved workspace / cache block
 
+// activation codes of the fused epilogues (the `relu` argument of the launchers: 0, 1 = the public values)
+constexpr int kActNone = 0, kActRelu = 1, kActElu = 2;
+
 static inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -62,10 +65,13 @@ gnn_status_t gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const 
 
 // ---- element-wise and reductions (elementwise.hip) ---------------------------------
 // out = G * [Y > 0]
-gnn_status_t relu_mask_launch(int64_t count, const float *G, const float *Y, float *out, hipStream_t st);
+// out = G * act'(x) with the derivative taken from the activation's output Y (kActRelu or kActElu)
+gnn_status_t activation_grad_launch(int64_t count, const float *G, const float *Y, float *out, int act, hipStream_t st);
 // out[c] = sum_i G[i][c], deterministic two-stage; workspace colsum_workspace_bytes(n, f)
 size_t colsum_workspace_bytes(int64_t n, int f);
 gnn_status_t colsum_launch(int64_t n, int f, const float *G, float *out, void *workspace, hipStream_t st);
+gnn_status_t squared_error_launch(int64_t count, const float *Z, const float *T, float *dZ, float *loss,
+                                  void *workspace, hipStream_t st);
 gnn_status_t softmax_xent_launch(int n, int c, const float *Z, const int32_t *labels, float *dZ, float *loss,
                                  void *workspace, hipStream_t st);
 

@@ -9,18 +9,19 @@ namespace gnn {
 namespace {
 
 __global__ void __launch_bounds__(256)
-relu_mask_kernel(long count4, long count, const float *__restrict__ G, const float *__restrict__ Y,
-                 float *__restrict__ out, int vec) {
+activation_grad_kernel(long count4, long count, const float *__restrict__ G, const float *__restrict__ Y,
+                       float *__restrict__ out, int vec, int act) {
+    // derivative of the activation from its output y: ReLU 1 / 0, ELU 1 / y + 1 (= exp(x) for x <= 0)
+    auto dact = [act](float g, float y) { return y > 0.f ? g : (act == kActElu ? g * (y + 1.f) : 0.f); };
     const long i = (long)blockIdx.x * 256 + threadIdx.x;
     if (vec) {
         if (i >= count4) return;
         const float4 g = reinterpret_cast<const float4 *>(G)[i];
         const float4 y = reinterpret_cast<const float4 *>(Y)[i];
-        reinterpret_cast<float4 *>(out)[i] =
-            make_float4(y.x > 0.f ? g.x : 0.f, y.y > 0.f ? g.y : 0.f, y.z > 0.f ? g.z : 0.f, y.w > 0.f ? g.w : 0.f);
+        reinterpret_cast<float4 *>(out)[i] = make_float4(dact(g.x, y.x), dact(g.y, y.y), dact(g.z, y.z), dact(g.w, y.w));
     } else {
         if (i >= count) return;
-        out[i] = Y[i] > 0.f ? G[i] : 0.f;
+        out[i] = dact(G[i], Y[i]);
     }
 }
 
@@ -118,6 +119,26 @@ __global__ void sum_serial_kernel(int count, const float *__restrict__ in, float
     }
 }
 
+// dZ = Z - T and one partial of 1/2 sum dZ^2 per block (grid-stride, fixed block count)
+__global__ void __launch_bounds__(256)
+squared_error_kernel(long count, const float *__restrict__ Z, const float *__restrict__ T, float *__restrict__ dZ,
+                     float *__restrict__ block_loss) {
+    __shared__ float red[256];
+    float acc = 0.f;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < count; i += (long)gridDim.x * 256) {
+        const float e = Z[i] - T[i];
+        dZ[i] = e;
+        acc = fmaf(0.5f * e, e, acc);
+    }
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float s = 0.f;
+        for (int k = 0; k < 256; ++k) s += red[k];
+        block_loss[blockIdx.x] = s;
+    }
+}
+
 long colsum_rows_per_block(long n) {
     long r = ceil_div(n, 1024);
     return r < 64 ? 64 : r;
@@ -125,12 +146,12 @@ long colsum_rows_per_block(long n) {
 
 }  // namespace
 
-gnn_status_t relu_mask_launch(int64_t count, const float *G, const float *Y, float *out, hipStream_t st) {
+gnn_status_t activation_grad_launch(int64_t count, const float *G, const float *Y, float *out, int act, hipStream_t st) {
     if (count <= 0) return GNN_OK;
     const int vec = count % 4 == 0 && aligned16(G) && aligned16(Y) && aligned16(out);
     const long threads = vec ? count / 4 : count;
-    hipLaunchKernelGGL(relu_mask_kernel, dim3((unsigned)ceil_div(threads, 256)), dim3(256), 0, st, (long)(count / 4),
-                       (long)count, G, Y, out, vec);
+    hipLaunchKernelGGL(activation_grad_kernel, dim3((unsigned)ceil_div(threads, 256)), dim3(256), 0, st,
+                       (long)(count / 4), (long)count, G, Y, out, vec, act);
     return launch_status();
 }
 
@@ -169,6 +190,17 @@ gnn_status_t softmax_xent_launch(int n, int c, const float *Z, const int32_t *la
     const int blocks = (int)ceil_div(n, 256);
     float *part = static_cast<float *>(workspace);
     hipLaunchKernelGGL(softmax_xent_kernel, dim3(blocks), dim3(256), 0, st, n, c, Z, labels, dZ, part);
+    GNN_TRY(launch_status());
+    hipLaunchKernelGGL(sum_serial_kernel, dim3(1), dim3(64), 0, st, blocks, part, loss);
+    return launch_status();
+}
+
+gnn_status_t squared_error_launch(int64_t count, const float *Z, const float *T, float *dZ, float *loss,
+                                  void *workspace, hipStream_t st) {
+    float *part = static_cast<float *>(workspace);
+    int blocks = (int)ceil_div(count > 0 ? count : 1, 256);
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(squared_error_kernel, dim3(blocks), dim3(256), 0, st, (long)count, Z, T, dZ, part);
     GNN_TRY(launch_status());
     hipLaunchKernelGGL(sum_serial_kernel, dim3(1), dim3(64), 0, st, blocks, part, loss);
     return launch_status();

@@ -47,14 +47,14 @@ gnn_status_t gat_forward(Plan &p, const gnn_graph_t &g, const float *X, const fl
                                     B.alpha, B.mask, at<char>(workspace, L.w_walk), st));
     // Y_i = sum_e alpha_e M_j (+ b): SpMM with one weight per entry and head
     GNN_TRY(spmm_launch(n, q, g.csr_rowptr, g.csr_col, g.csr_erow, EdgeWeights{B.alpha, nullptr, h, k}, B.M, f, Y,
-                        d.has_bias ? b : nullptr, 0, at<char>(workspace, L.w_spmm), st));
+                        d.has_bias ? b : nullptr, d.fuse_elu ? kActElu : kActNone, at<char>(workspace, L.w_spmm), st));
     p.cache_filled = true;
     return GNN_OK;
 }
 
 gnn_status_t gat_backward(Plan &p, const gnn_graph_t &g, const float *X, const float *W, const float *a_src,
-                          const float *a_dst, const float *dY, float *dW, float *da_src, float *da_dst, float *db,
-                          float *dX, void *cache, void *workspace, hipStream_t st) {
+                          const float *a_dst, const float *Y, const float *dY_in, float *dW, float *da_src,
+                          float *da_dst, float *db, float *dX, void *cache, void *workspace, hipStream_t st) {
     const gnn_plan_desc_t &d = p.desc;
     const int n = d.n, q = d.nnz, m = d.f_in, h = d.heads, k = d.f_out, f = h * k;
     if ((!g.csr_erow || !g.csc_ecol) && q > 0) return GNN_ERR_BAD_GRAPH;
@@ -70,6 +70,14 @@ gnn_status_t gat_backward(Plan &p, const gnn_graph_t &g, const float *X, const f
     if (variant != GNN_CACHE_GAT_FEAT_EDGE)
         GNN_TRY(gat_edge_softmax_launch(n, q, h, g.csr_rowptr, g.csr_erow, g.csr_col, B.s, B.d, d.leaky_slope, B.stat,
                                         B.alpha, nullptr, at<char>(workspace, L.w_walk), st));
+
+    // gradient through the fused ELU, from the layer's output
+    const float *dY = dY_in;
+    if (d.fuse_elu) {
+        float *G = at<float>(workspace, L.w_G);
+        GNN_TRY(activation_grad_launch((int64_t)n * f, dY_in, Y, G, kActElu, st));
+        dY = G;
+    }
 
     float *gy = at<float>(workspace, L.w_gy), *sums = at<float>(workspace, L.w_sums);
     float *ds = at<float>(workspace, L.w_ds), *dd = at<float>(workspace, L.w_dd), *dM = at<float>(workspace, L.w_dM);

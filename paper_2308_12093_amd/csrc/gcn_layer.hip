@@ -50,7 +50,9 @@ gnn_status_t gcn_forward(Plan &p, const gnn_graph_t &g, const float *X, const fl
         float *P = cached ? static_cast<float *>(cache) : ws.take<float>((size_t)n * m);
         void *sp = ws.take<char>(spmm_workspace_bytes(d.nnz, m));
         void *wt = ws.take<char>(gemm_workspace_bytes(0, 0, n, k, m));
-        GNN_TRY(spmm(g, forward_view(g, m), X, m, P, nullptr, 0, sp, st));
+        // a constant input (promised by the caller) needs its A'X only once
+        if (!(cached && d.constant_input && p.cache_filled))
+            GNN_TRY(spmm(g, forward_view(g, m), X, m, P, nullptr, 0, sp, st));
         GNN_TRY(gemm_launch(0, 0, n, k, m, P, W, Y, bias, d.fuse_relu, wt, st));
         if (cached) p.cache_filled = true;
     }
@@ -68,7 +70,7 @@ gnn_status_t gcn_backward(Plan &p, const gnn_graph_t &g, const float *X, const f
     const float *G = dY;
     if (d.fuse_relu) {                              // gradient through the fused ReLU
         float *Gm = ws.take<float>((size_t)n * k);
-        GNN_TRY(relu_mask_launch((int64_t)n * k, dY, Y, Gm, st));
+        GNN_TRY(activation_grad_launch((int64_t)n * k, dY, Y, Gm, kActRelu, st));
         G = Gm;
     }
     if (d.has_bias) {                               // db = G^T 1

@@ -19,7 +19,7 @@ using Plan = ::gnn_plan;
 struct GatLayout {
     size_t c_M, c_s, c_d, c_alpha, c_mask, cache_bytes;
     size_t w_M, w_s, w_d, w_alpha, w_stat, w_walk, w_spmm, w_gemm_nn;          // used by forward (and backward)
-    size_t w_gy, w_sums, w_ds, w_dd, w_spmm_h, w_dM, w_red, w_gemm_tn;         // backward only
+    size_t w_gy, w_sums, w_ds, w_dd, w_spmm_h, w_dM, w_red, w_gemm_tn, w_G;    // backward only (w_G: fused ELU)
     size_t workspace_bytes;
 };
 
@@ -34,7 +34,8 @@ gnn_status_t gcn_backward(Plan &p, const gnn_graph_t &g, const float *X, const f
 gnn_status_t gat_forward(Plan &p, const gnn_graph_t &g, const float *X, const float *W, const float *a_src,
                          const float *a_dst, const float *b, float *Y, void *cache, void *workspace, hipStream_t st);
 gnn_status_t gat_backward(Plan &p, const gnn_graph_t &g, const float *X, const float *W, const float *a_src,
-                          const float *a_dst, const float *dY, float *dW, float *da_src, float *da_dst, float *db,
-                          float *dX, void *cache, void *workspace, hipStream_t st);
+                          const float *a_dst, const float *Y, const float *dY, float *dW, float *da_src,
+                          float *da_dst, float *db, float *dX, void *cache, void *workspace, hipStream_t st);
+double spmm_time_model_us(int64_t n, int64_t nnz, int f);
 
 }  // namespace gnn

@@ -2,6 +2,7 @@
 // Sec. 3.2 / Table "GAT caching") and the sizes that follow from it.  Host code only.
 #include "plan.h"
 
+#include <cmath>
 #include <new>
 
 namespace gnn {
@@ -10,16 +11,32 @@ namespace {
 
 bool valid_enum(int v, int lo, int hi) { return v >= lo && v <= hi; }
 
+// Cost of one SpMM of dense width f as the selection sees it: the width itself under the
+// paper's rule (Sec. 3.1 takes SpMM time to be proportional to it), the fitted time of this
+// library's kernel on an MI355X under the calibrated selection.
+double spmm_cost(const gnn_plan_desc_t &d, int64_t f) {
+    return d.selection == GNN_SELECT_CALIBRATED ? spmm_time_model_us(d.n, d.nnz, (int)f) : (double)f;
+}
+
 gnn_status_t resolve_gcn(Plan &p) {
     const gnn_plan_desc_t &d = p.desc;
     const int64_t m = d.f_in, k = d.f_out;
     const bool dx = d.need_input_grad != 0;
     if (d.cache != GNN_CACHE_AUTO && d.cache != GNN_CACHE_NONE && d.cache != GNN_CACHE_AX) return GNN_ERR_INVALID_ARG;
     const bool allow_cache = d.cache != GNN_CACHE_NONE;
-    // usage conditions of the two tables
-    const bool nocache_fwd_tf = k < m;
-    const bool nocache_bwd_fp = dx ? (k < 2 * m) : (k < m);
-    const bool cached_tf_fp = dx ? (k < m) : (2 * k < m);
+    // The schemes differ only in their SpMMs (Tables "GCN schemes", "GCN schemes with caching"):
+    //   transform-first forward  one of width k      propagate-first forward  one of width m
+    //   fused-propagate backward one of width k      split-propagate backward  A'X (width m, unless
+    //                                                cached) and, with dX, A'^T (G Theta^T) (width m)
+    // With cost = width the comparisons below are the usage conditions printed in the tables
+    // (ties go to propagate-first / split-propagate, as "k >= m" does there).
+    const double ck = spmm_cost(d, k), cm = spmm_cost(d, m);
+    const bool reuse = allow_cache && d.constant_input;           // A'X of a constant input is computed once
+    const double cached_tf_fp_cost = 2 * ck;
+    const double cached_pf_sp_cost = (reuse ? 0.0 : cm) + (dx ? cm : 0.0);
+    const bool cached_tf_fp = cached_tf_fp_cost < cached_pf_sp_cost;
+    const bool nocache_fwd_tf = ck < cm;
+    const bool nocache_bwd_fp = ck < (dx ? 2 * cm : cm);
 
     gnn_order_t order = d.order;
     gnn_bwd_t bwd = d.bwd;
@@ -108,6 +125,20 @@ gnn_status_t resolve_gat(Plan &p) {
 
 }  // namespace
 
+// Fitted to this library's entry-balanced SpMM on an MI355X (R-MAT graphs, 2^11 .. 2^22 nodes):
+// a fixed cost of the two launches, then per entry the larger of a floor (index traffic and
+// one cache line per gathered row, reached below ~32 columns) and a per-column cost that
+// grows once the dense operand no longer fits the caches.
+double spmm_time_model_us(int64_t n, int64_t nnz, int f) {
+    if (n <= 0 || nnz <= 0 || f <= 0) return 0.0;
+    const double dense_mb = 4.0 * (double)n * f / 1e6;
+    double c = 0.32;                                               // ps per entry and column
+    if (dense_mb > 70.0) c += 0.045 * std::log2(dense_mb / 70.0);
+    if (c > 0.53) c = 0.53;
+    const double per_entry_ps = c * f > 13.0 ? c * f : 13.0;
+    return 12.0 + (double)nnz * per_entry_ps * 1e-6;
+}
+
 GatLayout gat_layout(const Plan &p) {
     const gnn_plan_desc_t &d = p.desc;
     const size_t n = d.n, q = d.nnz, h = d.heads, k = d.f_out, f = h * k, m = d.f_in, fl = sizeof(float);
@@ -139,6 +170,7 @@ GatLayout gat_layout(const Plan &p) {
     L.w_dM = take(n * f * fl);
     L.w_red = take(colsum_workspace_bytes(n, (int)f));
     L.w_gemm_tn = take(gemm_workspace_bytes(1, 0, m, f, n));
+    L.w_G = d.fuse_elu ? take(n * f * fl) : (size_t)-1;
     L.workspace_bytes = off + kAlign;
     return L;
 }
@@ -150,6 +182,9 @@ gnn_status_t plan_create(const gnn_plan_desc_t *desc, Plan **out) {
         !valid_enum(d.bwd, 0, 2) || !valid_enum(d.cache, 0, 5))
         return GNN_ERR_INVALID_ARG;
     if (d.n < 0 || d.nnz < 0 || d.f_in <= 0 || d.f_out <= 0) return GNN_ERR_INVALID_ARG;
+    if (!valid_enum(d.selection, GNN_SELECT_PAPER_RULE, GNN_SELECT_CALIBRATED)) return GNN_ERR_INVALID_ARG;
+    if (d.layer == GNN_LAYER_GCN && d.fuse_elu) return GNN_ERR_INVALID_ARG;
+    if (d.layer == GNN_LAYER_GAT && d.constant_input) return GNN_ERR_INVALID_ARG;
     Plan *p = new (std::nothrow) Plan();
     if (!p) return GNN_ERR_INVALID_ARG;
     p->desc = d;

@@ -31,9 +31,10 @@
 namespace gnn {
 namespace {
 
-__device__ __forceinline__ float epilogue(float x, const float *bias, int c, int relu) {
+__device__ __forceinline__ float epilogue(float x, const float *bias, int c, int act) {
     if (bias) x += bias[c];
-    if (relu) x = fmaxf(x, 0.f);
+    if (act == kActRelu) x = fmaxf(x, 0.f);
+    else if (act == kActElu) x = x > 0.f ? x : expm1f(x);
     return x;
 }
 

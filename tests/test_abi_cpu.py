@@ -167,3 +167,91 @@ def test_operator_calls_check_sizes():
     assert B.lib.gnn_gemm(0, 0, -1, 4, 4, one, one, one, null, 0, null, 0, null) == B.GNN_ERR_INVALID_ARG
     tw = B.gnn_transpose_workspace_bytes(100, 1000)
     assert B.lib.gnn_csr_transpose(100, 1000, one, one, one, one, one, one, tw - 1, null) == B.GNN_ERR_BUFFER_TOO_SMALL
+
+
+# ---- calibrated selection and constant inputs (host logic) --------------------------------
+def model_us(n, nnz, f):
+    """The documented time model, evaluated here from the text of the header."""
+    import math
+    dense_mb = 4.0 * n * f / 1e6
+    c = 0.32 if dense_mb <= 70.0 else min(0.53, 0.32 + 0.045 * math.log2(dense_mb / 70.0))
+    return 12.0 + nnz * max(13.0, c * f) * 1e-6
+
+
+def golden_times():
+    rows = []
+    for line in open(os.path.join(ROOT, "tests", "golden", "spmm_times_mi355x.txt")):
+        if line.strip() and not line.startswith("#"):
+            n, nnz, f, us = line.split()
+            rows.append((int(n), int(nnz), int(f), float(us)))
+    return rows
+
+
+def test_time_model_matches_its_documentation_and_the_measurements_it_was_fitted_to():
+    for n, nnz, f, us in golden_times():
+        got = B.gnn_spmm_time_model_us(n, nnz, f)
+        assert got == pytest.approx(model_us(n, nnz, f), rel=1e-12)
+        assert 0.75 * us <= got <= 1.3 * us, (n, nnz, f, us, got)
+    assert B.gnn_spmm_time_model_us(0, 0, 16) == 0.0
+    # monotone in the width, flat at the per-entry floor
+    t = [B.gnn_spmm_time_model_us(131072, 1841460, f) for f in (8, 16, 32, 64, 128, 256)]
+    assert t[0] == t[1] == t[2] and t[2] < t[3] < t[4] < t[5]
+
+
+CAL = dict(selection=B.GNN_SELECT_CALIBRATED, n=131072, nnz=1841460)
+
+
+def test_calibrated_selection_moves_the_crossovers_where_spmm_time_is_flat():
+    FP, SP = B.GNN_BWD_FUSED_PROPAGATE, B.GNN_BWD_SPLIT_PROPAGATE
+    # without dX the rule flips at k = m / 2 = 64; two narrow SpMMs cost more than half a wide one
+    for k, rule, cal in ((32, TF, TF), (48, TF, TF), (60, TF, PF), (64, PF, PF)):
+        assert plan(128, k, False, n=131072, nnz=1841460).info.order == rule
+        assert plan(128, k, False, **CAL).info.order == cal
+    # m = 64: a width-64 SpMM is cheaper than two at the floor, whatever k
+    assert plan(64, 16, False, n=131072, nnz=1841460).info.order == TF
+    p = plan(64, 16, False, **CAL)
+    assert (p.info.order, p.info.bwd, p.info.cache) == (PF, SP, B.GNN_CACHE_AX)
+    # the small graph of cfg1 (m = 512, k = 16, no dX): one launch pair less wins, as measured
+    p = plan(512, 16, False, selection=B.GNN_SELECT_CALIBRATED, n=2048, nnz=18432)
+    assert (p.info.order, p.info.cache) == (PF, B.GNN_CACHE_AX)
+    assert plan(512, 16, True, selection=B.GNN_SELECT_CALIBRATED, n=2048, nnz=18432).info.order == TF
+    # with dX both schemes run two SpMMs: same choice as the rule away from the floor
+    for m, k in ((128, 64), (128, 256), (512, 128), (128, 512)):
+        assert plan(m, k, True, **CAL).info.order == plan(m, k, True, n=131072, nnz=1841460).info.order
+    # no caching, backward with dX: one SpMM of width 64 beats two of width 16 (rule: 64 >= 2 * 16 -> split)
+    assert plan(16, 64, True, cache=B.GNN_CACHE_NONE, n=131072, nnz=1841460).info.bwd == SP
+    assert plan(16, 64, True, cache=B.GNN_CACHE_NONE, **CAL).info.bwd == FP
+    with pytest.raises(B.GnnError):
+        plan(16, 16, True, selection=7)
+
+
+def test_chosen_scheme_has_the_smallest_modelled_spmm_time():
+    n, nnz = 131072, 1841460
+    t = lambda f: B.gnn_spmm_time_model_us(n, nnz, f)
+    for m in (16, 64, 128, 512):
+        for k in (8, 16, 48, 64, 128, 256, 1024):
+            for dx in (False, True):
+                p = plan(m, k, dx, **CAL)
+                cost = {TF: 2 * t(k), PF: t(m) + (t(m) if dx else 0.0)}
+                assert cost[p.info.order] <= min(cost.values()) + 1e-9, (m, k, dx)
+
+
+def test_constant_input_makes_the_cached_scheme_free_in_forward():
+    SP = B.GNN_BWD_SPLIT_PROPAGATE
+    for m, k in ((512, 16), (128, 8), (16, 16), (64, 512)):
+        p = plan(m, k, False, constant_input=True)
+        assert (p.info.order, p.info.bwd, p.info.cache) == (PF, SP, B.GNN_CACHE_AX), (m, k)
+    # with dX the cached scheme still pays one SpMM of width m per iteration against two of width k
+    assert plan(512, 16, True, constant_input=True).info.order == TF        # 2 * 16 < 512
+    assert plan(128, 64, True, constant_input=True).info.order == PF        # 2 * 64 >= 128
+    assert plan(128, 64, True).info.order == TF
+    # no cache allowed: nothing to reuse
+    assert plan(512, 16, False, constant_input=True, cache=B.GNN_CACHE_NONE).info.order == TF
+    p = plan(128, 64, False, constant_input=True)
+    p.reset_cache()
+    with pytest.raises(B.GnnError):
+        B.Plan(B.GNN_LAYER_GAT, 100, 900, 16, 8, heads=2, constant_input=True)
+    with pytest.raises(B.GnnError):
+        plan(16, 16, True, fuse_elu=True)
+    assert B.Plan(B.GNN_LAYER_GAT, 100, 900, 16, 8, heads=2, fuse_elu=True).info.workspace_bytes > \
+        B.Plan(B.GNN_LAYER_GAT, 100, 900, 16, 8, heads=2).info.workspace_bytes

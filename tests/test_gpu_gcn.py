@@ -140,3 +140,39 @@ def test_cached_backward_needs_a_forward_first(B, G):
     with pytest.raises(B.GnnError) as e:
         B.gcn_layer_bwd(plan, g, None, t(8, 16), None, t(g.n, 16), t(8, 16), None, t(g.n, 8), cache, ws)
     assert e.value.status == B.GNN_ERR_STATE
+
+
+def test_constant_input_computes_the_cached_product_once(B, G):
+    """A first layer whose input never changes (constant_input): forward fills the A'X cache once and
+    later calls do not read X again until the cache is reset; results stay those of the oracle."""
+    s = synth.streams(41)
+    rowptr, col = synth.rmat_graph(10, 8, False, s["graph"], s["relabel"])
+    n, m, k = rowptr.size - 1, 48, 16                          # k < m / 2: the rule alone would transform first
+    X, X_other = synth.normal(s["X"], n, m), synth.normal(synth.substream(41, "X", 1), n, m)
+    W1, W2 = synth.glorot_uniform(s["W"], (m, k), m, k), synth.glorot_uniform(s["W2"], (m, k), m, k)
+    dY = synth.normal(s["dY"], n, k)
+    g = G.gcn_graph(rowptr, col)
+    rp, c, deg = oracle.add_self_loops_degree(rowptr, col)
+    val = oracle.gcn_normalize(rp, c, deg)
+    plan = B.Plan(B.GNN_LAYER_GCN, g.n, g.nnz, m, k, need_input_grad=False, constant_input=True)
+    assert (plan.info.order, plan.info.cache) == (B.GNN_ORDER_PROPAGATE_FIRST, B.GNN_CACHE_AX)
+    ws, cache = B.alloc(plan.info.workspace_bytes), B.alloc(plan.info.cache_bytes)
+    Y = torch.full((n, k), float("nan"), dtype=torch.float32, device="cuda")
+    dW = torch.full((m, k), float("nan"), dtype=torch.float32, device="cuda")
+
+    def step(x, w):
+        B.gcn_layer_fwd(plan, g, dev(x), dev(w), None, Y, cache, ws)
+        B.gcn_layer_bwd(plan, g, None, dev(w), None, dev(dY), dW, None, None, cache, ws)
+        torch.cuda.synchronize()
+        return host(Y), host(dW)
+
+    y, dw = step(X, W1)                                        # iteration 1 fills the cache
+    assert_close(y, oracle.gcn_forward(rp, c, val, X, W1), "iteration 1 Y")
+    assert_close(dw, oracle.gcn_backward(rp, c, val, X, W1, dY, None, False)[0], "iteration 1 dW")
+    y, dw = step(X_other, W2)                                  # new weights; the X argument is not read
+    assert_close(y, oracle.gcn_forward(rp, c, val, X, W2), "iteration 2 Y (cached A'X)")
+    assert_close(dw, oracle.gcn_backward(rp, c, val, X, W2, dY, None, False)[0], "iteration 2 dW")
+    plan.reset_cache()
+    y, dw = step(X_other, W2)                                  # after a reset the new input counts
+    assert_close(y, oracle.gcn_forward(rp, c, val, X_other, W2), "after reset Y")
+    assert_close(dw, oracle.gcn_backward(rp, c, val, X_other, W2, dY, None, False)[0], "after reset dW")

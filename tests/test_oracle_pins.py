@@ -357,6 +357,55 @@ def test_tie_band_switches_only_near_zero_logits():
 
 
 # ------------------------------------------------------------------ loss
+def test_elu_and_its_gradient_against_torch():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((40, 7)) * 2.0
+    x[0, :3] = [0.0, -1e-9, 1e-9]
+    g = rng.standard_normal(x.shape)
+    t = torch.tensor(x, requires_grad=True)
+    y = torch.nn.functional.elu(t)
+    (y * torch.tensor(g)).sum().backward()
+    np.testing.assert_allclose(oracle.elu(x), y.detach().numpy(), rtol=1e-14, atol=1e-15)
+    np.testing.assert_allclose(oracle.elu_grad_from_output(g, oracle.elu(x)), t.grad.numpy(), rtol=1e-13, atol=1e-15)
+    assert oracle.elu(np.array([-50.0]))[0] == pytest.approx(-1.0, abs=1e-15)      # saturates, no overflow
+    assert oracle.elu(np.array([700.0]))[0] == 700.0
+
+
+def test_two_layer_gat_with_elu_and_squared_error_against_torch_autograd():
+    """The paper's GAT network (Sec. 4): GAT -> ELU -> GAT, squared error; every gradient of the
+    chained oracle calls against autograd on the dense masked-softmax form."""
+    slope, h, k1, k2 = 0.2, 2, 3, 2
+    rng = np.random.default_rng(11)
+    rowptr, col = small_graph(n=23, q=90, seed=211, diagonal=False)
+    rp, c, _ = oracle.add_self_loops_degree(rowptr, col)
+    n, m = 23, 4
+    X = rng.standard_normal((n, m))
+    W1, W2 = rng.standard_normal((m, h * k1)) * 0.7, rng.standard_normal((h * k1, h * k2)) * 0.7
+    a1s, a1d, a2s, a2d = (rng.standard_normal((h, kk)) for kk in (k1, k1, k2, k2))
+    b1, b2 = rng.standard_normal(h * k1), rng.standard_normal(h * k2)
+    T = rng.standard_normal((n, h * k2))
+    params = (X, W1, a1s, a1d, b1, W2, a2s, a2d, b2)
+    tens = [torch.tensor(a, requires_grad=True) for a in params]
+    tX, tW1, ta1s, ta1d, tb1, tW2, ta2s, ta2d, tb2 = tens
+    H = torch.nn.functional.elu(_torch_dense_gat(rp, c, tX, tW1, ta1s, ta1d, tb1, h, k1, slope))
+    Z = _torch_dense_gat(rp, c, H, tW2, ta2s, ta2d, tb2, h, k2, slope)
+    loss_t = 0.5 * ((Z - torch.tensor(T)) ** 2).sum()
+    loss_t.backward()
+
+    f1 = oracle.gat_forward(rp, c, X, W1, a1s, a1d, b1, h, slope)
+    H1 = oracle.elu(f1["Y"])
+    f2 = oracle.gat_forward(rp, c, H1, W2, a2s, a2d, b2, h, slope)
+    loss, dZ = oracle.sum_squared_error(f2["Y"], T)
+    g2 = oracle.gat_backward(rp, c, H1, W2, a2s, a2d, dZ, h, slope)
+    dpre = oracle.elu_grad_from_output(g2["dX"], H1)
+    g1 = oracle.gat_backward(rp, c, X, W1, a1s, a1d, dpre, h, slope)
+    assert loss == pytest.approx(float(loss_t.detach()), rel=1e-12)
+    np.testing.assert_allclose(f2["Y"], Z.detach().numpy(), rtol=1e-11, atol=1e-12)
+    got = (g1["dX"], g1["dW"], g1["da_src"], g1["da_dst"], g1["db"], g2["dW"], g2["da_src"], g2["da_dst"], g2["db"])
+    for name, a, t in zip("dX dW1 da1s da1d db1 dW2 da2s da2d db2".split(), got, tens):
+        np.testing.assert_allclose(a, t.grad.numpy().reshape(a.shape), rtol=1e-9, atol=1e-10, err_msg=name)
+
+
 def test_softmax_xent_against_torch():
     rng = np.random.default_rng(4)
     Z = rng.standard_normal((50, 7)) * 3

@@ -32,7 +32,13 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg4", "cfg5", "gatnet"],
+                    help="gatnet: two GAT layers (8 heads, ELU between, squared error) on the cfg4 graph")
+    ap.add_argument("--hidden", type=int, default=8, help="gatnet: features per head of both layers (paper: 8..128)")
+    ap.add_argument("--selection", default="rule", choices=["rule", "calibrated"],
+                    help="GCN AUTO plans: the paper's width rule or the measured SpMM time model")
+    ap.add_argument("--constant-input", action="store_true",
+                    help="GCN: promise a constant X, so that the cached A'X is computed once")
     ap.add_argument("--scale", type=int, default=None, help="override the R-MAT scale (debug)")
     ap.add_argument("--scheme", default="auto", choices=["auto", "tf_fp", "pf_sp_nocache", "pf_sp_cache"])
     ap.add_argument("--gat-cache", default="auto", choices=["auto", "none", "feat", "nodeatt", "edge"],
@@ -98,6 +104,57 @@ def measured_traffic(workload, launch_widths):
     if any(f not in per_width for f in launch_widths):
         return None
     return round(sum(per_width[f] for f in launch_widths) / len(launch_widths))
+
+
+def bench_gat_network(args, torch, B, graphs, synth):
+    """Two-layer GAT network of Sec. 4 on the cfg4 graph: GAT(256 -> 8 x hidden) -> ELU -> GAT(-> 8 x hidden),
+    squared-error loss; one step = forward + loss + backward of both layers."""
+    w = synth.config4(scale=args.scale or 17)
+    h, m, k = w.dims["heads"], w.dims["f_in"], args.hidden
+    g = graphs.gat_graph(w.rowptr, w.col, "cuda")
+    n, q, f = g.n, g.nnz, h * k
+    variant = {"auto": B.GNN_CACHE_AUTO, "none": B.GNN_CACHE_NONE, "feat": B.GNN_CACHE_GAT_FEAT,
+               "nodeatt": B.GNN_CACHE_GAT_FEAT_NODEATT, "edge": B.GNN_CACHE_GAT_FEAT_EDGE}[args.gat_cache]
+    p1 = B.Plan(B.GNN_LAYER_GAT, n, q, m, k, heads=h, need_input_grad=False, has_bias=True, cache=variant, fuse_elu=True)
+    p2 = B.Plan(B.GNN_LAYER_GAT, n, q, f, k, heads=h, need_input_grad=True, has_bias=True, cache=variant)
+    gen = torch.Generator(device="cuda").manual_seed(0)
+    rnd = lambda *s, scale=1.0: torch.randn(s, device="cuda", generator=gen) * scale
+    X = torch.from_numpy(w.tensors["X"]).cuda()
+    W1, W2 = rnd(m, f, scale=(2.0 / (m + f)) ** 0.5), rnd(f, f, scale=(1.0 / f) ** 0.5)
+    a = [rnd(h, k, scale=(2.0 / (h + k)) ** 0.5) for _ in range(4)]
+    b1, b2, T = rnd(f, scale=0.1), rnd(f, scale=0.1), rnd(n, f)
+    e = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
+    H1, Z, dZ, dH1, loss = e(n, f), e(n, f), e(n, f), e(n, f), e(1)
+    g1 = (e(m, f), e(h, k), e(h, k), e(f))
+    g2 = (e(f, f), e(h, k), e(h, k), e(f))
+    ws = B.alloc(max(p1.info.workspace_bytes, p2.info.workspace_bytes, 4096))
+    c1 = B.alloc(p1.info.cache_bytes) if p1.info.cache_bytes else None
+    c2 = B.alloc(p2.info.cache_bytes) if p2.info.cache_bytes else None
+
+    def step():
+        B.gat_layer_fwd(p1, g, X, W1, a[0], a[1], b1, H1, c1, ws)
+        B.gat_layer_fwd(p2, g, H1, W2, a[2], a[3], b2, Z, c2, ws)
+        B.gnn_sum_squared_error(Z.numel(), Z, T, dZ, loss, ws)
+        B.gat_layer_bwd(p2, g, H1, W2, a[2], a[3], dZ, g2[0], g2[1], g2[2], g2[3], dH1, c2, ws)
+        B.gat_layer_bwd(p1, g, X, W1, a[0], a[1], dH1, g1[0], g1[1], g1[2], g1[3], None, c1, ws, Y=H1)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    edge_feat = q * (m + f) + q * (f + f)
+    out = {"metric": "two-layer GAT network fwd+bwd edge-feat/s", "value": edge_feat / (ms * 1e-3),
+           "unit": "edge*feat/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"gatnet on {w.name}: n={n}, nnz={q}, GAT({m} -> {h} x {k}) -> ELU -> GAT({f} -> {h} x {k}), "
+                                  f"squared error, cache variant={int(p1.info.cache)}",
+                      "cache_bytes": int(p1.info.cache_bytes + p2.info.cache_bytes)},
+           "roofline": None, "cpu_baseline": None}
+    print(json.dumps(out))
 
 
 def bench_gat(args, torch, B, graphs, synth):
@@ -168,6 +225,8 @@ def main():
 
     if args.workload == "cfg4":
         return bench_gat(args, torch, B, graphs, synth)
+    if args.workload == "gatnet":
+        return bench_gat_network(args, torch, B, graphs, synth)
     if args.workload == "cfg1":
         w = synth.config1()
     elif args.workload == "cfg2":
@@ -190,7 +249,9 @@ def main():
     }
 
     def make_layer(k, scheme, dx):
-        plan = B.Plan(B.GNN_LAYER_GCN, n, q, f_in, k, need_input_grad=dx, **scheme_kw[scheme])
+        plan = B.Plan(B.GNN_LAYER_GCN, n, q, f_in, k, need_input_grad=dx, constant_input=args.constant_input,
+                      selection=B.GNN_SELECT_CALIBRATED if args.selection == "calibrated" else B.GNN_SELECT_PAPER_RULE,
+                      **scheme_kw[scheme])
         L = dict(k=k, plan=plan,
                  W=torch.from_numpy(w.tensors[f"W{k}"]).to(dev), dY=torch.from_numpy(w.tensors[f"dY{k}"]).to(dev),
                  Y=torch.empty((n, k), dtype=torch.float32, device=dev),
@@ -310,7 +371,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: R-MAT/ER graph n={n}, nnz={q} (self-loops incl.), F_in={f_in}, "
                                f"F_out={list(f_outs)}, GCN single layer fwd+bwd, scheme={args.scheme}, "
-                               f"input_grad={need_dx}",
+                               f"input_grad={need_dx}, selection={args.selection}, constant_input={args.constant_input}",
                    "schemes": {str(L["k"]): {"order": int(L["plan"].info.order), "bwd": int(L["plan"].info.bwd),
                                              "cache": int(L["plan"].info.cache)} for L in layers}},
         "roofline": roofline,

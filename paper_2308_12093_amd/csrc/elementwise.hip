@@ -25,32 +25,54 @@ activation_grad_kernel(long count4, long count, const float *__restrict__ G, con
     }
 }
 
-// Stage 1 of out[c] = sum_i wgt(i, c) * G[i][c].  The 256 threads of a block form
-// (256 / fp) row lanes x fp columns (fp = power of two >= min(f, 256)); each block owns
-// `rows_per_block` consecutive rows and writes one partial row of f sums.
+// Stage 1 of out[c] = sum_i wgt(i, c) * G[i][c].  A thread owns VEC consecutive columns; the 256
+// threads of a block form (256 / fp) row lanes x fp column groups (fp = power of two >=
+// min(f / VEC, 256)); each block owns `rows_per_block` consecutive rows and writes one partial
+// row of f sums.  Four rows are in flight per thread (rotating accumulators, added in a
+// fixed order).  VEC = 4 needs f and head_dim to be multiples of 4 and 16-byte aligned rows.
+template <int VEC>
 __global__ void __launch_bounds__(256)
 colsum_partial_kernel(long n, int f, int fp, long rows_per_block, const float *__restrict__ G,
                       const float *__restrict__ wgt, int heads, int head_dim, double *__restrict__ part) {
-    __shared__ double red[256];
+    __shared__ double red[256][VEC];
     const int c0 = threadIdx.x % fp, rl = threadIdx.x / fp, lanes = 256 / fp;
     const long r0 = (long)blockIdx.x * rows_per_block;
     const long r1 = min(n, r0 + rows_per_block);
-    for (int cb = 0; cb < f; cb += fp) {
-        const int c = cb + c0;
-        double a = 0.0;
+    const int groups = (f + VEC - 1) / VEC;
+    for (int cb = 0; cb < groups; cb += fp) {
+        const int c = (cb + c0) * VEC;
+        double a[4][VEC];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) a[j][v] = 0.0;
         if (c < f) {
             const int hd = wgt ? c / head_dim : 0;
-            for (long i = r0 + rl; i < r1; i += lanes) {
-                const double g = G[(size_t)i * f + c];
-                a += wgt ? g * (double)wgt[(size_t)i * heads + hd] : g;
+            auto row = [&](long i, double (&acc)[VEC]) {
+                const double w = wgt ? (double)wgt[(size_t)i * heads + hd] : 1.0;
+                if constexpr (VEC == 4) {
+                    const float4 g = *reinterpret_cast<const float4 *>(G + (size_t)i * f + c);
+                    acc[0] += w * g.x; acc[1] += w * g.y; acc[2] += w * g.z; acc[3] += w * g.w;
+                } else {
+                    acc[0] += w * (double)G[(size_t)i * f + c];
+                }
+            };
+            long i = r0 + rl;
+            for (; i + 3L * lanes < r1; i += 4L * lanes) {
+                row(i, a[0]); row(i + lanes, a[1]); row(i + 2L * lanes, a[2]); row(i + 3L * lanes, a[3]);
             }
+            for (; i < r1; i += lanes) row(i, a[0]);
         }
-        red[threadIdx.x] = a;
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) red[threadIdx.x][v] = (a[0][v] + a[1][v]) + (a[2][v] + a[3][v]);
         __syncthreads();
         if (rl == 0 && c < f) {
-            double s = 0.0;
-            for (int k = 0; k < lanes; ++k) s += red[k * fp + c0];
-            part[(size_t)blockIdx.x * f + c] = s;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) {
+                double s = 0.0;
+                for (int k = 0; k < lanes; ++k) s += red[k * fp + c0][v];
+                part[(size_t)blockIdx.x * f + c + v] = s;
+            }
         }
         __syncthreads();
     }
@@ -165,11 +187,17 @@ static gnn_status_t colsum_weighted(int64_t n, int f, const float *G, const floa
     if (f <= 0) return GNN_OK;
     const long rpb = colsum_rows_per_block(n);
     const int blocks = (int)ceil_div(n > 0 ? n : 1, rpb);
+    const bool vec = f % 4 == 0 && head_dim % 4 == 0 && aligned16(G);
+    const int groups = vec ? f / 4 : f;
     int fp = 1;
-    while (fp < f && fp < 256) fp <<= 1;
+    while (fp < groups && fp < 256) fp <<= 1;
     double *part = static_cast<double *>(workspace);
-    hipLaunchKernelGGL(colsum_partial_kernel, dim3(blocks), dim3(256), 0, st, (long)n, f, fp, rpb, G, wgt, heads,
-                       head_dim, part);
+    if (vec)
+        hipLaunchKernelGGL(colsum_partial_kernel<4>, dim3(blocks), dim3(256), 0, st, (long)n, f, fp, rpb, G, wgt, heads,
+                           head_dim, part);
+    else
+        hipLaunchKernelGGL(colsum_partial_kernel<1>, dim3(blocks), dim3(256), 0, st, (long)n, f, fp, rpb, G, wgt, heads,
+                           head_dim, part);
     GNN_TRY(launch_status());
     hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)ceil_div(f, 16)), dim3(256), 0, st, f, blocks, part, out);
     return launch_status();

@@ -22,19 +22,30 @@ namespace {
 __device__ __forceinline__ float leaky(float y, float slope) { return y > 0.f ? y : slope * y; }
 
 // ---- s_i = <a_src, m_i>, d_i = <a_dst, m_i> per head (App. B) ------------------------
+// One thread per (node, head); VEC = 4 reads the k features as float4.
+template <int VEC>
 __global__ void __launch_bounds__(256)
 node_attention_kernel(long count, int h, int k, const float *__restrict__ M, const float *__restrict__ a_src,
                       const float *__restrict__ a_dst, float *__restrict__ s, float *__restrict__ d) {
     const long t = (long)blockIdx.x * 256 + threadIdx.x;      // t = i * h + p
     if (t >= count) return;
-    const int p = (int)(t % h);
+    const int p = count < (1L << 31) ? (int)((unsigned)t % (unsigned)h) : (int)(t % h);
     const float *m = M + (size_t)t * k;
     const float *as = a_src + (size_t)p * k, *ad = a_dst + (size_t)p * k;
     float ss = 0.f, dd = 0.f;
-    for (int c = 0; c < k; ++c) {
-        const float v = m[c];
-        ss = fmaf(as[c], v, ss);
-        dd = fmaf(ad[c], v, dd);
+    if constexpr (VEC == 4) {
+        for (int c = 0; c < k; c += 4) {
+            const float4 v = *reinterpret_cast<const float4 *>(m + c);
+            const float4 u = *reinterpret_cast<const float4 *>(as + c), w = *reinterpret_cast<const float4 *>(ad + c);
+            ss = fmaf(u.x, v.x, ss); ss = fmaf(u.y, v.y, ss); ss = fmaf(u.z, v.z, ss); ss = fmaf(u.w, v.w, ss);
+            dd = fmaf(w.x, v.x, dd); dd = fmaf(w.y, v.y, dd); dd = fmaf(w.z, v.z, dd); dd = fmaf(w.w, v.w, dd);
+        }
+    } else {
+        for (int c = 0; c < k; ++c) {
+            const float v = m[c];
+            ss = fmaf(as[c], v, ss);
+            dd = fmaf(ad[c], v, dd);
+        }
     }
     s[t] = ss;
     d[t] = dd;
@@ -259,21 +270,63 @@ head_fixup_kernel(int nnz, int h, int span, long nspan, const int32_t *__restric
     }
 }
 
-// ---- entry-parallel kernels, thread t = e * h + p --------------------------------------
+// ---- entry-parallel kernels ------------------------------------------------------------
+// Thread t = e * (h / HV) + pg handles HV consecutive heads of entry e (HV = 4 when h is a
+// multiple of 4: every access is then a 16-byte one; the buffers are 256-byte aligned blocks).
+__device__ __forceinline__ void split_index(long t, long count, int groups, long &e, int &pg) {
+    if (count < (1L << 31)) {                                  // 32-bit division when it is enough
+        const unsigned q = (unsigned)t / (unsigned)groups;
+        e = q;
+        pg = (int)((unsigned)t - q * (unsigned)groups);
+    } else {
+        e = t / groups;
+        pg = (int)(t % groups);
+    }
+}
+
+template <int HV> __device__ __forceinline__ void load_vec(const float *p, float (&v)[HV]) {
+    if constexpr (HV == 4) {
+        const float4 q = *reinterpret_cast<const float4 *>(p);
+        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    } else v[0] = *p;
+}
+template <int HV> __device__ __forceinline__ void store_vec(float *p, const float (&v)[HV]) {
+    if constexpr (HV == 4) *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    else *p = v[0];
+}
+
 // alpha_e = exp(w_e - max_i) / sum_i, mask_e = (y_e > 0)
+template <int HV>
 __global__ void __launch_bounds__(256)
 edge_alpha_kernel(long count, int h, const int32_t *__restrict__ erow, const int32_t *__restrict__ col,
                   const float *__restrict__ s, const float *__restrict__ d, const float *__restrict__ stat,
                   float slope, float *__restrict__ alpha, uint8_t *__restrict__ mask) {
     const long t = (long)blockIdx.x * 256 + threadIdx.x;
     if (t >= count) return;
-    const long e = t / h;
-    const int p = (int)(t % h);
+    long e; int pg;
+    split_index(t, count, h / HV, e, pg);
+    const int p0 = pg * HV;
     const int r = erow[e], c = col[e];
-    const float y = s[(size_t)r * h + p] + d[(size_t)c * h + p];
-    const float2 ml = reinterpret_cast<const float2 *>(stat)[(size_t)r * h + p];
-    alpha[t] = __expf(leaky(y, slope) - ml.x) / ml.y;
-    if (mask) mask[t] = y > 0.f;
+    float sv[HV], dv[HV], st0[HV], st1[HV], out[HV];
+    load_vec<HV>(s + (size_t)r * h + p0, sv);
+    load_vec<HV>(d + (size_t)c * h + p0, dv);
+    const float *sp = stat + ((size_t)r * h + p0) * 2;            // (max, sum) pairs
+    if constexpr (HV == 4) {
+        const float4 x = *reinterpret_cast<const float4 *>(sp), y = *reinterpret_cast<const float4 *>(sp + 4);
+        st0[0] = x.x; st1[0] = x.y; st0[1] = x.z; st1[1] = x.w; st0[2] = y.x; st1[2] = y.y; st0[3] = y.z; st1[3] = y.w;
+    } else { st0[0] = sp[0]; st1[0] = sp[1]; }
+    uint8_t m[HV];
+#pragma unroll
+    for (int i = 0; i < HV; ++i) {
+        const float y = sv[i] + dv[i];
+        out[i] = __expf(leaky(y, slope) - st0[i]) / st1[i];
+        m[i] = y > 0.f;
+    }
+    store_vec<HV>(alpha + (size_t)e * h + p0, out);
+    if (mask) {
+        if constexpr (HV == 4) *reinterpret_cast<uchar4 *>(mask + (size_t)e * h + p0) = make_uchar4(m[0], m[1], m[2], m[3]);
+        else mask[(size_t)e * h + p0] = m[0];
+    }
 }
 
 // D_e = val_e * <B_i, Ct_j> per head (App. E.2)
@@ -300,20 +353,39 @@ sddmm_edge_kernel(long count, int h, int k, const int32_t *__restrict__ erow, co
 }
 
 // g_y_e = alpha_e (g_alpha_e - t_i) * (y_e > 0 ? 1 : beta); gy holds g_alpha on entry
+template <int HV>
 __global__ void __launch_bounds__(256)
 edge_gy_kernel(long count, int h, const int32_t *__restrict__ erow, const int32_t *__restrict__ col,
                const float *__restrict__ alpha, const uint8_t *__restrict__ mask, const float *__restrict__ s,
                const float *__restrict__ d, const float *__restrict__ sums, float slope, float *__restrict__ gy) {
     const long t = (long)blockIdx.x * 256 + threadIdx.x;
     if (t >= count) return;
-    const long e = t / h;
-    const int p = (int)(t % h);
+    long e; int pg;
+    split_index(t, count, h / HV, e, pg);
+    const int p0 = pg * HV;
     const int r = erow[e];
-    bool pos;
-    if (mask) pos = mask[t] != 0;
-    else pos = (s[(size_t)r * h + p] + d[(size_t)col[e] * h + p]) > 0.f;
-    const float ti = sums[((size_t)r * h + p) * 3];
-    gy[t] = alpha[t] * (gy[t] - ti) * (pos ? 1.f : slope);
+    bool pos[HV];
+    if (mask) {
+        if constexpr (HV == 4) {
+            const uchar4 m = *reinterpret_cast<const uchar4 *>(mask + (size_t)e * h + p0);
+            pos[0] = m.x != 0; pos[1] = m.y != 0; pos[2] = m.z != 0; pos[3] = m.w != 0;
+        } else pos[0] = mask[(size_t)e * h + p0] != 0;
+    } else {
+        float sv[HV], dv[HV];
+        load_vec<HV>(s + (size_t)r * h + p0, sv);
+        load_vec<HV>(d + (size_t)col[e] * h + p0, dv);
+#pragma unroll
+        for (int i = 0; i < HV; ++i) pos[i] = (sv[i] + dv[i]) > 0.f;
+    }
+    float al[HV], g[HV];
+    load_vec<HV>(alpha + (size_t)e * h + p0, al);
+    load_vec<HV>(gy + (size_t)e * h + p0, g);
+#pragma unroll
+    for (int i = 0; i < HV; ++i) {
+        const float ti = sums[((size_t)r * h + p0 + i) * 3];
+        g[i] = al[i] * (g[i] - ti) * (pos[i] ? 1.f : slope);
+    }
+    store_vec<HV>(gy + (size_t)e * h + p0, g);
 }
 
 // ds_i = sum_e g_y_e = (1 - beta) (P_i - t_i Q_i): the softmax gradient sums to zero over a row,
@@ -326,16 +398,26 @@ node_ds_kernel(long count, const float *__restrict__ sums, float slope, float *_
     ds[t] = (1.f - slope) * (P - ti * Q);
 }
 
-// dM_{i,p,c} += ds_{i,p} a_src_{p,c} + dd_{i,p} a_dst_{p,c}
+// dM_{i,p,c} += ds_{i,p} a_src_{p,c} + dd_{i,p} a_dst_{p,c}; one thread per VEC consecutive c
+template <int VEC>
 __global__ void __launch_bounds__(256)
 add_rank1_kernel(long count, int h, int k, const float *__restrict__ ds, const float *__restrict__ dd,
                  const float *__restrict__ a_src, const float *__restrict__ a_dst, float *__restrict__ dM) {
-    const long t = (long)blockIdx.x * 256 + threadIdx.x;      // t = (i * h + p) * k + c
-    if (t >= count) return;
-    const int f = h * k;
-    const int pc = (int)(t % f);
-    const long ip = t / k;
-    dM[t] += ds[ip] * a_src[pc] + dd[ip] * a_dst[pc];
+    const long tv = (long)blockIdx.x * 256 + threadIdx.x;     // element t = VEC * tv = (i * h + p) * k + c
+    if (tv >= count) return;
+    const int kv = k / VEC, fv = h * kv;
+    long ip, node;                                            // ip = i * h + p;  pcv = (p * k + c) / VEC
+    int cv, pcv;
+    split_index(tv, count, kv, ip, cv);
+    split_index(tv, count, fv, node, pcv);
+    const float a = ds[ip], b = dd[ip];
+    float u[VEC], w[VEC], m[VEC];
+    load_vec<VEC>(a_src + (size_t)pcv * VEC, u);
+    load_vec<VEC>(a_dst + (size_t)pcv * VEC, w);
+    load_vec<VEC>(dM + (size_t)tv * VEC, m);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) m[i] += a * u[i] + b * w[i];
+    store_vec<VEC>(dM + (size_t)tv * VEC, m);
 }
 
 int pow2_at_least(int x) {
@@ -392,8 +474,12 @@ gnn_status_t gat_node_attention_launch(int n, int h, int k, const float *M, cons
                                        float *s, float *d, hipStream_t st) {
     const long count = (long)n * h;
     if (count <= 0) return GNN_OK;
-    hipLaunchKernelGGL(node_attention_kernel, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count, h, k, M,
-                       a_src, a_dst, s, d);
+    if (k % 4 == 0 && aligned16(M) && aligned16(a_src) && aligned16(a_dst))
+        hipLaunchKernelGGL(node_attention_kernel<4>, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count, h,
+                           k, M, a_src, a_dst, s, d);
+    else
+        hipLaunchKernelGGL(node_attention_kernel<1>, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count, h,
+                           k, M, a_src, a_dst, s, d);
     return launch_status();
 }
 
@@ -405,9 +491,16 @@ gnn_status_t gat_edge_softmax_launch(int n, int nnz, int h, const int32_t *rowpt
     if (nnz <= 0) return GNN_OK;
     StatsOp op{s, d, slope};
     GNN_TRY(run_head_walker<StatsOp>(nnz, h, rowptr, erow, col, op, stat, static_cast<float *>(workspace), st));
-    const long count = (long)nnz * h;
-    hipLaunchKernelGGL(edge_alpha_kernel, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count, h, erow, col,
-                       s, d, stat, slope, alpha, mask);
+    if (h % 4 == 0 && aligned16(s) && aligned16(d) && aligned16(stat) && aligned16(alpha) &&
+        (!mask || (reinterpret_cast<uintptr_t>(mask) & 3u) == 0)) {
+        const long count = (long)nnz * (h / 4);
+        hipLaunchKernelGGL(edge_alpha_kernel<4>, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count, h, erow,
+                           col, s, d, stat, slope, alpha, mask);
+    } else {
+        const long count = (long)nnz * h;
+        hipLaunchKernelGGL(edge_alpha_kernel<1>, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count, h, erow,
+                           col, s, d, stat, slope, alpha, mask);
+    }
     return launch_status();
 }
 
@@ -431,8 +524,13 @@ gnn_status_t gat_edge_backward_launch(int n, int nnz, int h, const int32_t *rowp
     SumsOp op{alpha, gy, mask, s, d};
     GNN_TRY(run_head_walker<SumsOp>(nnz, h, rowptr, erow, col, op, sums, static_cast<float *>(workspace), st));
     const long ecount = (long)nnz * h, ncount = (long)n * h;
-    hipLaunchKernelGGL(edge_gy_kernel, dim3((unsigned)ceil_div(ecount, 256)), dim3(256), 0, st, ecount, h, erow, col,
-                       alpha, mask, s, d, sums, slope, gy);
+    if (h % 4 == 0 && aligned16(alpha) && aligned16(gy) && aligned16(s) && aligned16(d) &&
+        (!mask || (reinterpret_cast<uintptr_t>(mask) & 3u) == 0))
+        hipLaunchKernelGGL(edge_gy_kernel<4>, dim3((unsigned)ceil_div(ecount / 4, 256)), dim3(256), 0, st, ecount / 4, h,
+                           erow, col, alpha, mask, s, d, sums, slope, gy);
+    else
+        hipLaunchKernelGGL(edge_gy_kernel<1>, dim3((unsigned)ceil_div(ecount, 256)), dim3(256), 0, st, ecount, h, erow,
+                           col, alpha, mask, s, d, sums, slope, gy);
     GNN_TRY(launch_status());
     hipLaunchKernelGGL(node_ds_kernel, dim3((unsigned)ceil_div(ncount, 256)), dim3(256), 0, st, ncount, sums, slope, ds);
     return launch_status();
@@ -442,8 +540,12 @@ gnn_status_t gat_add_rank1_launch(int n, int h, int k, const float *ds, const fl
                                   const float *a_dst, float *dM, hipStream_t st) {
     const long count = (long)n * h * k;
     if (count <= 0) return GNN_OK;
-    hipLaunchKernelGGL(add_rank1_kernel, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count, h, k, ds, dd,
-                       a_src, a_dst, dM);
+    if (k % 4 == 0 && aligned16(dM) && aligned16(a_src) && aligned16(a_dst))
+        hipLaunchKernelGGL(add_rank1_kernel<4>, dim3((unsigned)ceil_div(count / 4, 256)), dim3(256), 0, st, count / 4, h,
+                           k, ds, dd, a_src, a_dst, dM);
+    else
+        hipLaunchKernelGGL(add_rank1_kernel<1>, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count, h, k, ds,
+                           dd, a_src, a_dst, dM);
     return launch_status();
 }
 

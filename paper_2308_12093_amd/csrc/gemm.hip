@@ -4,11 +4,8 @@
 //
 // One block = 256 threads = 4 wavefronts arranged WM x WN; each wavefront owns
 // TM x TN output tiles of one matrix instruction (32 x 32 for
-// v_mfma_f32_32x32x2_f32, 16 x 16 for v_mfma_f64_16x16x4_f64).  Both operands are
-// staged through LDS k-major ([BK][rows + pad]) so that the operand reads of the
-// matrix instruction are consecutive words; the loaders transpose on the way in
-// when the source is stored the other way round.  The next k-tile is fetched into
-// registers while the current one is multiplied.
+// v_mfma_f32_32x32x2_f32, 16 x 16 for v_mfma_f64_16x16x4_f64).  Operands are staged
+// through LDS in the layout they have in memory, 16 bytes at a time.
 //
 // The transposed-A form  X^T H  sums over every node (up to millions of terms of
 // either sign).  A float accumulator loses ~1e-7 * sqrt(#terms) * |term| there, which
@@ -22,8 +19,6 @@
 // Block ids are remapped so that the eight XCDs (ids are dealt round-robin to
 // them) each work on a contiguous range of (chunk, tile) pairs: the tiles that
 // re-read the same rows of an operand share an L2 and run close in time.
-#include <type_traits>
-
 #include "common.h"
 
 namespace gnn {
@@ -35,24 +30,31 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));   // a native vector:
 
 constexpr int BK = 32;
 
-// F64 = false:  C[M][N] (float)  = A[M][K] * (TB ? B[N][K]^T : B[K][N]) + bias, ReLU
-// F64 = true :  P[chunk][M][N] (double) = A[K][M]^T * B[K][N] over one chunk of K
-template <bool F64, bool TB, int WM, int WN, int TM, int TN>
+// ---- fp64: P[chunk][M][N] (double) = A[K][M]^T * B[K][N] over one chunk of K ---------------
+// Both operands have the reduction index as their row index, so k-tiles go to LDS as they are
+// ([BK][columns + pad], 16-byte in).  One v_mfma_f64_16x16x4_f64 takes, per lane (lu, lk), the
+// element (k = lk, i = lu) of a 4 x 16 slice of each operand.  A wavefront owns TM x TN such
+// tiles, interleaved: tile x holds the output rows  base + TM * i + x  (columns likewise with
+// TN), so the TM values a lane needs from one k-row are consecutive words and come with one
+// LDS read (b32 / b64 / b128), and the TN partial sums a lane holds for one output row are
+// consecutive doubles.  Row padding spreads the four k-rows of a read over the banks.
+// LDS is double-buffered: the next k-tile is fetched into registers before the current one is
+// multiplied and written to the other buffer after it (one barrier per k-tile); the operands
+// of k-step s+1 are read and widened before the instructions of step s.
+template <int WM, int WN, int TM, int TN>
 __global__ void __launch_bounds__(256)
-gemm_kernel(int M, int N, long K, const float *__restrict__ A, const float *__restrict__ B, void *__restrict__ Cv,
-            const float *__restrict__ bias, int relu, long k_chunk, int tiles_m, int tiles_n, int splits, int vec_a,
-            int vec_b) {
-    constexpr bool TA = F64;
-    constexpr int UNIT = F64 ? 16 : 32;                 // edge of one matrix-instruction tile
-    constexpr int KSTEP = F64 ? 4 : 2;                  // reduction depth of one instruction
-    constexpr int BM = WM * TM * UNIT, BN = WN * TN * UNIT;
-    // row padding: the four k-rows read by one fp64 matrix instruction (16 consecutive words each) must
-    // fall into four different groups of 16 LDS banks: row length = 16 mod 64 words
-    constexpr int PA = TA ? (F64 ? (80 - BM % 64) % 64 : 4) : 1, PB = TB ? 1 : (F64 ? (80 - BN % 64) % 64 : 4);
-    constexpr int NA = BM * BK / 4, NB = BN * BK / 4;   // float4 granules per tile
+gemm_tn_f64_kernel(int M, int N, long K, const float *__restrict__ A, const float *__restrict__ B,
+                   double *__restrict__ P, long k_chunk, int tiles_m, int tiles_n, int splits, int vec_a, int vec_b) {
+    constexpr int BM = WM * TM * 16, BN = WN * TN * 16, KSTEP = 4;
+    // words per LDS row: the lanes of one k-row read 16 * T consecutive words; T = 1: four rows fill the 64
+    // banks at a row length of 16 mod 64; T = 2: two rows per pass, 32 mod 64; T = 4: one row per pass
+    constexpr int LA = BM + (TM == 1 ? (80 - BM % 64) % 64 : TM == 2 ? (96 - BM % 64) % 64 : 4);
+    constexpr int LB = BN + (TN == 1 ? (80 - BN % 64) % 64 : TN == 2 ? (96 - BN % 64) % 64 : 4);
+    constexpr int NA = BM * BK / 4, NB = BN * BK / 4;   // 16-byte granules per tile
     constexpr int GA = (NA + 255) / 256, GB = (NB + 255) / 256;
-    __shared__ float As[BK][BM + PA];
-    __shared__ float Bs[BK][BN + PB];
+    extern __shared__ __align__(16) float lds[];
+    float (*As)[BK][LA] = reinterpret_cast<float (*)[BK][LA]>(lds);                    // [2][BK][LA]
+    float (*Bs)[BK][LB] = reinterpret_cast<float (*)[BK][LB]>(lds + 2 * BK * LA);      // [2][BK][LB]
 
     const long tiles = (long)tiles_m * tiles_n;
     const long total = tiles * splits;
@@ -69,189 +71,116 @@ gemm_kernel(int M, int N, long K, const float *__restrict__ A, const float *__re
     const int t = threadIdx.x;
     const int wave = t / 64, lane = t % 64;
     const int wm = wave / WN, wn = wave % WN;
-    const int lu = lane % UNIT, lk = lane / UNIT;       // position inside the instruction's operand
+    const int lu = lane % 16, lk = lane / 16;           // position inside the instruction's operand
 
-    float4 ra[GA], rb[GB];
-
-    auto fetch = [&](long k0) {
+    floatx4 ra[GA], rb[GB];
+    // granule j of a k-tile: k-row j / (cols / 4), columns 4 * (j % (cols / 4)) ...
+    auto fetch_one = [&](const float *__restrict__ src, int cols_total, int col0, int tile_cols, int v4, long k0,
+                         int j) __attribute__((always_inline)) {
+        floatx4 v = {0.f, 0.f, 0.f, 0.f};
+        const int kk = j / (tile_cols / 4), cq = (j % (tile_cols / 4)) * 4;
+        const long gk = k0 + kk;
+        const int gc = col0 + cq;
+        if (gk < kend) {
+            const float *q = src + gk * cols_total + gc;
+            if (v4 && gc + 3 < cols_total) v = *reinterpret_cast<const floatx4 *>(q);
+            else {
+                if (gc < cols_total) v.x = q[0];
+                if (gc + 1 < cols_total) v.y = q[1];
+                if (gc + 2 < cols_total) v.z = q[2];
+                if (gc + 3 < cols_total) v.w = q[3];
+            }
+        }
+        return v;
+    };
+    auto fetch = [&](long k0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int p = 0; p < GA; ++p)
+            if (NA % 256 == 0 || t + 256 * p < NA) ra[p] = fetch_one(A, M, m0, BM, vec_a, k0, t + 256 * p);
+#pragma unroll
+        for (int p = 0; p < GB; ++p)
+            if (NB % 256 == 0 || t + 256 * p < NB) rb[p] = fetch_one(B, N, n0, BN, vec_b, k0, t + 256 * p);
+    };
+    auto stage = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int p = 0; p < GA; ++p) {
             const int j = t + 256 * p;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (NA % 256 == 0 || j < NA) {
-                if constexpr (!TA) {                       // A[M][K], granule runs along k
-                    const int row = j / (BK / 4), kq = (j % (BK / 4)) * 4;
-                    const long gi = m0 + row, gk = k0 + kq;
-                    if (gi < M) {
-                        const float *src = A + gi * K + gk;
-                        if (vec_a && gk + 3 < kend) v = *reinterpret_cast<const float4 *>(src);
-                        else {
-                            if (gk < kend) v.x = src[0];
-                            if (gk + 1 < kend) v.y = src[1];
-                            if (gk + 2 < kend) v.z = src[2];
-                            if (gk + 3 < kend) v.w = src[3];
-                        }
-                    }
-                } else {                                   // A[K][M], granule runs along the output row index
-                    const int kk = j / (BM / 4), iq = (j % (BM / 4)) * 4;
-                    const long gk = k0 + kk, gi = m0 + iq;
-                    if (gk < kend) {
-                        const float *src = A + gk * M + gi;
-                        if (vec_a && gi + 3 < M) v = *reinterpret_cast<const float4 *>(src);
-                        else {
-                            if (gi < M) v.x = src[0];
-                            if (gi + 1 < M) v.y = src[1];
-                            if (gi + 2 < M) v.z = src[2];
-                            if (gi + 3 < M) v.w = src[3];
-                        }
-                    }
-                }
-            }
-            ra[p] = v;
+            if (NA % 256 == 0 || j < NA) *reinterpret_cast<floatx4 *>(&As[buf][j / (BM / 4)][(j % (BM / 4)) * 4]) = ra[p];
         }
 #pragma unroll
         for (int p = 0; p < GB; ++p) {
             const int j = t + 256 * p;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (NB % 256 == 0 || j < NB) {
-                if constexpr (!TB) {                       // B[K][N], granule runs along the output column index
-                    const int kk = j / (BN / 4), jq = (j % (BN / 4)) * 4;
-                    const long gk = k0 + kk, gj = n0 + jq;
-                    if (gk < kend) {
-                        const float *src = B + gk * N + gj;
-                        if (vec_b && gj + 3 < N) v = *reinterpret_cast<const float4 *>(src);
-                        else {
-                            if (gj < N) v.x = src[0];
-                            if (gj + 1 < N) v.y = src[1];
-                            if (gj + 2 < N) v.z = src[2];
-                            if (gj + 3 < N) v.w = src[3];
-                        }
-                    }
-                } else {                                   // B[N][K], granule runs along k
-                    const int cj = j / (BK / 4), kq = (j % (BK / 4)) * 4;
-                    const long gj = n0 + cj, gk = k0 + kq;
-                    if (gj < N) {
-                        const float *src = B + gj * K + gk;
-                        if (vec_b && gk + 3 < kend) v = *reinterpret_cast<const float4 *>(src);
-                        else {
-                            if (gk < kend) v.x = src[0];
-                            if (gk + 1 < kend) v.y = src[1];
-                            if (gk + 2 < kend) v.z = src[2];
-                            if (gk + 3 < kend) v.w = src[3];
-                        }
-                    }
-                }
-            }
-            rb[p] = v;
+            if (NB % 256 == 0 || j < NB) *reinterpret_cast<floatx4 *>(&Bs[buf][j / (BN / 4)][(j % (BN / 4)) * 4]) = rb[p];
         }
     };
 
-    auto stage = [&]() {
-#pragma unroll
-        for (int p = 0; p < GA; ++p) {
-            const int j = t + 256 * p;
-            if (NA % 256 != 0 && j >= NA) continue;
-            if constexpr (!TA) {
-                const int row = j / (BK / 4), kq = (j % (BK / 4)) * 4;
-                As[kq + 0][row] = ra[p].x; As[kq + 1][row] = ra[p].y;
-                As[kq + 2][row] = ra[p].z; As[kq + 3][row] = ra[p].w;
-            } else {
-                const int kk = j / (BM / 4), iq = (j % (BM / 4)) * 4;
-                *reinterpret_cast<float4 *>(&As[kk][iq]) = ra[p];
-            }
-        }
-#pragma unroll
-        for (int p = 0; p < GB; ++p) {
-            const int j = t + 256 * p;
-            if (NB % 256 != 0 && j >= NB) continue;
-            if constexpr (!TB) {
-                const int kk = j / (BN / 4), jq = (j % (BN / 4)) * 4;
-                *reinterpret_cast<float4 *>(&Bs[kk][jq]) = rb[p];
-            } else {
-                const int cj = j / (BK / 4), kq = (j % (BK / 4)) * 4;
-                Bs[kq + 0][cj] = rb[p].x; Bs[kq + 1][cj] = rb[p].y;
-                Bs[kq + 2][cj] = rb[p].z; Bs[kq + 3][cj] = rb[p].w;
-            }
-        }
-    };
-
-    using AccT = typename std::conditional<F64, doublex4, floatx16>::type;
-    constexpr int NV = F64 ? 4 : 16;
-    AccT acc[TM][TN];
-#pragma unroll
-    for (int a = 0; a < TM; ++a)
-#pragma unroll
-        for (int b = 0; b < TN; ++b)
-#pragma unroll
-            for (int v = 0; v < NV; ++v) acc[a][b][v] = 0;
-
-    if (kbeg < kend) {
-        fetch(kbeg);
-        stage();
-        __syncthreads();
-        for (long k0 = kbeg; k0 < kend; k0 += BK) {
-            const bool more = k0 + BK < kend;
-            if (more) fetch(k0 + BK);
-            // operands of k-step s+1 are read (and widened) before the matrix instructions of step s
-            float a[2][TM], b[2][TN];
-            auto read = [&](int kk, float (&av)[TM], float (&bv)[TN]) __attribute__((always_inline)) {
-#pragma unroll
-                for (int x = 0; x < TM; ++x) av[x] = As[kk + lk][(wm * TM + x) * UNIT + lu];
-#pragma unroll
-                for (int y = 0; y < TN; ++y) bv[y] = Bs[kk + lk][(wn * TN + y) * UNIT + lu];
-            };
-            auto mma = [&](const float (&av)[TM], const float (&bv)[TN]) __attribute__((always_inline)) {
-#pragma unroll
-                for (int x = 0; x < TM; ++x)
-#pragma unroll
-                    for (int y = 0; y < TN; ++y) {
-                        if constexpr (F64)
-                            acc[x][y] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)av[x], (double)bv[y], acc[x][y], 0, 0, 0);
-                        else
-                            acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[x], bv[y], acc[x][y], 0, 0, 0);
-                    }
-            };
-            read(0, a[0], b[0]);
-#pragma unroll
-            for (int s2 = 0; s2 < BK / KSTEP; s2 += 2) {
-                read((s2 + 1) * KSTEP, a[1], b[1]);
-                __builtin_amdgcn_sched_barrier(0);
-                mma(a[0], b[0]);
-                __builtin_amdgcn_sched_barrier(0);
-                if (s2 + 2 < BK / KSTEP) read((s2 + 2) * KSTEP, a[0], b[0]);
-                __builtin_amdgcn_sched_barrier(0);
-                mma(a[1], b[1]);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            __syncthreads();
-            if (more) {
-                stage();
-                __syncthreads();
-            }
-        }
-    }
-
-    // Accumulator register v of lane (lk, lu) holds column lu and
-    //   fp32 32x32: row 8*(v/4) + 4*lk + v%4      fp64 16x16: row 4*v + lk
+    doublex4 acc[TM][TN];
 #pragma unroll
     for (int x = 0; x < TM; ++x)
 #pragma unroll
-        for (int y = 0; y < TN; ++y) {
-            const int gj = n0 + (wn * TN + y) * UNIT + lu;
-            if (gj >= N) continue;
+        for (int y = 0; y < TN; ++y) acc[x][y] = doublex4{0.0, 0.0, 0.0, 0.0};
+
+    auto read = [&](int buf, int kk, float (&av)[TM], float (&bv)[TN]) __attribute__((always_inline)) {
+        const float *pa = &As[buf][kk + lk][(wm * 16 + lu) * TM];
+        const float *pb = &Bs[buf][kk + lk][(wn * 16 + lu) * TN];
+        if constexpr (TM == 4) { const floatx4 q = *reinterpret_cast<const floatx4 *>(pa); av[0] = q.x; av[1] = q.y; av[2] = q.z; av[3] = q.w; }
+        else if constexpr (TM == 2) { const float2 q = *reinterpret_cast<const float2 *>(pa); av[0] = q.x; av[1] = q.y; }
+        else av[0] = *pa;
+        if constexpr (TN == 4) { const floatx4 q = *reinterpret_cast<const floatx4 *>(pb); bv[0] = q.x; bv[1] = q.y; bv[2] = q.z; bv[3] = q.w; }
+        else if constexpr (TN == 2) { const float2 q = *reinterpret_cast<const float2 *>(pb); bv[0] = q.x; bv[1] = q.y; }
+        else bv[0] = *pb;
+    };
+    auto mma = [&](const float (&av)[TM], const float (&bv)[TN]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int v = 0; v < NV; ++v) {
-                const int r = F64 ? 4 * v + lk : 8 * (v / 4) + 4 * lk + (v % 4);
-                const int gi = m0 + (wm * TM + x) * UNIT + r;
-                if (gi >= M) continue;
-                if constexpr (F64) {
-                    static_cast<double *>(Cv)[((size_t)split * M + gi) * N + gj] = acc[x][y][v];
-                } else {
-                    float o = acc[x][y][v] + (bias ? bias[gj] : 0.f);
-                    if (relu) o = fmaxf(o, 0.f);
-                    static_cast<float *>(Cv)[(size_t)gi * N + gj] = o;
-                }
-            }
+        for (int x = 0; x < TM; ++x)
+#pragma unroll
+            for (int y = 0; y < TN; ++y)
+                acc[x][y] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)av[x], (double)bv[y], acc[x][y], 0, 0, 0);
+    };
+    auto multiply = [&](int buf) __attribute__((always_inline)) {
+        float a0[TM], b0[TN], a1[TM], b1[TN];
+        read(buf, 0, a0, b0);
+#pragma unroll
+        for (int s2 = 0; s2 < BK / KSTEP; s2 += 2) {
+            read(buf, (s2 + 1) * KSTEP, a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (s2 + 2 < BK / KSTEP) read(buf, (s2 + 2) * KSTEP, a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    if (kbeg < kend) {
+        fetch(kbeg);
+        stage(0);
+        __syncthreads();
+        int buf = 0;
+        for (long k0 = kbeg; k0 < kend; k0 += BK) {
+            const bool more = k0 + BK < kend;
+            if (more) fetch(k0 + BK);
+            multiply(buf);
+            if (more) stage(buf ^ 1);
+            __syncthreads();
+            buf ^= 1;
+        }
+    }
+
+    // Accumulator register v of lane (lk, lu) of tile (x, y): row 4 v + lk, column lu of the 16 x 16 tile,
+    // i.e. output row m0 + (wm * 16 + 4 v + lk) * TM + x, output column n0 + (wn * 16 + lu) * TN + y
+    double *out = P + (size_t)split * M * N;
+    const int gj0 = n0 + (wn * 16 + lu) * TN;
+#pragma unroll
+    for (int x = 0; x < TM; ++x)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int gi = m0 + (wm * 16 + 4 * v + lk) * TM + x;
+            if (gi >= M) continue;
+#pragma unroll
+            for (int y = 0; y < TN; ++y)
+                if (gj0 + y < N) out[(size_t)gi * N + gj0 + y] = acc[x][y][v];
         }
 }
 
@@ -634,8 +563,12 @@ size_t gemm_workspace_bytes(int ta, int tb, int64_t M, int64_t N, int64_t K) {
     }
 #define GEMM_F64_CASE(WM_, WN_, TM_, TN_)                                                                        \
     if (tl.wm == WM_ && tl.wn == WN_ && tl.tm == TM_ && tl.tn == TN_) {                                          \
-        hipLaunchKernelGGL((gemm_kernel<true, false, WM_, WN_, TM_, TN_>), grid, dim3(256), 0, st, (int)M,       \
-                           (int)N, (long)K, A, B, workspace, nullptr, 0, k_chunk, tiles_m, tiles_n, splits,      \
+        constexpr int BM_ = WM_ * TM_ * 16, BN_ = WN_ * TN_ * 16;                                                \
+        constexpr int LA_ = BM_ + (TM_ == 1 ? (80 - BM_ % 64) % 64 : TM_ == 2 ? (96 - BM_ % 64) % 64 : 4);       \
+        constexpr int LB_ = BN_ + (TN_ == 1 ? (80 - BN_ % 64) % 64 : TN_ == 2 ? (96 - BN_ % 64) % 64 : 4);       \
+        const size_t lds = (size_t)2 * BK * (LA_ + LB_) * sizeof(float);                                         \
+        hipLaunchKernelGGL((gemm_tn_f64_kernel<WM_, WN_, TM_, TN_>), grid, dim3(256), lds, st, (int)M, (int)N,   \
+                           (long)K, A, B, static_cast<double *>(workspace), k_chunk, tiles_m, tiles_n, splits,   \
                            vec_a, vec_b);                                                                        \
         launched = true;                                                                                         \
     }

@@ -306,7 +306,8 @@ gnn_status_t gnn_sddmm_csr(int32_t n, int32_t nnz, const int32_t *erow, const in
                            void *hip_stream);
 
 /*
- * gnn_gemm - C = op(A) op(B), fp32 with fp32 accumulation on the matrix cores.
+ * gnn_gemm - C = op(A) op(B) on the matrix cores: fp32 operands and results; fp32 accumulation,
+ *   except that the transposed-A form accumulates in fp64 (its reduction runs over all nodes).
  *   trans_a == 0: A is [M, K] else A is [K, M] and used transposed (then K may be huge:
  *   the product is split along K and reduced in a fixed order; deterministic).
  *   trans_b == 0: B is [K, N] else B is [N, K].  C is [M, N].  All row-major, dense (ld = columns).

@@ -28,6 +28,8 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef double doublex4 __attribute__((ext_vector_type(4)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));   // a native vector: loads and stores stay typed
 
+constexpr int kGemmGeneral = 0, kGemmInterior = 1, kGemmEdge = 2;
+
 constexpr int BK = 32;
 
 // ---- fp64: P[chunk][M][N] (double) = A[K][M]^T * B[K][N] over one chunk of K ---------------
@@ -199,16 +201,21 @@ gemm_tn_f64_kernel(int M, int N, long K, const float *__restrict__ A, const floa
 // after those of step i+1 (one barrier per step), so the loads of the next output tile are
 // in flight while the current tile is finished and stored.
 //
-// FAST: every tile is full, K is a multiple of the k-tile and all rows are 16-byte aligned.
-// The step loop then has no branch around a load: the fetch cursor stops at the last step
-// instead of being switched off (the last k-tile is simply read again), which lets the
-// compiler count outstanding loads exactly and wait only for the older of the two register
-// sets.  The general form guards every access and takes whatever waits that needs.
-template <int WM, int WN, int TM, int TN, int BKT, bool FAST>
+// Three instantiations.  The two fast ones need 16-byte aligned operand rows (K a multiple of 4)
+// and have no branch around a load in the step loop: the bias of the current tile is re-loaded
+// every step, and the fetch cursor stops at the last step instead of being switched off (the
+// last k-tile is simply read again), so the compiler counts outstanding loads exactly and waits
+// only for the older of the two register sets.  kGemmInterior: M, N, K are multiples of the
+// tile, every load is a uniform base plus a fixed lane offset.  kGemmEdge: any M, N, K; loads
+// past an edge are redirected to valid addresses (see fetch).  kGemmGeneral guards every access
+// (unaligned rows) and takes whatever waits that needs.
+
+template <int WM, int WN, int TM, int TN, int BKT, int MODE>
 __global__ void __launch_bounds__(256)
 gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *__restrict__ Bt,
                 float *__restrict__ C, const float *__restrict__ bias, int relu, int tiles_m, int tiles_n,
                 int tiles_per_block, int vec_a, int vec_b) {
+    constexpr bool FAST = MODE != kGemmGeneral;
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = BKT, LD = BK + 4;
     constexpr int RPP = 256 / (BK / 4);                   // tile rows covered by one pass of the 256 threads
     constexpr int NJ = BK / 8;                            // 16-byte operand reads per tile row and lane
@@ -265,19 +272,39 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
             reg[p] = v;
         }
     };
-    auto fetch = [&](floatx4 (&ra)[GA], floatx4 (&rb)[GB]) __attribute__((always_inline)) {
+    bool kin0 = true, kin1 = true;                         // per register set: the lane's granule lies inside K
+    auto fetch = [&](floatx4 (&ra)[GA], floatx4 (&rb)[GB], bool &kin) __attribute__((always_inline)) {
         const int m0 = ftm * BM, n0 = ftn * BN, k0 = fkt * BK;
         const float *pa = A + (size_t)m0 * K + k0;         // uniform bases of the tile being fetched
         const float *pb = Bt + (size_t)n0 * K + k0;
         if constexpr (FAST) {
+            kin = true;
+            if constexpr (MODE == kGemmInterior) {
+                // every tile is full: one uniform base per load plus the lane's fixed offset
 #pragma unroll
-            for (int p = 0; p < GA; ++p)
-                if (BM % RPP == 0 || lrow + RPP * p < BM)
-                    ra[p] = *reinterpret_cast<const floatx4 *>(reinterpret_cast<const char *>(pa + (size_t)p * RPP * K) + lane_ld);
+                for (int p = 0; p < GA; ++p)
+                    if (BM % RPP == 0 || lrow + RPP * p < BM)
+                        ra[p] = *reinterpret_cast<const floatx4 *>(reinterpret_cast<const char *>(pa + (size_t)p * RPP * K) + lane_ld);
 #pragma unroll
-            for (int p = 0; p < GB; ++p)
-                if (BN % RPP == 0 || lrow + RPP * p < BN)
-                    rb[p] = *reinterpret_cast<const floatx4 *>(reinterpret_cast<const char *>(pb + (size_t)p * RPP * K) + lane_ld);
+                for (int p = 0; p < GB; ++p)
+                    if (BN % RPP == 0 || lrow + RPP * p < BN)
+                        rb[p] = *reinterpret_cast<const floatx4 *>(reinterpret_cast<const char *>(pb + (size_t)p * RPP * K) + lane_ld);
+            } else {
+                // ragged M, N or K: rows past the matrix re-read the last row (their products land in
+                // accumulator rows that are never stored); a granule past K re-reads column 0 and is zeroed
+                // on its way to LDS.  The same loads for every tile, none behind a branch, none out of bounds.
+                const int gk = k0 + lkq;
+                kin = gk < K;
+                const float *ka = A + (kin ? gk : 0), *kb = Bt + (kin ? gk : 0);
+#pragma unroll
+                for (int p = 0; p < GA; ++p)
+                    if (BM % RPP == 0 || lrow + RPP * p < BM)
+                        ra[p] = *reinterpret_cast<const floatx4 *>(ka + (size_t)min(m0 + lrow + RPP * p, M - 1) * K);
+#pragma unroll
+                for (int p = 0; p < GB; ++p)
+                    if (BN % RPP == 0 || lrow + RPP * p < BN)
+                        rb[p] = *reinterpret_cast<const floatx4 *>(kb + (size_t)min(n0 + lrow + RPP * p, N - 1) * K);
+            }
         } else {
             const bool kfull = k0 + BK <= K;
             if (kfull && vec_a && m0 + BM <= M && (size_t)BM * K < (1u << 30)) {
@@ -305,13 +332,16 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
             }
         }
     };
-    auto stage = [&](int buf, const floatx4 (&ra)[GA], const floatx4 (&rb)[GB]) __attribute__((always_inline)) {
+    auto stage = [&](int buf, const floatx4 (&ra)[GA], const floatx4 (&rb)[GB], bool kin) __attribute__((always_inline)) {
+        const floatx4 zero = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int p = 0; p < GA; ++p)
-            if (BM % RPP == 0 || lrow + RPP * p < BM) *reinterpret_cast<floatx4 *>(&As[buf][lrow + RPP * p][lkq]) = ra[p];
+            if (BM % RPP == 0 || lrow + RPP * p < BM)
+                *reinterpret_cast<floatx4 *>(&As[buf][lrow + RPP * p][lkq]) = kin ? ra[p] : zero;
 #pragma unroll
         for (int p = 0; p < GB; ++p)
-            if (BN % RPP == 0 || lrow + RPP * p < BN) *reinterpret_cast<floatx4 *>(&Bs[buf][lrow + RPP * p][lkq]) = rb[p];
+            if (BN % RPP == 0 || lrow + RPP * p < BN)
+                *reinterpret_cast<floatx4 *>(&Bs[buf][lrow + RPP * p][lkq]) = kin ? rb[p] : zero;
     };
 
     floatx16 acc[TM][TN];
@@ -377,12 +407,12 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
     auto load_bias = [&]() __attribute__((always_inline)) {
         if constexpr (FAST) {
 #pragma unroll
-            for (int y = 0; y < TN; ++y) bcol[y] = bias_src[ctn * BN + (wn * TN + y) * 32 + l32];
+            for (int y = 0; y < TN; ++y) bcol[y] = bias_src[min(ctn * BN + (wn * TN + y) * 32 + l32, N - 1)];
         }
     };
     auto finish_tile = [&]() __attribute__((always_inline)) {
         const int cm0 = ctm * BM, cn0 = ctn * BN;
-        const bool cfull = FAST || (cm0 + BM <= M && cn0 + BN <= N && (size_t)BM * N < (1u << 30));
+        const bool cfull = cm0 + BM <= M && cn0 + BN <= N && (size_t)BM * N < (1u << 30);
         if (cfull) {
             float *c0 = C + (size_t)(cm0 + wm * TM * 32) * N + cn0 + wn * TN * 32;     // uniform per wavefront
             auto put = [&](int x, int y, int v, float o) __attribute__((always_inline)) {
@@ -416,7 +446,7 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
 #pragma unroll
                 for (int y = 0; y < TN; ++y) {
                     const int gj = cn0 + (wn * TN + y) * 32 + l32;
-                    const float bj = (bias && gj < N) ? bias[gj] : 0.f;
+                    const float bj = FAST ? (bias ? bcol[y] : 0.f) : ((bias && gj < N) ? bias[gj] : 0.f);
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int gi = cm0 + (wm * TM + x) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
@@ -444,17 +474,17 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
     for (int step = -2; step < steps; step += 2) {
         // even step: multiply buffer 0; step+1 is in set 0, fetch step+2 into set 1
         load_bias();
-        fetch(ra1, rb1);
+        fetch(ra1, rb1, kin1);
         if (step >= 0) multiply(0);
-        stage(1, ra0, rb0);
+        stage(1, ra0, rb0, kin0);
         __syncthreads();
         if (step >= 0) after_multiply();
         if (step + 1 >= steps) break;
         // odd step: multiply buffer 1; step+2 is in set 1, fetch step+3 into set 0
         load_bias();
-        fetch(ra0, rb0);
+        fetch(ra0, rb0, kin0);
         if (step >= 0) multiply(1);
-        stage(0, ra1, rb1);
+        stage(0, ra1, rb1, kin1);
         __syncthreads();
         if (step >= 0) after_multiply();
     }
@@ -548,16 +578,21 @@ size_t gemm_workspace_bytes(int ta, int tb, int64_t M, int64_t N, int64_t K) {
     if (tl.wm == WM_ && tl.wn == WN_ && tl.tm == TM_ && tl.tn == TN_) {                                     \
         constexpr int BM_ = WM_ * TM_ * 32, BN_ = WN_ * TN_ * 32;                                           \
         const size_t lds = (size_t)2 * (BM_ + BN_) * (32 + 4) * sizeof(float);                              \
-        const bool fast = vec_a && vec_b && K > 0 && M % BM_ == 0 && N % BN_ == 0 && K % 32 == 0 &&         \
-                          (size_t)BM_ * K < (1u << 30) && (size_t)BN_ * K < (1u << 30) &&                   \
-                          (size_t)BM_ * N < (1u << 30);                                                     \
-        if (fast)                                                                                           \
-            hipLaunchKernelGGL((gemm_f32_kernel<WM_, WN_, TM_, TN_, 32, true>), grid, dim3(256), lds, st,   \
-                               (int)M, (int)N, (int)K, A, Bt, C, bias, relu, tiles_m, tiles_n,              \
+        const bool aligned = vec_a && vec_b && K > 0;                                                       \
+        const bool interior = aligned && M % BM_ == 0 && N % BN_ == 0 && K % 32 == 0 &&                     \
+                              (size_t)BM_ * K < (1u << 30) && (size_t)BN_ * K < (1u << 30) &&               \
+                              (size_t)BM_ * N < (1u << 30);                                                 \
+        if (interior)                                                                                       \
+            hipLaunchKernelGGL((gemm_f32_kernel<WM_, WN_, TM_, TN_, 32, kGemmInterior>), grid, dim3(256),   \
+                               lds, st, (int)M, (int)N, (int)K, A, Bt, C, bias, relu, tiles_m, tiles_n,     \
+                               tiles_per_block, vec_a, vec_b);                                              \
+        else if (aligned)                                                                                   \
+            hipLaunchKernelGGL((gemm_f32_kernel<WM_, WN_, TM_, TN_, 32, kGemmEdge>), grid, dim3(256), lds,  \
+                               st, (int)M, (int)N, (int)K, A, Bt, C, bias, relu, tiles_m, tiles_n,          \
                                tiles_per_block, vec_a, vec_b);                                              \
         else                                                                                                \
-            hipLaunchKernelGGL((gemm_f32_kernel<WM_, WN_, TM_, TN_, 32, false>), grid, dim3(256), lds, st,  \
-                               (int)M, (int)N, (int)K, A, Bt, C, bias, relu, tiles_m, tiles_n,              \
+            hipLaunchKernelGGL((gemm_f32_kernel<WM_, WN_, TM_, TN_, 32, kGemmGeneral>), grid, dim3(256),    \
+                               lds, st, (int)M, (int)N, (int)K, A, Bt, C, bias, relu, tiles_m, tiles_n,     \
                                tiles_per_block, vec_a, vec_b);                                              \
         launched = true;                                                                                    \
     }

@@ -326,9 +326,13 @@ def main():
         tot_ms += cnt * avg
         launches += cnt
     achieved = tot_bytes / tot_ms / 1e6          # GB/s over all SpMM launches of one step
+    traffic = measured_traffic(w.name, launch_widths)
     roofline = {"bound": "hbm", "kernel": "spmm_seg_kernel", "achieved": round(achieved, 1), "peak": 8000.0,
                 "unit": "GB/s", "frac": round(achieved / 8000.0, 4),
-                "traffic": measured_traffic(w.name, launch_widths),
+                "traffic": traffic,
+                # the same launches priced by the bytes the L2s actually exchanged with the fabric (rocprofv3)
+                "traffic_GBps": None if traffic is None else round(traffic * launches / tot_ms / 1e6, 1),
+                "traffic_frac": None if traffic is None else round(traffic * launches / tot_ms / 1e6 / 8000.0, 4),
                 "launches_per_step": launches,
                 "bytes_per_launch": {str(f): per_width[f]["bytes"] for f in widths},
                 "avg_ms_per_launch": {str(f): round(per_width[f]["avg_ms"], 5) for f in widths},

@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--hidden", type=int, default=8, help="gatnet: features per head of both layers (paper: 8..128)")
     ap.add_argument("--selection", default="rule", choices=["rule", "calibrated"],
                     help="GCN AUTO plans: the paper's width rule or the measured SpMM time model")
+    ap.add_argument("--aggregator", default="gcn", choices=["gcn", "mean", "gin"],
+                    help="GCN workloads: entry values of the propagation matrix (same layer, same schemes)")
     ap.add_argument("--constant-input", action="store_true",
                     help="GCN: promise a constant X, so that the cached A'X is computed once")
     ap.add_argument("--scale", type=int, default=None, help="override the R-MAT scale (debug)")
@@ -237,7 +239,8 @@ def main():
     need_dx = not args.no_input_grad
 
     dev = "cuda"
-    g = graphs.gcn_graph(w.rowptr, w.col, dev, symmetric=True)
+    agg = {"gcn": B.GNN_AGG_GCN_SYM, "mean": B.GNN_AGG_MEAN, "gin": B.GNN_AGG_GIN_SUM}[args.aggregator]
+    g = graphs.gcn_graph(w.rowptr, w.col, dev, symmetric=True, aggregator=agg, eps=0.1)
     n, q = g.n, g.nnz
     X = torch.from_numpy(w.tensors["X"]).to(dev)
 
@@ -344,7 +347,8 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         rp, c, deg = oracle.add_self_loops_degree(w.rowptr, w.col)
-        val = oracle.gcn_normalize(rp, c, deg)
+        val = oracle.gcn_normalize(rp, c, deg) if args.aggregator == "gcn" else \
+            oracle.aggregator_weights(rp, c, deg, args.aggregator, 0.1)
         t0 = time.perf_counter()
         for k in f_outs:
             oracle.gcn_forward(rp, c, val, w.tensors["X"], w.tensors[f"W{k}"])
@@ -375,7 +379,8 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: R-MAT/ER graph n={n}, nnz={q} (self-loops incl.), F_in={f_in}, "
                                f"F_out={list(f_outs)}, GCN single layer fwd+bwd, scheme={args.scheme}, "
-                               f"input_grad={need_dx}, selection={args.selection}, constant_input={args.constant_input}",
+                               f"input_grad={need_dx}, selection={args.selection}, constant_input={args.constant_input}, "
+                               f"aggregator={args.aggregator}",
                    "schemes": {str(L["k"]): {"order": int(L["plan"].info.order), "bwd": int(L["plan"].info.bwd),
                                              "cache": int(L["plan"].info.cache)} for L in layers}},
         "roofline": roofline,

@@ -256,6 +256,19 @@ gnn_status_t gnn_gcn_normalize(int32_t n, const int32_t *rowptr, const int32_t *
                                float *val_out, void *hip_stream);
 
 /*
+ * gnn_aggregator_weights - entry values for the other layers with the same chained product A' X Theta
+ * (Sec. 3.1 "Generalizability"; App. "GCN Forward Pass": mean aggregation is D A X Theta), on the
+ * pattern of A + I with the degrees written by gnn_add_self_loops_degree:
+ *   GNN_AGG_GCN_SYM  1 / sqrt(deg_i deg_j)            (what gnn_gcn_normalize writes)
+ *   GNN_AGG_MEAN     1 / deg_i                         (row-normalised: mean over N(i) and i itself)
+ *   GNN_AGG_GIN_SUM  1, and 1 + eps on the diagonal    (the sum aggregation of a GIN layer)
+ * The mean weights are not symmetric: the graph then needs its CSC arrays (symmetric = 0) for backward.
+ */
+typedef enum { GNN_AGG_GCN_SYM = 0, GNN_AGG_MEAN = 1, GNN_AGG_GIN_SUM = 2 } gnn_aggregator_t;
+gnn_status_t gnn_aggregator_weights(gnn_aggregator_t kind, float eps, int32_t n, const int32_t *rowptr,
+                                    const int32_t *col, const int32_t *deg, float *val_out, void *hip_stream);
+
+/*
  * gnn_csr_transpose - CSC arrays of a CSR matrix (App. D.1): colptr_out [n+1], row_out [nnz]
  * ascending inside every column, perm_out [nnz] (CSC slot -> CSR slot).  Deterministic:
  * a stable radix sort of the row-major entries by column.

@@ -123,6 +123,19 @@ def gcn_normalize(rowptr, col, deg):
     return val
 
 
+def aggregator_weights(rowptr, col, deg, kind, eps=0.0):
+    """Entry values of the other layers with the same chained product (Sec. 3.1 "Generalizability"):
+    "mean": D^-1 (A + I), every entry of row i is 1 / deg_i;  "gin": A + (1 + eps) I."""
+    rowptr = np.asarray(rowptr)
+    col = np.asarray(col)
+    rows = np.repeat(np.arange(rowptr.size - 1), np.diff(rowptr))
+    if kind == "mean":
+        return 1.0 / np.asarray(deg, np.float64)[rows]
+    if kind == "gin":
+        return np.where(col == rows, 1.0 + eps, 1.0)
+    raise ValueError(kind)
+
+
 def csr_transpose(rowptr, col):
     """CSC arrays of the same matrix + perm (CSC slot -> CSR slot).  All int32."""
     rowptr, prp = _i32(rowptr)

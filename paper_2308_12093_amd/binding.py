@@ -33,6 +33,7 @@ GNN_BWD_AUTO, GNN_BWD_FUSED_PROPAGATE, GNN_BWD_SPLIT_PROPAGATE = 0, 1, 2
 (GNN_CACHE_AUTO, GNN_CACHE_NONE, GNN_CACHE_AX, GNN_CACHE_GAT_FEAT, GNN_CACHE_GAT_FEAT_NODEATT,
  GNN_CACHE_GAT_FEAT_EDGE) = range(6)
 GNN_SELECT_PAPER_RULE, GNN_SELECT_CALIBRATED = 0, 1
+GNN_AGG_GCN_SYM, GNN_AGG_MEAN, GNN_AGG_GIN_SUM = 0, 1, 2
 
 _vp = ctypes.c_void_p
 _i32 = ctypes.c_int32
@@ -76,6 +77,7 @@ _PROTOS = {
     "gnn_add_self_loops_degree": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(_i32), _vp, _sz, _vp]),
     "gnn_scan_workspace_bytes": (_sz, [_i32]),
     "gnn_gcn_normalize": (ctypes.c_int, [_i32, _vp, _vp, _vp, _vp, _vp]),
+    "gnn_aggregator_weights": (ctypes.c_int, [ctypes.c_int, ctypes.c_float, _i32, _vp, _vp, _vp, _vp, _vp]),
     "gnn_csr_transpose": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "gnn_transpose_workspace_bytes": (_sz, [_i32, _i32]),
     "gnn_expand_ptr": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp]),
@@ -224,6 +226,11 @@ def gnn_add_self_loops_degree(n, nnz, rowptr, col, rowptr_out, col_out, deg_out,
 def gnn_gcn_normalize(n, rowptr, col, deg, val_out):
     _check(lib.gnn_gcn_normalize(n, _ptr(rowptr), _ptr(col), _ptr(deg), _ptr(val_out), _stream()),
            "gnn_gcn_normalize")
+
+
+def gnn_aggregator_weights(kind, eps, n, rowptr, col, deg, val_out):
+    _check(lib.gnn_aggregator_weights(int(kind), float(eps), n, _ptr(rowptr), _ptr(col), _ptr(deg), _ptr(val_out),
+                                      _stream()), "gnn_aggregator_weights")
 
 
 def gnn_transpose_workspace_bytes(n, nnz):

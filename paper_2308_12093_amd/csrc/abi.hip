@@ -160,7 +160,15 @@ gnn_status_t gnn_gcn_normalize(int32_t n, const int32_t *rowptr, const int32_t *
                                float *val_out, void *hip_stream) {
     if (n < 0 || !rowptr) return GNN_ERR_INVALID_ARG;
     if (n > 0 && (!deg || !col || !val_out)) return GNN_ERR_INVALID_ARG;
-    return normalize_launch(n, rowptr, col, deg, val_out, as_stream(hip_stream));
+    return normalize_launch(n, rowptr, col, deg, val_out, GNN_AGG_GCN_SYM, 0.f, as_stream(hip_stream));
+}
+
+gnn_status_t gnn_aggregator_weights(gnn_aggregator_t kind, float eps, int32_t n, const int32_t *rowptr,
+                                    const int32_t *col, const int32_t *deg, float *val_out, void *hip_stream) {
+    if (kind != GNN_AGG_GCN_SYM && kind != GNN_AGG_MEAN && kind != GNN_AGG_GIN_SUM) return GNN_ERR_INVALID_ARG;
+    if (n < 0 || !rowptr) return GNN_ERR_INVALID_ARG;
+    if (n > 0 && (!deg || !col || !val_out)) return GNN_ERR_INVALID_ARG;
+    return normalize_launch(n, rowptr, col, deg, val_out, kind, eps, as_stream(hip_stream));
 }
 
 size_t gnn_transpose_workspace_bytes(int32_t n, int32_t nnz) {

@@ -81,7 +81,7 @@ size_t transpose_workspace_bytes(int n, int nnz);
 gnn_status_t add_self_loops_launch(int n, int nnz, const int32_t *rowptr, const int32_t *col, int32_t *rowptr_out,
                                    int32_t *col_out, int32_t *deg_out, void *workspace, hipStream_t st);
 gnn_status_t normalize_launch(int n, const int32_t *rowptr, const int32_t *col, const int32_t *deg, float *val,
-                              hipStream_t st);
+                              int kind, float eps, hipStream_t st);
 gnn_status_t transpose_launch(int n, int nnz, const int32_t *rowptr, const int32_t *col, int32_t *colptr,
                               int32_t *row, int32_t *perm, void *workspace, hipStream_t st);
 gnn_status_t expand_ptr_launch(int n, int nnz, const int32_t *ptr, int32_t *out, hipStream_t st);

@@ -110,13 +110,19 @@ selfloop_fill_kernel(int n, const int32_t *__restrict__ rowptr, const int32_t *_
 
 __global__ void __launch_bounds__(256)
 normalize_kernel(int n, const int32_t *__restrict__ rowptr, const int32_t *__restrict__ col,
-                 const int32_t *__restrict__ deg, float *__restrict__ val) {
+                 const int32_t *__restrict__ deg, float *__restrict__ val, int kind, float eps) {
     const int i = blockIdx.x * 4 + threadIdx.x / 64;
     const int lane = threadIdx.x % 64;
     if (i >= n) return;
     const float di = (float)deg[i];
-    for (int x = rowptr[i] + lane; x < rowptr[i + 1]; x += 64)
-        val[x] = 1.0f / sqrtf(di * (float)deg[col[x]]);
+    for (int x = rowptr[i] + lane; x < rowptr[i + 1]; x += 64) {
+        const int j = col[x];
+        float v;
+        if (kind == GNN_AGG_GCN_SYM) v = 1.0f / sqrtf(di * (float)deg[j]);
+        else if (kind == GNN_AGG_MEAN) v = 1.0f / di;
+        else v = j == i ? 1.0f + eps : 1.0f;
+        val[x] = v;
+    }
 }
 
 __global__ void __launch_bounds__(256)
@@ -264,9 +270,10 @@ gnn_status_t add_self_loops_launch(int n, int nnz, const int32_t *rowptr, const 
 }
 
 gnn_status_t normalize_launch(int n, const int32_t *rowptr, const int32_t *col, const int32_t *deg, float *val,
-                              hipStream_t st) {
+                              int kind, float eps, hipStream_t st) {
     if (n <= 0) return GNN_OK;
-    hipLaunchKernelGGL(normalize_kernel, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, n, rowptr, col, deg, val);
+    hipLaunchKernelGGL(normalize_kernel, dim3((unsigned)ceil_div(n, 4)), dim3(256), 0, st, n, rowptr, col, deg, val,
+                       kind, eps);
     return launch_status();
 }
 

@@ -45,17 +45,24 @@ def expand(n, ptr, nnz):
     return out[:nnz]
 
 
-def gcn_graph(rowptr_np, col_np, device="cuda", symmetric=True, balanced=True) -> B.Graph:
-    """Raw pattern (host) -> normalised graph on the device, ready for gcn_layer_fwd / bwd.
+def gcn_graph(rowptr_np, col_np, device="cuda", symmetric=True, balanced=True,
+              aggregator=B.GNN_AGG_GCN_SYM, eps=0.0) -> B.Graph:
+    """Raw pattern (host) -> weighted graph on the device, ready for gcn_layer_fwd / bwd.
 
-    symmetric=True promises an undirected input, so A' is its own transpose and
-    no CSC arrays are built; otherwise the transpose, its values and its
-    expanded column index are built as well."""
+    symmetric=True promises an undirected input whose weights are symmetric too, so A' is its
+    own transpose and no CSC arrays are built; otherwise the transpose, its values and its
+    expanded column index are built as well.  `aggregator` picks the entry values
+    (gnn_aggregator_weights); mean weights are never symmetric."""
     n = rowptr_np.size - 1
     rp, c, deg = add_self_loops(n, _dev_i32(rowptr_np, device), _dev_i32(col_np, device))
     nnz = int(c.numel())
     val = torch.empty(max(nnz, 1), dtype=torch.float32, device=device)[:nnz]
-    B.gnn_gcn_normalize(n, rp, c, deg, val)
+    if aggregator == B.GNN_AGG_GCN_SYM:
+        B.gnn_gcn_normalize(n, rp, c, deg, val)
+    else:
+        B.gnn_aggregator_weights(aggregator, eps, n, rp, c, deg, val)
+        if aggregator == B.GNN_AGG_MEAN:
+            symmetric = False
     erow = expand(n, rp, nnz) if balanced else None
     if symmetric:
         g = B.Graph(n, rp, c, val, erow, symmetric=True)

@@ -176,3 +176,32 @@ def test_constant_input_computes_the_cached_product_once(B, G):
     y, dw = step(X_other, W2)                                  # after a reset the new input counts
     assert_close(y, oracle.gcn_forward(rp, c, val, X_other, W2), "after reset Y")
     assert_close(dw, oracle.gcn_backward(rp, c, val, X_other, W2, dY, None, False)[0], "after reset dW")
+
+
+@pytest.mark.parametrize("kind,directed", [("mean", False), ("mean", True), ("gin", False), ("gin", True)])
+@pytest.mark.parametrize("name", ["auto", "tf_fp", "pf_sp_cache"])
+def test_mean_and_gin_aggregation_run_through_the_same_layer(B, G, kind, directed, name):
+    """Other layers with the same chained product (Sec. 3.1 "Generalizability"): only the entry
+    values differ, so the layer entry points, the orders and the cache are the ones of GCN.
+    Mean weights (1 / deg_i) are not symmetric even on an undirected graph: backward goes through
+    the CSC arrays."""
+    s = synth.streams(51)
+    rowptr, col = synth.rmat_graph(10, 8, directed, s["graph"], s["relabel"])
+    n, m, k = rowptr.size - 1, 40, 24
+    X, W = synth.normal(s["X"], n, m), synth.glorot_uniform(s["W"], (m, k), m, k)
+    b, dY = synth.normal(s["b"], k), synth.normal(s["dY"], n, k)
+    agg = dict(mean=B.GNN_AGG_MEAN, gin=B.GNN_AGG_GIN_SUM)[kind]
+    eps = 0.3
+    g = G.gcn_graph(rowptr, col, symmetric=not directed, aggregator=agg, eps=eps)
+    assert g.c.symmetric == (0 if (directed or kind == "mean") else 1)
+    rp, c, deg = oracle.add_self_loops_degree(rowptr, col)
+    val = oracle.aggregator_weights(rp, c, deg, kind, eps)
+    assert_close(host(g.val), val, f"{kind} weights", tol=1e-6)
+    for need_dx in (True, False):
+        Y, gW, gb, gX, _ = run_layer(B, g, X, W, b, dY, need_dx, False, schemes(B)[name])
+        rY, rW, rb, rX = oracle_layer(rp, c, val, X, W, b, dY, need_dx, False)
+        assert_close(Y, rY, f"{kind} {name} Y")
+        assert_close(gW, rW, f"{kind} {name} dW")
+        assert_close(gb, rb, f"{kind} {name} db")
+        if need_dx:
+            assert_close(gX, rX, f"{kind} {name} dX")

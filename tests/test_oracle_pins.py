@@ -406,6 +406,26 @@ def test_two_layer_gat_with_elu_and_squared_error_against_torch_autograd():
         np.testing.assert_allclose(a, t.grad.numpy().reshape(a.shape), rtol=1e-9, atol=1e-10, err_msg=name)
 
 
+def test_mean_and_gin_weights_against_dense_definitions():
+    """Mean aggregation is D^-1 (A + I) X (rows of the weight matrix sum to one, the layer output is the
+    neighbourhood mean); the GIN sum is (A + (1 + eps) I) X."""
+    rowptr, col = small_graph(n=29, q=120, seed=77, diagonal=False)
+    rp, c, deg = oracle.add_self_loops_degree(rowptr, col)
+    n = rp.size - 1
+    pat = dense_pattern(rp, c)
+    rng = np.random.default_rng(3)
+    X = rng.standard_normal((n, 5))
+    mean = oracle.aggregator_weights(rp, c, deg, "mean")
+    got = oracle.spmm(rp, c, mean, X)
+    ref = np.stack([X[np.flatnonzero(pat[i])].mean(axis=0) for i in range(n)])
+    np.testing.assert_allclose(got, ref, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(np.add.reduceat(mean, rp[:-1]), 1.0, rtol=1e-14)
+    eps = 0.25
+    gin = oracle.aggregator_weights(rp, c, deg, "gin", eps)
+    A_plain = pat - np.eye(n)                                      # the pattern without the added diagonal
+    np.testing.assert_allclose(oracle.spmm(rp, c, gin, X), (1 + eps) * X + A_plain @ X, rtol=1e-13, atol=1e-13)
+
+
 def test_softmax_xent_against_torch():
     rng = np.random.default_rng(4)
     Z = rng.standard_normal((50, 7)) * 3

@@ -352,6 +352,35 @@ sddmm_edge_kernel(long count, int h, int k, const int32_t *__restrict__ erow, co
     D[t] = val ? val[e] * acc : acc;
 }
 
+// The same product for long feature vectors (k >= 32, a multiple of 4): L lanes share one (entry, head)
+// pair, each reading 16 consecutive bytes per pass, so a pair's two rows are read as whole lines;
+// the L partial dot products are added by a fixed butterfly.
+template <int L>
+__global__ void __launch_bounds__(256)
+sddmm_coop_kernel(long pairs, int h, int k, const int32_t *__restrict__ erow, const int32_t *__restrict__ col,
+                  const float *__restrict__ val, const float *__restrict__ Bm, const float *__restrict__ Ct,
+                  float *__restrict__ D) {
+    const long t = (long)blockIdx.x * 256 + threadIdx.x;
+    const long pair = t / L;
+    const int l = (int)(t % L);
+    const bool live = pair < pairs;                           // whole groups of L lanes are live or not
+    float acc = 0.f;
+    long e = 0;
+    if (live) {
+        int p;
+        split_index(pair, pairs, h, e, p);
+        const float *b = Bm + ((size_t)erow[e] * h + p) * k;
+        const float *c = Ct + ((size_t)col[e] * h + p) * k;
+        for (int x = 4 * l; x < k; x += 4 * L) {
+            const float4 u = *reinterpret_cast<const float4 *>(b + x), v = *reinterpret_cast<const float4 *>(c + x);
+            acc = fmaf(u.x, v.x, acc); acc = fmaf(u.y, v.y, acc); acc = fmaf(u.z, v.z, acc); acc = fmaf(u.w, v.w, acc);
+        }
+    }
+#pragma unroll
+    for (int d = L / 2; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, kWave);
+    if (live && l == 0) D[pair] = val ? val[e] * acc : acc;
+}
+
 // g_y_e = alpha_e (g_alpha_e - t_i) * (y_e > 0 ? 1 : beta); gy holds g_alpha on entry
 template <int HV>
 __global__ void __launch_bounds__(256)
@@ -510,6 +539,15 @@ gnn_status_t sddmm_launch(int n, int nnz, const int32_t *erow, const int32_t *co
     const long count = (long)nnz * heads;
     if (count <= 0) return GNN_OK;
     const int vec = f % 4 == 0 && aligned16(B) && aligned16(Ct);
+    if (vec && f >= 32) {
+        // lanes per pair: a quarter of the feature count, 8 .. 32
+        const int L = f >= 128 ? 32 : (f >= 64 ? 16 : 8);
+        const dim3 grid((unsigned)ceil_div(count * L, 256));
+        if (L == 32) hipLaunchKernelGGL(sddmm_coop_kernel<32>, grid, dim3(256), 0, st, count, heads, f, erow, col, val, B, Ct, D);
+        else if (L == 16) hipLaunchKernelGGL(sddmm_coop_kernel<16>, grid, dim3(256), 0, st, count, heads, f, erow, col, val, B, Ct, D);
+        else hipLaunchKernelGGL(sddmm_coop_kernel<8>, grid, dim3(256), 0, st, count, heads, f, erow, col, val, B, Ct, D);
+        return launch_status();
+    }
     hipLaunchKernelGGL(sddmm_edge_kernel, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count, heads, f,
                        erow, col, val, B, Ct, D, vec);
     return launch_status();

@@ -369,7 +369,7 @@ Shape pick_shape(int f, bool vec4) {
     if (sh.lpe > 64) sh.lpe = 64;
     if (!vec4 && sh.lpe < 8) sh.lpe = 8;
     int nt = (chunks + sh.lpe - 1) / sh.lpe;
-    sh.nt = nt <= 1 ? 1 : (nt <= 2 ? 2 : 4);
+    sh.nt = nt <= 1 ? 1 : 2;                               // wider rows take more feature tiles (grid.y)
     sh.tiles_y = (chunks + sh.lpe * sh.nt - 1) / (sh.lpe * sh.nt);
     return sh;
 }
@@ -441,9 +441,8 @@ gnn_status_t spmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *c
     if (g_prof_start) (void)hipEventRecord(g_prof_start, st);
     SPMM_CASE(4, 1, 1, 8) SPMM_CASE(4, 2, 1, 8) SPMM_CASE(4, 4, 1, 8) SPMM_CASE(4, 8, 1, 8)
     SPMM_CASE(4, 16, 1, 8) SPMM_CASE(4, 32, 1, 8) SPMM_CASE(4, 64, 1, 8) SPMM_CASE(4, 64, 2, 4)
-    SPMM_CASE(4, 64, 4, 2)
     SPMM_CASE(1, 8, 1, 8) SPMM_CASE(1, 16, 1, 8) SPMM_CASE(1, 32, 1, 8) SPMM_CASE(1, 64, 1, 8)
-    SPMM_CASE(1, 64, 2, 4) SPMM_CASE(1, 64, 4, 2)
+    SPMM_CASE(1, 64, 2, 4)
     if (!launched) return GNN_ERR_UNSUPPORTED;
     if (g_prof_stop) (void)hipEventRecord(g_prof_stop, st);
     GNN_TRY(launch_status());

@@ -24,6 +24,8 @@ FLAGS = [
     # keep MFMA accumulators in ordinary VGPRs: with the AGPR form the compiler copied all
     # 64 accumulator registers in and out around every k-tile of the persistent GEMM loop
     "-mllvm", "-amdgpu-mfma-vgpr-form=1",
+    # per-kernel register / scratch / LDS figures as remarks: _compile turns scratch use into an error
+    "-Rpass-analysis=kernel-resource-usage",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
@@ -35,10 +37,25 @@ def _compile(src: str) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stderr}")
-    noise = "packed-fp32-ops"
-    warn = "\n".join(l for l in r.stderr.splitlines() if l.strip() and noise not in l)
-    if warn:
-        sys.stderr.write(warn + "\n")
+    # A kernel whose local arrays end up in scratch (private) memory runs several times slower than
+    # the same kernel with them in registers, silently: refuse to build one.
+    kernel, offenders, plain = None, [], []
+    for line in r.stderr.splitlines():
+        if "kernel-resource-usage" in line:
+            if "Function Name:" in line:
+                kernel = line.split("Function Name:")[1].split("[")[0].strip()
+            elif "ScratchSize [bytes/lane]:" in line:
+                size = int(line.split("ScratchSize [bytes/lane]:")[1].split("[")[0])
+                if size > 0:
+                    offenders.append(f"{kernel}: {size} bytes per lane")
+        elif "packed-fp32-ops" not in line and line.strip():
+            plain.append(line)
+    # the remark lines are followed by source excerpts ("  13 | ...", "     | ^"): drop those too
+    plain = [l for l in plain if not l.lstrip().startswith("|") and not (l.strip()[:1].isdigit() and " | " in l)]
+    if offenders:
+        raise RuntimeError(f"{os.path.basename(src)}: kernels with scratch memory:\n  " + "\n  ".join(offenders))
+    if plain:
+        sys.stderr.write("\n".join(plain) + "\n")
     return obj
 
 

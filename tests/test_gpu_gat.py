@@ -257,3 +257,25 @@ def test_config4_full_size(B, G):
         for name in names:
             np.testing.assert_allclose(own[variant][name], own["NONE"][name], rtol=1e-4, atol=1e-4,
                                        err_msg=f"cfg4 {variant} vs NONE: {name}")
+
+
+@pytest.mark.parametrize("n", [1, 3])
+def test_graph_without_edges_attends_to_itself_only(B, G, n):
+    """Every row holds its self-loop only: alpha = 1, so the layer is X Theta + b, the attention
+    parameters get zero gradient and the other gradients are those of a dense layer."""
+    rowptr, col = np.zeros(n + 1, np.int32), np.zeros(0, np.int32)
+    rng = np.random.default_rng(n)
+    m, h, k = 6, 2, 4
+    t = dict(X=rng.standard_normal((n, m), dtype=np.float32), W=rng.standard_normal((m, h * k), dtype=np.float32),
+             a_src=rng.standard_normal((h, k), dtype=np.float32), a_dst=rng.standard_normal((h, k), dtype=np.float32),
+             b=rng.standard_normal(h * k, dtype=np.float32), dY=rng.standard_normal((n, h * k), dtype=np.float32))
+    X64, W64, dY64 = (t[x].astype(np.float64) for x in ("X", "W", "dY"))
+    for variant in VARIANTS:
+        layer = Layer(B, G, rowptr, col, t, h, getattr(B, "GNN_CACHE_" + variant))
+        assert_close(layer.forward(), X64 @ W64 + t["b"], f"{variant} Y")
+        got = layer.backward()
+        assert_close(got["dW"], X64.T @ dY64, f"{variant} dW")
+        assert_close(got["dX"], dY64 @ W64.T, f"{variant} dX")
+        assert_close(got["db"], dY64.sum(axis=0), f"{variant} db")
+        assert_close(got["da_src"], np.zeros((h, k)), f"{variant} da_src")
+        assert_close(got["da_dst"], np.zeros((h, k)), f"{variant} da_dst")

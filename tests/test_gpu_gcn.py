@@ -205,3 +205,23 @@ def test_mean_and_gin_aggregation_run_through_the_same_layer(B, G, kind, directe
         assert_close(gb, rb, f"{kind} {name} db")
         if need_dx:
             assert_close(gX, rX, f"{kind} {name} dX")
+
+
+@pytest.mark.parametrize("n", [1, 2, 65])
+def test_graph_without_edges_reduces_to_a_dense_layer(B, G, n):
+    """Only the added self-loops remain: A' = I, so the layer is X W + b and its gradients are those of
+    a dense layer (closed form, no oracle needed), whatever the scheme."""
+    rowptr, col = np.zeros(n + 1, np.int32), np.zeros(0, np.int32)
+    rng = np.random.default_rng(n)
+    m, k = 12, 20
+    X, W = rng.standard_normal((n, m), dtype=np.float32), rng.standard_normal((m, k), dtype=np.float32)
+    b, dY = rng.standard_normal(k, dtype=np.float32), rng.standard_normal((n, k), dtype=np.float32)
+    g = G.gcn_graph(rowptr, col)
+    assert g.nnz == n and np.allclose(host(g.val), 1.0)
+    X64, W64, dY64 = X.astype(np.float64), W.astype(np.float64), dY.astype(np.float64)
+    for name in ("tf_fp", "pf_sp_cache", "pf_sp_nocache"):
+        Y, gW, gb, gX, _ = run_layer(B, g, X, W, b, dY, True, False, schemes(B)[name])
+        assert_close(Y, X64 @ W64 + b, f"{name} Y")
+        assert_close(gW, X64.T @ dY64, f"{name} dW")
+        assert_close(gb, dY64.sum(axis=0), f"{name} db")
+        assert_close(gX, dY64 @ W64.T, f"{name} dX")

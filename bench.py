@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--scheme", default="auto", choices=["auto", "tf_fp", "pf_sp_nocache", "pf_sp_cache"])
     ap.add_argument("--gat-cache", default="auto", choices=["auto", "none", "feat", "nodeatt", "edge"],
                     help="cfg4 only: GAT caching variant")
+    ap.add_argument("--graph", action="store_true",
+                    help="GCN workloads: record one step in a HIP graph and time its replays (small graphs are launch-bound)")
     ap.add_argument("--no-input-grad", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also print per-F_out / per-scheme timings to stderr")
@@ -280,9 +282,22 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    run = step
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run = graph.replay
+        run()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
@@ -380,7 +395,7 @@ def main():
         "config": {"workload": f"{w.name}: R-MAT/ER graph n={n}, nnz={q} (self-loops incl.), F_in={f_in}, "
                                f"F_out={list(f_outs)}, GCN single layer fwd+bwd, scheme={args.scheme}, "
                                f"input_grad={need_dx}, selection={args.selection}, constant_input={args.constant_input}, "
-                               f"aggregator={args.aggregator}",
+                               f"aggregator={args.aggregator}, hip_graph={args.graph}",
                    "schemes": {str(L["k"]): {"order": int(L["plan"].info.order), "bwd": int(L["plan"].info.bwd),
                                              "cache": int(L["plan"].info.cache)} for L in layers}},
         "roofline": roofline,

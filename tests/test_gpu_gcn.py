@@ -225,3 +225,44 @@ def test_graph_without_edges_reduces_to_a_dense_layer(B, G, n):
         assert_close(gW, X64.T @ dY64, f"{name} dW")
         assert_close(gb, dY64.sum(axis=0), f"{name} db")
         assert_close(gX, dY64 @ W64.T, f"{name} dX")
+
+
+def test_layer_calls_can_be_captured_in_a_hip_graph_and_replayed(B, G):
+    """The layer entry points only enqueue kernels on the caller's stream, so a forward + backward
+    can be recorded once and replayed; every replay (with eager work and synchronisations between
+    them) must reproduce the eager result bit for bit."""
+    s = synth.streams(61)
+    rowptr, col = synth.rmat_graph(10, 8, False, s["graph"], s["relabel"])
+    n, m, k = rowptr.size - 1, 64, 32
+    g = G.gcn_graph(rowptr, col)
+    X, W, dY = dev(synth.normal(s["X"], n, m)), dev(synth.glorot_uniform(s["W"], (m, k), m, k)), dev(synth.normal(s["dY"], n, k))
+    for scheme in ("tf_fp", "pf_sp_cache"):
+        plan = B.Plan(B.GNN_LAYER_GCN, g.n, g.nnz, m, k, **schemes(B)[scheme])
+        ws = B.alloc(plan.info.workspace_bytes)
+        cache = B.alloc(plan.info.cache_bytes) if plan.info.cache_bytes else None
+        e = lambda *sh: torch.full(sh, float("nan"), dtype=torch.float32, device="cuda")
+        Y, dW, dX = e(n, k), e(m, k), e(n, m)
+
+        def step():
+            B.gcn_layer_fwd(plan, g, X, W, None, Y, cache, ws)
+            B.gcn_layer_bwd(plan, g, X, W, None, dY, dW, None, dX, cache, ws)
+
+        step()
+        torch.cuda.synchronize()
+        eager = [host(t) for t in (Y, dW, dX)]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()                                             # warm-up on the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for replay in range(3):
+            for t in (Y, dW, dX):
+                t.fill_(float("nan"))                          # eager work between replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for got, ref, name in zip((Y, dW, dX), eager, ("Y", "dW", "dX")):
+                assert np.array_equal(host(got), ref), f"{scheme} replay {replay}: {name}"

@@ -39,6 +39,8 @@ def parse():
                     help="GCN AUTO plans: the paper's width rule or the measured SpMM time model")
     ap.add_argument("--aggregator", default="gcn", choices=["gcn", "mean", "gin"],
                     help="GCN workloads: entry values of the propagation matrix (same layer, same schemes)")
+    ap.add_argument("--layer", default="gcn", choices=["gcn", "sage"],
+                    help="cfg1/cfg2/cfg5: GCN (the headline) or GraphSAGE, which adds a dense self term X W_self")
     ap.add_argument("--constant-input", action="store_true",
                     help="GCN: promise a constant X, so that the cached A'X is computed once")
     ap.add_argument("--scale", type=int, default=None, help="override the R-MAT scale (debug)")
@@ -254,7 +256,8 @@ def main():
     }
 
     def make_layer(k, scheme, dx):
-        plan = B.Plan(B.GNN_LAYER_GCN, n, q, f_in, k, need_input_grad=dx, constant_input=args.constant_input,
+        kind = B.GNN_LAYER_SAGE if args.layer == "sage" else B.GNN_LAYER_GCN
+        plan = B.Plan(kind, n, q, f_in, k, need_input_grad=dx, constant_input=args.constant_input,
                       selection=B.GNN_SELECT_CALIBRATED if args.selection == "calibrated" else B.GNN_SELECT_PAPER_RULE,
                       **scheme_kw[scheme])
         L = dict(k=k, plan=plan,
@@ -262,15 +265,24 @@ def main():
                  Y=torch.empty((n, k), dtype=torch.float32, device=dev),
                  dW=torch.empty((f_in, k), dtype=torch.float32, device=dev),
                  dX=torch.empty((n, f_in), dtype=torch.float32, device=dev) if dx else None,
+                 Ws=torch.from_numpy(np.ascontiguousarray(w.tensors[f"W{k}"][::-1])).to(dev),   # SAGE self weight
+                 dWs=torch.empty((f_in, k), dtype=torch.float32, device=dev),
                  ws=B.alloc(plan.info.workspace_bytes),
                  cache=B.alloc(plan.info.cache_bytes) if plan.info.cache_bytes else None)
         return L
 
     def fwd(L):
-        B.gcn_layer_fwd(L["plan"], g, X, L["W"], None, L["Y"], L["cache"], L["ws"])
+        if args.layer == "sage":
+            B.sage_layer_fwd(L["plan"], g, X, L["Ws"], L["W"], None, L["Y"], L["cache"], L["ws"])
+        else:
+            B.gcn_layer_fwd(L["plan"], g, X, L["W"], None, L["Y"], L["cache"], L["ws"])
 
     def bwd(L):
-        B.gcn_layer_bwd(L["plan"], g, X, L["W"], None, L["dY"], L["dW"], None, L["dX"], L["cache"], L["ws"])
+        if args.layer == "sage":
+            B.sage_layer_bwd(L["plan"], g, X, L["Ws"], L["W"], None, L["dY"], L["dWs"], L["dW"], None, L["dX"],
+                             L["cache"], L["ws"])
+        else:
+            B.gcn_layer_bwd(L["plan"], g, X, L["W"], None, L["dY"], L["dW"], None, L["dX"], L["cache"], L["ws"])
 
     layers = [make_layer(k, args.scheme, need_dx) for k in f_outs]
 
@@ -366,8 +378,13 @@ def main():
             oracle.aggregator_weights(rp, c, deg, args.aggregator, 0.1)
         t0 = time.perf_counter()
         for k in f_outs:
-            oracle.gcn_forward(rp, c, val, w.tensors["X"], w.tensors[f"W{k}"])
-            oracle.gcn_backward(rp, c, val, w.tensors["X"], w.tensors[f"W{k}"], w.tensors[f"dY{k}"], None, need_dx)
+            Xh, Wh, dYh = w.tensors["X"], w.tensors[f"W{k}"], w.tensors[f"dY{k}"]
+            if args.layer == "sage":
+                oracle.sage_forward(rp, c, val, Xh, Wh[::-1], Wh)
+                oracle.sage_backward(rp, c, val, Xh, Wh[::-1], Wh, dYh, None, need_dx)
+            else:
+                oracle.gcn_forward(rp, c, val, Xh, Wh)
+                oracle.gcn_backward(rp, c, val, Xh, Wh, dYh, None, need_dx)
         dt = time.perf_counter() - t0
         cpu = {"value": edge_feat / dt, "unit": "edge*feat/s", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": f"one full step (fwd+bwd for F_out in {list(f_outs)}) of the same workload, {dt:.1f} s",
@@ -393,9 +410,9 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: R-MAT/ER graph n={n}, nnz={q} (self-loops incl.), F_in={f_in}, "
-                               f"F_out={list(f_outs)}, GCN single layer fwd+bwd, scheme={args.scheme}, "
+                               f"F_out={list(f_outs)}, {args.layer.upper()} single layer fwd+bwd, scheme={args.scheme}, "
                                f"input_grad={need_dx}, selection={args.selection}, constant_input={args.constant_input}, "
-                               f"aggregator={args.aggregator}, hip_graph={args.graph}",
+                               f"layer={args.layer}, aggregator={args.aggregator}, hip_graph={args.graph}",
                    "schemes": {str(L["k"]): {"order": int(L["plan"].info.order), "bwd": int(L["plan"].info.bwd),
                                              "cache": int(L["plan"].info.cache)} for L in layers}},
         "roofline": roofline,

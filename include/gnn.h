@@ -44,7 +44,7 @@ typedef enum {
     GNN_ERR_HIP = 6               /* a HIP call or launch failed */
 } gnn_status_t;
 
-typedef enum { GNN_LAYER_GCN = 0, GNN_LAYER_GAT = 1 } gnn_layer_t;
+typedef enum { GNN_LAYER_GCN = 0, GNN_LAYER_GAT = 1, GNN_LAYER_SAGE = 2 } gnn_layer_t;
 
 /* How an AUTO order / backward scheme is chosen for GCN. */
 typedef enum {
@@ -209,6 +209,24 @@ gnn_status_t gcn_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const flo
                            void *cache, void *workspace, void *hip_stream);
 
 /*
+ * sage_layer_fwd / sage_layer_bwd - a GraphSAGE layer, the other layer that Sec. 3.1 "Generalizability"
+ * names for the same chained product:  Y = X W_self + A' X W_neigh + 1 b^T  (optionally ReLU), with A'
+ * the row-normalised pattern (gnn_aggregator_weights, GNN_AGG_MEAN) or any other entry values.
+ * The plan is made with layer = GNN_LAYER_SAGE; order, backward scheme, cache (A'X) and their AUTO
+ * choice are those of GCN, since the SpMM widths are the same (F_out transform-first, F_in propagate-first).
+ *   X [n, f_in], W_self / W_neigh [f_in, f_out], b [f_out] or NULL, Y [n, f_out]
+ *   backward: dW_self = X^T G, dW_neigh = (A'X)^T G, db = G^T 1, dX = G W_self^T + A'^T G W_neigh^T
+ *   (G = dY, masked by [Y > 0] with fuse_relu).  X is needed by backward in every scheme.
+ * cache / workspace sizes: gnn_plan_query.  Errors as gcn_layer_fwd / gcn_layer_bwd.
+ */
+gnn_status_t sage_layer_fwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W_self,
+                            const float *W_neigh, const float *b, float *Y, void *cache, void *workspace,
+                            void *hip_stream);
+gnn_status_t sage_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W_self,
+                            const float *W_neigh, const float *Y, const float *dY, float *dW_self,
+                            float *dW_neigh, float *db, float *dX, void *cache, void *workspace, void *hip_stream);
+
+/*
  * gat_layer_fwd - multi-head GAT forward (Eqs. gat-fwd, gat-fwd-att), heads concatenated.
  *   X [n, f_in], W [f_in, heads*f_out], a_src / a_dst [heads, f_out], b [heads*f_out] or NULL,
  *   Y [n, heads*f_out] laid out [n][head][f_out] (head is the middle axis, Sec. 3.2);
@@ -325,9 +343,13 @@ gnn_status_t gnn_sddmm_csr(int32_t n, int32_t nnz, const int32_t *erow, const in
  *   the product is split along K and reduced in a fixed order; deterministic).
  *   trans_b == 0: B is [K, N] else B is [N, K].  C is [M, N].  All row-major, dense (ld = columns).
  *   bias [N] or NULL, relu: fused epilogue.  Supported: (0,0), (0,1), (1,0).
+ *   relu is a flag word: GNN_GEMM_RELU (1) applies max(., 0); GNN_GEMM_ACCUMULATE (4) adds the
+ *   product (and bias) to what C holds before the ReLU, trans_a == 0 only (GNN_ERR_UNSUPPORTED
+ *   otherwise); any other bit is GNN_ERR_INVALID_ARG.
  *   workspace: gnn_gemm_workspace_bytes(trans_a, trans_b, M, N, K); required for (0,0) (holds B^T)
  *   and (1,0) (holds the partial products); (0,1) needs none.
  */
+enum { GNN_GEMM_RELU = 1, GNN_GEMM_ACCUMULATE = 4 };
 gnn_status_t gnn_gemm(int32_t trans_a, int32_t trans_b, int64_t M, int64_t N, int64_t K,
                       const float *A, const float *B, float *C, const float *bias, int32_t relu,
                       void *workspace, size_t workspace_bytes, void *hip_stream);

@@ -219,6 +219,34 @@ def gcn_backward(rowptr, col, val, X, Theta, G, Y_relu=None, need_dx=True):
     return dTheta, db, dX
 
 
+def sage_forward(rowptr, col, val, X, W_self, W_neigh, b=None, relu=False):
+    """GraphSAGE layer (Sec. 3.1 "Generalizability"): X W_self + A' X W_neigh + 1 b^T, optionally ReLU;
+    ``val`` are the entries of the aggregation matrix A' (row-normalised pattern for the mean)."""
+    X = np.asarray(X, np.float64)
+    Y = X @ np.asarray(W_self, np.float64) + spmm(rowptr, col, val, X) @ np.asarray(W_neigh, np.float64)
+    if b is not None:
+        Y = Y + np.asarray(b, np.float64)[None, :]
+    if relu:
+        Y = np.maximum(Y, 0.0)
+    return Y
+
+
+def sage_backward(rowptr, col, val, X, W_self, W_neigh, G, Y_relu=None, need_dx=True):
+    """Gradients of sage_forward: dW_self = X^T G, dW_neigh = (A'X)^T G, db = G^T 1,
+    dX = G W_self^T + A'^T (G W_neigh^T)."""
+    X = np.asarray(X, np.float64)
+    G = np.asarray(G, np.float64)
+    if Y_relu is not None:
+        G = G * (np.asarray(Y_relu) > 0)
+    dWs = X.T @ G
+    dWn = spmm(rowptr, col, val, X).T @ G
+    db = G.sum(axis=0)
+    dX = None
+    if need_dx:
+        dX = G @ np.asarray(W_self, np.float64).T + spmm_transposed(rowptr, col, val, G @ np.asarray(W_neigh, np.float64).T)
+    return dWs, dWn, db, dX
+
+
 def softmax_xent(Z, labels):
     """Sum-reduced softmax cross-entropy and dZ = softmax(Z) - onehot."""
     Z, pz = _f64(Z)

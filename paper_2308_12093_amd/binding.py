@@ -27,7 +27,7 @@ lib = ctypes.CDLL(LIB_PATH)
 GNN_OK = 0
 (GNN_ERR_INVALID_ARG, GNN_ERR_BAD_GRAPH, GNN_ERR_BUFFER_TOO_SMALL, GNN_ERR_STATE,
  GNN_ERR_UNSUPPORTED, GNN_ERR_HIP) = range(1, 7)
-GNN_LAYER_GCN, GNN_LAYER_GAT = 0, 1
+GNN_LAYER_GCN, GNN_LAYER_GAT, GNN_LAYER_SAGE = 0, 1, 2
 GNN_ORDER_AUTO, GNN_ORDER_TRANSFORM_FIRST, GNN_ORDER_PROPAGATE_FIRST = 0, 1, 2
 GNN_BWD_AUTO, GNN_BWD_FUSED_PROPAGATE, GNN_BWD_SPLIT_PROPAGATE = 0, 1, 2
 (GNN_CACHE_AUTO, GNN_CACHE_NONE, GNN_CACHE_AX, GNN_CACHE_GAT_FEAT, GNN_CACHE_GAT_FEAT_NODEATT,
@@ -72,6 +72,8 @@ _PROTOS = {
     "gnn_spmm_time_model_us": (ctypes.c_double, [_i64, _i64, _i32]),
     "gcn_layer_fwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 7),
     "gcn_layer_bwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 10),
+    "sage_layer_fwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 8),
+    "sage_layer_bwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 12),
     "gat_layer_fwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 9),
     "gat_layer_bwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 14),
     "gnn_add_self_loops_degree": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(_i32), _vp, _sz, _vp]),
@@ -196,6 +198,17 @@ def gcn_layer_fwd(plan: Plan, graph: Graph, X, W, b, Y, cache, workspace):
 def gcn_layer_bwd(plan: Plan, graph: Graph, X, W, Y, dY, dW, db, dX, cache, workspace):
     _check(lib.gcn_layer_bwd(plan.handle, ctypes.byref(graph.c), _ptr(X), _ptr(W), _ptr(Y), _ptr(dY), _ptr(dW),
                              _ptr(db), _ptr(dX), _ptr(cache), _ptr(workspace), _stream()), "gcn_layer_bwd")
+
+
+def sage_layer_fwd(plan: Plan, graph: Graph, X, W_self, W_neigh, b, Y, cache, workspace):
+    _check(lib.sage_layer_fwd(plan.handle, ctypes.byref(graph.c), _ptr(X), _ptr(W_self), _ptr(W_neigh), _ptr(b),
+                              _ptr(Y), _ptr(cache), _ptr(workspace), _stream()), "sage_layer_fwd")
+
+
+def sage_layer_bwd(plan: Plan, graph: Graph, X, W_self, W_neigh, Y, dY, dW_self, dW_neigh, db, dX, cache, workspace):
+    _check(lib.sage_layer_bwd(plan.handle, ctypes.byref(graph.c), _ptr(X), _ptr(W_self), _ptr(W_neigh), _ptr(Y),
+                              _ptr(dY), _ptr(dW_self), _ptr(dW_neigh), _ptr(db), _ptr(dX), _ptr(cache),
+                              _ptr(workspace), _stream()), "sage_layer_bwd")
 
 
 def gat_layer_fwd(plan: Plan, graph: Graph, X, W, a_src, a_dst, b, Y, cache, workspace):

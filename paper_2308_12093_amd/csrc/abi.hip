@@ -98,6 +98,47 @@ gnn_status_t gcn_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const flo
     return gcn_backward(*plan, *graph, X, W, Y, dY, dW, db, dX, cache, workspace, as_stream(hip_stream));
 }
 
+gnn_status_t sage_layer_fwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W_self,
+                            const float *W_neigh, const float *b, float *Y, void *cache, void *workspace,
+                            void *hip_stream) {
+    if (!plan || plan->desc.layer != GNN_LAYER_SAGE) return GNN_ERR_INVALID_ARG;
+    GNN_TRY(check_graph(plan, graph, true, false, false));
+    if (!X || !W_self || !W_neigh || !Y || !workspace) return GNN_ERR_INVALID_ARG;
+    if (plan->desc.has_bias && !b) return GNN_ERR_INVALID_ARG;
+    if (plan->info.cache == GNN_CACHE_AX && !cache) return GNN_ERR_INVALID_ARG;
+    if (bad_align(workspace) || (cache && bad_align(cache))) return GNN_ERR_INVALID_ARG;
+    if (plan->desc.n == 0) return GNN_OK;
+    return sage_forward(*plan, *graph, X, W_self, W_neigh, b, Y, cache, workspace, as_stream(hip_stream));
+}
+
+gnn_status_t sage_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W_self,
+                            const float *W_neigh, const float *Y, const float *dY, float *dW_self,
+                            float *dW_neigh, float *db, float *dX, void *cache, void *workspace, void *hip_stream) {
+    if (!plan || plan->desc.layer != GNN_LAYER_SAGE) return GNN_ERR_INVALID_ARG;
+    const bool cached = plan->info.cache == GNN_CACHE_AX;
+    const bool needs_t = !graph || !graph->symmetric;
+    const bool runs_spmm_t = plan->info.bwd == GNN_BWD_FUSED_PROPAGATE || plan->desc.need_input_grad;
+    GNN_TRY(check_graph(plan, graph, true, needs_t && runs_spmm_t, graph && !graph->csc_val));
+    if (!X || !W_self || !W_neigh || !dY || !dW_self || !dW_neigh || !workspace) return GNN_ERR_INVALID_ARG;
+    if (plan->desc.fuse_relu && !Y) return GNN_ERR_INVALID_ARG;
+    if (plan->desc.has_bias && !db) return GNN_ERR_INVALID_ARG;
+    if (plan->desc.need_input_grad && !dX) return GNN_ERR_INVALID_ARG;
+    if (cached && !cache) return GNN_ERR_INVALID_ARG;
+    if (bad_align(workspace) || (cache && bad_align(cache))) return GNN_ERR_INVALID_ARG;
+    if (cached && !plan->cache_filled) return GNN_ERR_STATE;
+    if (plan->desc.n == 0) {
+        hipStream_t st = as_stream(hip_stream);
+        const size_t wb = sizeof(float) * plan->desc.f_in * plan->desc.f_out;
+        if (hipMemsetAsync(dW_self, 0, wb, st) != hipSuccess) return GNN_ERR_HIP;
+        if (hipMemsetAsync(dW_neigh, 0, wb, st) != hipSuccess) return GNN_ERR_HIP;
+        if (plan->desc.has_bias && hipMemsetAsync(db, 0, sizeof(float) * plan->desc.f_out, st) != hipSuccess)
+            return GNN_ERR_HIP;
+        return GNN_OK;
+    }
+    return sage_backward(*plan, *graph, X, W_self, W_neigh, Y, dY, dW_self, dW_neigh, db, dX, cache, workspace,
+                         as_stream(hip_stream));
+}
+
 gnn_status_t gat_layer_fwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W,
                            const float *a_src, const float *a_dst, const float *b, float *Y,
                            void *cache, void *workspace, void *hip_stream) {
@@ -241,6 +282,8 @@ gnn_status_t gnn_gemm(int32_t trans_a, int32_t trans_b, int64_t M, int64_t N, in
     if (M == 0 || N == 0) return GNN_OK;
     if (!C || (K > 0 && (!A || !B))) return GNN_ERR_INVALID_ARG;
     if (trans_a && trans_b) return GNN_ERR_UNSUPPORTED;
+    if (relu & ~(GNN_GEMM_RELU | GNN_GEMM_ACCUMULATE)) return GNN_ERR_INVALID_ARG;
+    if (trans_a && (relu & GNN_GEMM_ACCUMULATE)) return GNN_ERR_UNSUPPORTED;
     const size_t need = gnn_gemm_workspace_bytes(trans_a, trans_b, M, N, K);
     if (trans_a || !trans_b) {                          // only the A B^T form needs no scratch
         if (!workspace || bad_align(workspace)) return GNN_ERR_INVALID_ARG;

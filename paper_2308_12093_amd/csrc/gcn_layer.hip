@@ -2,6 +2,8 @@
 // the plan chose (Sec. 3.1; Fig. "Two schemes of computing the forward pass", Fig.
 // "Alternative schemes of computing the backward pass", Fig. "GCN computation scheme
 // using caching").  Host code: it only carves the workspace and enqueues kernels.
+// The GraphSAGE layer (Sec. 3.1 "Generalizability") is the same chain plus a dense
+// self term, added by the GEMM that follows or precedes the SpMM.
 #include "plan.h"
 
 namespace gnn {
@@ -101,6 +103,88 @@ gnn_status_t gcn_backward(Plan &p, const gnn_graph_t &g, const float *X, const f
         if (dx) {
             GNN_TRY(gemm_launch(0, 1, n, m, k, G, W, U, nullptr, 0, nullptr, st));
             GNN_TRY(spmm(g, transposed_view(g, m), U, m, dX, nullptr, 0, sp, st));
+        }
+    }
+    return GNN_OK;
+}
+
+// Y = X Ws + A' X Wn + b: the neighbour term in the order the plan chose, the self term by a GEMM
+// that adds to what Y holds (or is added to), bias and ReLU in whichever GEMM writes Y last.
+gnn_status_t sage_forward(Plan &p, const gnn_graph_t &g, const float *X, const float *Ws, const float *Wn,
+                          const float *b, float *Y, void *cache, void *workspace, hipStream_t st) {
+    const gnn_plan_desc_t &d = p.desc;
+    const int n = d.n, m = d.f_in, k = d.f_out;
+    const float *bias = d.has_bias ? b : nullptr;
+    const int last = kActAccumulate | (d.fuse_relu ? kActRelu : 0);
+    Carver ws(workspace);
+    if (p.info.order == GNN_ORDER_TRANSFORM_FIRST) {
+        float *T = ws.take<float>((size_t)n * k);
+        void *sp = ws.take<char>(spmm_workspace_bytes(d.nnz, k));
+        void *wt = ws.take<char>(gemm_workspace_bytes(0, 0, n, k, m));
+        GNN_TRY(gemm_launch(0, 0, n, k, m, X, Wn, T, nullptr, 0, wt, st));
+        GNN_TRY(spmm(g, forward_view(g, k), T, k, Y, nullptr, 0, sp, st));
+        GNN_TRY(gemm_launch(0, 0, n, k, m, X, Ws, Y, bias, last, wt, st));
+    } else {
+        const bool cached = p.info.cache == GNN_CACHE_AX;
+        float *P = cached ? static_cast<float *>(cache) : ws.take<float>((size_t)n * m);
+        void *sp = ws.take<char>(spmm_workspace_bytes(d.nnz, m));
+        void *wt = ws.take<char>(gemm_workspace_bytes(0, 0, n, k, m));
+        if (!(cached && d.constant_input && p.cache_filled))
+            GNN_TRY(spmm(g, forward_view(g, m), X, m, P, nullptr, 0, sp, st));
+        GNN_TRY(gemm_launch(0, 0, n, k, m, X, Ws, Y, nullptr, 0, wt, st));
+        GNN_TRY(gemm_launch(0, 0, n, k, m, P, Wn, Y, bias, last, wt, st));
+        if (cached) p.cache_filled = true;
+    }
+    return GNN_OK;
+}
+
+gnn_status_t sage_backward(Plan &p, const gnn_graph_t &g, const float *X, const float *Ws, const float *Wn,
+                           const float *Y, const float *dY, float *dWs, float *dWn, float *db, float *dX,
+                           void *cache, void *workspace, hipStream_t st) {
+    const gnn_plan_desc_t &d = p.desc;
+    const int n = d.n, m = d.f_in, k = d.f_out;
+    const bool dx = d.need_input_grad != 0;
+    Carver ws(workspace);
+
+    const float *G = dY;
+    if (d.fuse_relu) {
+        float *Gm = ws.take<float>((size_t)n * k);
+        GNN_TRY(activation_grad_launch((int64_t)n * k, dY, Y, Gm, kActRelu, st));
+        G = Gm;
+    }
+    if (d.has_bias) {
+        void *red = ws.take<char>(colsum_workspace_bytes(n, k));
+        GNN_TRY(colsum_launch(n, k, G, db, red, st));
+    }
+    void *gemm_ws = ws.take<char>(gemm_workspace_bytes(1, 0, m, k, n));
+    GNN_TRY(gemm_launch(1, 0, m, k, n, X, G, dWs, nullptr, 0, gemm_ws, st));          // dWs = X^T G
+
+    if (p.info.bwd == GNN_BWD_FUSED_PROPAGATE) {
+        // H = A'^T G once; dWn = X^T H; dX = G Ws^T + H Wn^T
+        float *H = ws.take<float>((size_t)n * k);
+        void *sp = ws.take<char>(spmm_workspace_bytes(d.nnz, k));
+        GNN_TRY(spmm(g, transposed_view(g, k), G, k, H, nullptr, 0, sp, st));
+        GNN_TRY(gemm_launch(1, 0, m, k, n, X, H, dWn, nullptr, 0, gemm_ws, st));
+        if (dx) {
+            GNN_TRY(gemm_launch(0, 1, n, m, k, G, Ws, dX, nullptr, 0, nullptr, st));
+            GNN_TRY(gemm_launch(0, 1, n, m, k, H, Wn, dX, nullptr, kActAccumulate, nullptr, st));
+        }
+    } else {
+        // dWn = (A'X)^T G with A'X from the cache or recomputed; dX = A'^T (G Wn^T) + G Ws^T
+        const bool cached = p.info.cache == GNN_CACHE_AX;
+        const float *P = static_cast<const float *>(cache);
+        float *Pw = cached ? nullptr : ws.take<float>((size_t)n * m);
+        float *U = dx ? ws.take<float>((size_t)n * m) : nullptr;
+        void *sp = ws.take<char>(spmm_workspace_bytes(d.nnz, m));
+        if (!cached) {
+            GNN_TRY(spmm(g, forward_view(g, m), X, m, Pw, nullptr, 0, sp, st));
+            P = Pw;
+        }
+        GNN_TRY(gemm_launch(1, 0, m, k, n, P, G, dWn, nullptr, 0, gemm_ws, st));
+        if (dx) {
+            GNN_TRY(gemm_launch(0, 1, n, m, k, G, Wn, U, nullptr, 0, nullptr, st));
+            GNN_TRY(spmm(g, transposed_view(g, m), U, m, dX, nullptr, 0, sp, st));
+            GNN_TRY(gemm_launch(0, 1, n, m, k, G, Ws, dX, nullptr, kActAccumulate, nullptr, st));
         }
     }
     return GNN_OK;

@@ -415,8 +415,11 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
         const bool cfull = cm0 + BM <= M && cn0 + BN <= N && (size_t)BM * N < (1u << 30);
         if (cfull) {
             float *c0 = C + (size_t)(cm0 + wm * TM * 32) * N + cn0 + wn * TN * 32;     // uniform per wavefront
+            auto at = [&](int x, int y, int v) __attribute__((always_inline)) {
+                return reinterpret_cast<float *>(reinterpret_cast<char *>(c0 + (size_t)(x * 32 + 8 * (v / 4) + (v % 4)) * N + y * 32) + lane_st);
+            };
             auto put = [&](int x, int y, int v, float o) __attribute__((always_inline)) {
-                *reinterpret_cast<float *>(reinterpret_cast<char *>(c0 + (size_t)(x * 32 + 8 * (v / 4) + (v % 4)) * N + y * 32) + lane_st) = o;
+                *at(x, y, v) = o;
                 acc[x][y][v] = 0.f;
             };
             if (!bias && !relu) {
@@ -435,7 +438,8 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
 #pragma unroll
                         for (int v = 0; v < 16; ++v) {
                             float o = acc[x][y][v] + bj;
-                            if (relu) o = fmaxf(o, 0.f);
+                            if (relu & kActAccumulate) o += *at(x, y, v);
+                            if (relu & kActRelu) o = fmaxf(o, 0.f);
                             put(x, y, v, o);
                         }
                 }
@@ -452,7 +456,8 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
                         const int gi = cm0 + (wm * TM + x) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
                         if (gj < N && gi < M) {
                             float o = acc[x][y][v] + bj;
-                            if (relu) o = fmaxf(o, 0.f);
+                            if (relu & kActAccumulate) o += C[(size_t)gi * N + gj];
+                            if (relu & kActRelu) o = fmaxf(o, 0.f);
                             C[(size_t)gi * N + gj] = o;
                         }
                         acc[x][y][v] = 0.f;

@@ -36,6 +36,11 @@ gnn_status_t gat_forward(Plan &p, const gnn_graph_t &g, const float *X, const fl
 gnn_status_t gat_backward(Plan &p, const gnn_graph_t &g, const float *X, const float *W, const float *a_src,
                           const float *a_dst, const float *Y, const float *dY, float *dW, float *da_src,
                           float *da_dst, float *db, float *dX, void *cache, void *workspace, hipStream_t st);
+gnn_status_t sage_forward(Plan &p, const gnn_graph_t &g, const float *X, const float *Ws, const float *Wn,
+                          const float *b, float *Y, void *cache, void *workspace, hipStream_t st);
+gnn_status_t sage_backward(Plan &p, const gnn_graph_t &g, const float *X, const float *Ws, const float *Wn,
+                           const float *Y, const float *dY, float *dWs, float *dWn, float *db, float *dX,
+                           void *cache, void *workspace, hipStream_t st);
 double spmm_time_model_us(int64_t n, int64_t nnz, int f);
 
 }  // namespace gnn

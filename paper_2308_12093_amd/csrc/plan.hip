@@ -178,19 +178,19 @@ GatLayout gat_layout(const Plan &p) {
 gnn_status_t plan_create(const gnn_plan_desc_t *desc, Plan **out) {
     if (!desc || !out) return GNN_ERR_INVALID_ARG;
     const gnn_plan_desc_t &d = *desc;
-    if (!valid_enum(d.layer, GNN_LAYER_GCN, GNN_LAYER_GAT) || !valid_enum(d.order, 0, 2) ||
+    if (!valid_enum(d.layer, GNN_LAYER_GCN, GNN_LAYER_SAGE) || !valid_enum(d.order, 0, 2) ||
         !valid_enum(d.bwd, 0, 2) || !valid_enum(d.cache, 0, 5))
         return GNN_ERR_INVALID_ARG;
     if (d.n < 0 || d.nnz < 0 || d.f_in <= 0 || d.f_out <= 0) return GNN_ERR_INVALID_ARG;
     if (!valid_enum(d.selection, GNN_SELECT_PAPER_RULE, GNN_SELECT_CALIBRATED)) return GNN_ERR_INVALID_ARG;
-    if (d.layer == GNN_LAYER_GCN && d.fuse_elu) return GNN_ERR_INVALID_ARG;
+    if (d.layer != GNN_LAYER_GAT && d.fuse_elu) return GNN_ERR_INVALID_ARG;
     if (d.layer == GNN_LAYER_GAT && d.constant_input) return GNN_ERR_INVALID_ARG;
     Plan *p = new (std::nothrow) Plan();
     if (!p) return GNN_ERR_INVALID_ARG;
     p->desc = d;
     p->info = gnn_plan_info_t{};
     gnn_status_t s;
-    if (d.layer == GNN_LAYER_GCN) {
+    if (d.layer != GNN_LAYER_GAT) {                       // GCN and SAGE: same schemes, same buffers
         p->desc.heads = 1;
         s = resolve_gcn(*p);
         if (s == GNN_OK) size_gcn(*p);

@@ -14,7 +14,7 @@ from paper_2308_12093_amd import binding as B  # noqa: E402
 def header_functions():
     text = open(os.path.join(ROOT, "include", "gnn.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"\b((?:gnn|gcn|gat)_[a-z0-9_]+)\s*\(", text)
+    names = re.findall(r"\b((?:gnn|gcn|gat|sage)_[a-z0-9_]+)\s*\(", text)
     return sorted(set(names))
 
 
@@ -25,6 +25,19 @@ def test_every_declared_symbol_is_exported_and_bound():
         assert hasattr(B.lib, name), name
         assert name in B.EXPORTS, name
     assert sorted(B.EXPORTS) == declared
+
+
+def test_sage_plans_resolve_like_gcn_plans():
+    """GraphSAGE runs SpMMs of the same widths as GCN, so every choice and buffer size is the same."""
+    for m, k, dx in ((128, 16, True), (16, 128, True), (64, 64, False)):
+        a = B.Plan(B.GNN_LAYER_GCN, 1000, 9000, m, k, need_input_grad=dx).info
+        b = B.Plan(B.GNN_LAYER_SAGE, 1000, 9000, m, k, need_input_grad=dx).info
+        assert (a.order, a.bwd, a.cache, a.cache_bytes, a.workspace_bytes) == \
+               (b.order, b.bwd, b.cache, b.cache_bytes, b.workspace_bytes)
+    with pytest.raises(B.GnnError):
+        B.Plan(B.GNN_LAYER_SAGE, 1000, 9000, 8, 8, fuse_elu=True)
+    with pytest.raises(B.GnnError):
+        B.Plan(3, 1000, 9000, 8, 8)
 
 
 def test_status_strings():

@@ -150,12 +150,12 @@ def test_spmm_is_deterministic(B):
 
 
 # ---------------------------------------------------------------- GEMM
-def run_gemm(B, ta, tb, A, Bm, bias=None, relu=False):
+def run_gemm(B, ta, tb, A, Bm, bias=None, relu=False, C0=None):
     M = A.shape[1] if ta else A.shape[0]
     K = A.shape[0] if ta else A.shape[1]
     N = Bm.shape[0] if tb else Bm.shape[1]
     ws = B.alloc(B.gnn_gemm_workspace_bytes(ta, tb, M, N, K))
-    C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    C = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda") if C0 is None else dev(C0)
     B.gnn_gemm(ta, tb, M, N, K, dev(A), dev(Bm), C, None if bias is None else dev(bias), relu, ws)
     torch.cuda.synchronize()
     return host(C)
@@ -173,6 +173,11 @@ def test_gemm_nn_and_nt(B, M, K, N):
     assert_close(run_gemm(B, 0, 0, A, W), ref, "nn")
     assert_close(run_gemm(B, 0, 0, A, W, bias, True), np.maximum(ref + bias, 0), "nn+bias+relu")
     assert_close(run_gemm(B, 0, 1, A, np.ascontiguousarray(W.T)), ref, "nt")
+    # flag word: 4 = add to what C holds (before the ReLU), 1 = ReLU
+    C0 = rng.standard_normal((M, N), dtype=np.float32)
+    assert_close(run_gemm(B, 0, 0, A, W, None, 4, C0), ref + C0, "nn accumulate")
+    assert_close(run_gemm(B, 0, 1, A, np.ascontiguousarray(W.T), bias, 5, C0), np.maximum(ref + bias + C0, 0),
+                 "nt accumulate+bias+relu")
 
 
 @pytest.mark.parametrize("K,M,N", [(50000, 128, 16), (70001, 128, 128), (20000, 100, 256), (9000, 512, 16),

@@ -426,6 +426,35 @@ def test_mean_and_gin_weights_against_dense_definitions():
     np.testing.assert_allclose(oracle.spmm(rp, c, gin, X), (1 + eps) * X + A_plain @ X, rtol=1e-13, atol=1e-13)
 
 
+def test_sage_layer_against_node_loop_and_autograd():
+    """GraphSAGE with the mean aggregator: each output row is x_i W_self + mean over the neighbourhood of x_j
+    times W_neigh (a loop over nodes), and the gradients are those of torch autograd on the dense form."""
+    rowptr, col = small_graph(n=23, q=90, seed=5, diagonal=False)
+    rp, c, deg = oracle.add_self_loops_degree(rowptr, col)
+    n = rp.size - 1
+    val = oracle.aggregator_weights(rp, c, deg, "mean")
+    rng = np.random.default_rng(8)
+    X, Ws, Wn = rng.standard_normal((n, 6)), rng.standard_normal((6, 4)), rng.standard_normal((6, 4))
+    b, G = rng.standard_normal(4), rng.standard_normal((n, 4))
+    Y = oracle.sage_forward(rp, c, val, X, Ws, Wn, b, relu=True)
+    for i in range(n):
+        nb = c[rp[i]:rp[i + 1]]
+        row = X[i] @ Ws + X[nb].mean(axis=0) @ Wn + b
+        np.testing.assert_allclose(Y[i], np.maximum(row, 0.0), rtol=1e-13, atol=1e-14)
+    A = dense_pattern(rp, c)
+    A = torch.tensor(A / A.sum(axis=1, keepdims=True))
+    Xt, Wst, Wnt, bt = (torch.tensor(a, requires_grad=True) for a in (X, Ws, Wn, b))
+    Yt = torch.relu(Xt @ Wst + A @ Xt @ Wnt + bt)
+    Yt.backward(torch.tensor(G))
+    dWs, dWn, db, dX = oracle.sage_backward(rp, c, val, X, Ws, Wn, G, Y_relu=Y)
+    for got, ref in ((dWs, Wst.grad), (dWn, Wnt.grad), (db, bt.grad), (dX, Xt.grad)):
+        np.testing.assert_allclose(got, ref.numpy(), rtol=1e-12, atol=1e-13)
+    # without the neighbour weight the layer is a dense layer; without the self weight a GCN-shaped one
+    np.testing.assert_allclose(oracle.sage_forward(rp, c, val, X, Ws, np.zeros_like(Wn)), X @ Ws, rtol=1e-14)
+    np.testing.assert_allclose(oracle.sage_forward(rp, c, val, X, np.zeros_like(Ws), Wn),
+                               oracle.gcn_forward(rp, c, val, X, Wn), rtol=1e-12, atol=1e-13)
+
+
 def test_softmax_xent_against_torch():
     rng = np.random.default_rng(4)
     Z = rng.standard_normal((50, 7)) * 3

@@ -52,6 +52,9 @@ def parse():
     ap.add_argument("--no-input-grad", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also print per-F_out / per-scheme timings to stderr")
+    ap.add_argument("--format-study", action="store_true",
+                    help="time SpMM on the cfg2 graph and on an even-degree graph of the same size in CSR, coordinate, "
+                         "ELLPACK and hybrid storage (App. D / E.1); prints one JSON line")
     ap.add_argument("--copy-reference", action="store_true",
                     help="only run three plain 256 MiB device copies (known bytes, to scale rocprofv3 byte counters)")
     return ap.parse_args()
@@ -110,6 +113,71 @@ def measured_traffic(workload, launch_widths):
     if any(f not in per_width for f in launch_widths):
         return None
     return round(sum(per_width[f] for f in launch_widths) / len(launch_widths))
+
+
+def format_study(args, torch, B, graphs, synth):
+    """SpMM time by storage format.  Two graphs of the same size: the R-MAT graph of cfg2 (hubs) and a
+    uniform random graph with the same number of nodes and edges (even rows, where ELLPACK is at home)."""
+    dev = "cuda"
+    ev = HipEvents()
+    e0, e1 = ev.create(), ev.create()
+    stream = torch.cuda.current_stream().cuda_stream
+    w = synth.config2(scale=args.scale or 17)
+    rng = synth.substream(0, "graph", 99)
+    pairs = (w.rowptr[-1] // 2)
+    er_rowptr, er_col = synth.erdos_renyi_gnm(w.n, int(pairs), rng)
+    out = {}
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        times = []
+        for _ in range(5):
+            ev.record(e0, stream)
+            for _ in range(5):
+                fn()
+            ev.record(e1, stream)
+            times.append(ev.elapsed_ms(e0, e1) / 5)
+        return float(np.mean(times))
+
+    for gname, (rowptr, col) in (("rmat", (w.rowptr, w.col)), ("uniform", (er_rowptr, er_col))):
+        g = graphs.gcn_graph(rowptr, col, dev, symmetric=True)
+        n, q = g.n, g.nnz
+        rest_ptr = torch.empty(n + 1, dtype=torch.int32, device=dev)
+        ws = B.alloc(B.gnn_hyb_workspace_bytes(n))
+        _, longest = B.gnn_csr_hyb_count(n, g.rowptr, 0, rest_ptr, ws)
+        res = {"n": n, "nnz": q, "longest_row": longest, "ell_padding": round(1 - q / (n * longest), 4), "ms": {}}
+        forms = {}
+        for t in sorted({16, 32, longest}):
+            rest, _ = B.gnn_csr_hyb_count(n, g.rowptr, t, rest_ptr, ws)
+            h = dict(t=t, rest=rest,
+                     ell_col=torch.empty((t, n), dtype=torch.int32, device=dev),
+                     ell_val=torch.empty((t, n), dtype=torch.float32, device=dev),
+                     row=torch.empty(max(rest, 1), dtype=torch.int32, device=dev),
+                     col=torch.empty(max(rest, 1), dtype=torch.int32, device=dev),
+                     val=torch.empty(max(rest, 1), dtype=torch.float32, device=dev))
+            B.gnn_csr_to_hyb(n, t, g.rowptr, g.col, g.val, rest_ptr, h["ell_col"], h["ell_val"], h["row"], h["col"],
+                             h["val"])
+            forms["ellpack" if t == longest else f"hybrid_t{t}"] = h
+        for f in (16, 64, 128):
+            Bm = torch.randn((n, f), dtype=torch.float32, device=dev)
+            C = torch.empty((n, f), dtype=torch.float32, device=dev)
+            sws = B.alloc(B.gnn_spmm_workspace_bytes(n, q, f))
+            ms = {"csr": timed(lambda: B.gnn_spmm_csr(n, q, g.rowptr, g.col, g.val, g.erow, Bm, f, C, None, False, sws)),
+                  "coo": timed(lambda: B.gnn_spmm_coo(n, q, g.erow, g.col, g.val, Bm, f, C))}
+            ref = C.clone()
+            B.gnn_spmm_csr(n, q, g.rowptr, g.col, g.val, g.erow, Bm, f, ref, None, False, sws)
+            for name, h in forms.items():
+                ms[name] = timed(lambda: B.gnn_spmm_hyb(n, h["t"], h["ell_col"], h["ell_val"], h["rest"], h["row"],
+                                                        h["col"], h["val"], Bm, f, C))
+                err = float((C - ref).abs().max())
+                assert err < 1e-3, (name, f, err)
+            res["ms"][str(f)] = {k: round(v, 4) for k, v in ms.items()}
+            print(f"{gname} f={f}: {res['ms'][str(f)]}", file=sys.stderr)
+        res["rest_entries"] = {k: int(h["rest"]) for k, h in forms.items()}
+        out[gname] = res
+        del forms
+    print(json.dumps({"format_study": out}))
 
 
 def bench_gat_network(args, torch, B, graphs, synth):
@@ -229,6 +297,8 @@ def main():
         return
     from paper_2308_12093_amd import binding as B, graphs, synth
 
+    if args.format_study:
+        return format_study(args, torch, B, graphs, synth)
     if args.workload == "cfg4":
         return bench_gat(args, torch, B, graphs, synth)
     if args.workload == "gatnet":

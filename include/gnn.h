@@ -317,6 +317,42 @@ gnn_status_t gnn_spmm_csr(int32_t n, int32_t nnz, const int32_t *rowptr, const i
 size_t gnn_spmm_workspace_bytes(int32_t n, int32_t nnz, int32_t f);
 
 /*
+ * Storage formats other than CSR (App. D.2 coordinate, D.3 ELLPACK, D.4 hybrid) and SpMM on them, for the
+ * format comparison of App. E.1.  The layers never use them.
+ *   ELLPACK arrays ell_col / ell_val [t][n] are slot-major: slot j of row i at [j * n + i]; a row's stored
+ *   entries fill its slots from the front, padding has column -1 and value 0.  With t >= the longest row this
+ *   is plain ELLPACK (p = t); with a smaller t it is the hybrid format: the first t entries of every row in
+ *   the ELLPACK arrays, the others row-major in coordinate arrays coo_row / coo_col / coo_val [rest_nnz].
+ *
+ * gnn_csr_hyb_count - rest_ptr_out [n+1] (device) = exclusive scan of max(0, row length - t);
+ *   rest_nnz_out_host / max_row_out_host: HOST pointers receiving rest_ptr_out[n] and the longest row
+ *   (either may be NULL).  Synchronises the stream.  workspace: gnn_hyb_workspace_bytes(n).
+ * gnn_csr_to_hyb - fills the arrays; val NULL = all ones.  rest_ptr NULL: no coordinate part is written
+ *   (entries beyond slot t are dropped, so pass t >= the longest row).  t = 0: everything goes to the
+ *   coordinate arrays (ell_* may be NULL).
+ * gnn_spmm_ell - C = A B from the ELLPACK arrays.  Deterministic.
+ * gnn_spmm_coo - C = A B (accumulate = 0: C is cleared first) or C += A B (accumulate != 0) from
+ *   coordinate arrays in any order; val NULL = all ones.  Uses fp32 atomic additions: the result is
+ *   reproducible only up to fp32 rounding.
+ * gnn_spmm_hyb - gnn_spmm_ell on the first t slots, then gnn_spmm_coo accumulating the rest.
+ *   B, C [n, f] row-major.  Errors: GNN_ERR_INVALID_ARG for negative sizes / NULL required pointers.
+ */
+size_t gnn_hyb_workspace_bytes(int32_t n);
+gnn_status_t gnn_csr_hyb_count(int32_t n, const int32_t *rowptr, int32_t t, int32_t *rest_ptr_out,
+                               int32_t *rest_nnz_out_host, int32_t *max_row_out_host,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+gnn_status_t gnn_csr_to_hyb(int32_t n, int32_t t, const int32_t *rowptr, const int32_t *col, const float *val,
+                            const int32_t *rest_ptr, int32_t *ell_col, float *ell_val,
+                            int32_t *coo_row, int32_t *coo_col, float *coo_val, void *hip_stream);
+gnn_status_t gnn_spmm_ell(int32_t n, int32_t t, const int32_t *ell_col, const float *ell_val,
+                          const float *B, int32_t f, float *C, void *hip_stream);
+gnn_status_t gnn_spmm_coo(int32_t n, int64_t nnz, const int32_t *row, const int32_t *col, const float *val,
+                          const float *B, int32_t f, float *C, int32_t accumulate, void *hip_stream);
+gnn_status_t gnn_spmm_hyb(int32_t n, int32_t t, const int32_t *ell_col, const float *ell_val,
+                          int64_t rest_nnz, const int32_t *coo_row, const int32_t *coo_col, const float *coo_val,
+                          const float *B, int32_t f, float *C, void *hip_stream);
+
+/*
  * gnn_profile_spmm_events - profiling aid (App. E.1 kernel timing).  While both arguments are
  * non-NULL hipEvent_t handles, every later launch of the entry-balanced SpMM kernel (from
  * gnn_spmm_csr or from a layer) records `start_event` right before and `stop_event` right

@@ -396,6 +396,54 @@ def sum_squared_error(Z, T):
 # --------------------------------------------------------------------------
 # the paper's operational-intensity model for SpMM (App. E.1, table)
 # --------------------------------------------------------------------------
+def csr_to_hybrid(rowptr, col, val, t):
+    """ELLPACK / hybrid CSR-COO storage (App. D.3, D.4): the first ``t`` entries of every row go to
+    Col, V of width t (kept slot-major, [t][n]; padding: column -1, value 0), the others, row by row, to
+    coordinate arrays.  With t >= the longest row the coordinate part is empty and p = t."""
+    rowptr, col = np.asarray(rowptr), np.asarray(col)
+    n = rowptr.size - 1
+    val = np.ones(col.size) if val is None else np.asarray(val, np.float64)
+    ell_col = np.full((t, n), -1, np.int32)
+    ell_val = np.zeros((t, n), np.float64)
+    rows, cols, vals = [], [], []
+    for i in range(n):
+        r0, r1 = int(rowptr[i]), int(rowptr[i + 1])
+        k = min(t, r1 - r0)
+        ell_col[:k, i] = col[r0:r0 + k]
+        ell_val[:k, i] = val[r0:r0 + k]
+        if r1 - r0 > t:
+            rows.append(np.full(r1 - r0 - t, i, np.int32))
+            cols.append(col[r0 + t:r1])
+            vals.append(val[r0 + t:r1])
+    cat = lambda parts, dt: np.concatenate(parts).astype(dt) if parts else np.zeros(0, dt)
+    return ell_col, ell_val, cat(rows, np.int32), cat(cols, np.int32), cat(vals, np.float64)
+
+
+def spmm_ell(ell_col, ell_val, B):
+    """C = A B with A in ELLPACK form: row i adds V[i][j] * B[Col[i][j]] over its slots j (padding skipped)."""
+    B = np.asarray(B, np.float64)
+    t, n = ell_col.shape
+    C = np.zeros((n, B.shape[1]))
+    for j in range(t):
+        live = ell_col[j] >= 0
+        C[live] += ell_val[j][live, None] * B[ell_col[j][live]]
+    return C
+
+
+def spmm_coo(n, row, col, val, B):
+    """C = A B with A as coordinate triples (App. D.2), in any order, duplicates adding up."""
+    B = np.asarray(B, np.float64)
+    val = np.ones(len(row)) if val is None else np.asarray(val, np.float64)
+    C = np.zeros((n, B.shape[1]))
+    np.add.at(C, np.asarray(row), val[:, None] * B[np.asarray(col)])
+    return C
+
+
+def ell_padding_fraction(n: int, q: int, p: int) -> float:
+    """Share of zeros in the n x p ELLPACK value matrix of a matrix with q entries (App. E.1)."""
+    return 1.0 - q / (n * p)
+
+
 def spmm_operational_intensity(fmt: str, n: int, q: int, f: int, p: int = 0) -> float:
     """FLOP per byte of C = A B with A n x n (q entries, longest row p), B n x f, 4-byte words.
 

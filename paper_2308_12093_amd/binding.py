@@ -80,6 +80,12 @@ _PROTOS = {
     "gnn_scan_workspace_bytes": (_sz, [_i32]),
     "gnn_gcn_normalize": (ctypes.c_int, [_i32, _vp, _vp, _vp, _vp, _vp]),
     "gnn_aggregator_weights": (ctypes.c_int, [ctypes.c_int, ctypes.c_float, _i32, _vp, _vp, _vp, _vp, _vp]),
+    "gnn_hyb_workspace_bytes": (_sz, [_i32]),
+    "gnn_csr_hyb_count": (ctypes.c_int, [_i32, _vp, _i32, _vp, ctypes.POINTER(_i32), ctypes.POINTER(_i32), _vp, _sz, _vp]),
+    "gnn_csr_to_hyb": (ctypes.c_int, [_i32, _i32] + [_vp] * 10),
+    "gnn_spmm_ell": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _i32, _vp, _vp]),
+    "gnn_spmm_coo": (ctypes.c_int, [_i32, _i64, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _vp]),
+    "gnn_spmm_hyb": (ctypes.c_int, [_i32, _i32, _vp, _vp, _i64, _vp, _vp, _vp, _vp, _i32, _vp, _vp]),
     "gnn_csr_transpose": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "gnn_transpose_workspace_bytes": (_sz, [_i32, _i32]),
     "gnn_expand_ptr": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp]),
@@ -275,6 +281,38 @@ def gnn_spmm_workspace_bytes(n, nnz, f):
 def gnn_spmm_csr(n, nnz, rowptr, col, val, erow, B, f, C, bias=None, relu=False, workspace=None):
     _check(lib.gnn_spmm_csr(n, nnz, _ptr(rowptr), _ptr(col), _ptr(val), _ptr(erow), _ptr(B), f, _ptr(C),
                             _ptr(bias), int(relu), _ptr(workspace), _nbytes(workspace), _stream()), "gnn_spmm_csr")
+
+
+# ---- other storage formats (format comparison) --------------------------------------
+def gnn_hyb_workspace_bytes(n):
+    return lib.gnn_hyb_workspace_bytes(n)
+
+
+def gnn_csr_hyb_count(n, rowptr, t, rest_ptr_out, workspace):
+    """Returns (rest_nnz, longest_row)."""
+    rest, longest = _i32(0), _i32(0)
+    _check(lib.gnn_csr_hyb_count(n, _ptr(rowptr), t, _ptr(rest_ptr_out), ctypes.byref(rest), ctypes.byref(longest),
+                                 _ptr(workspace), _nbytes(workspace), _stream()), "gnn_csr_hyb_count")
+    return rest.value, longest.value
+
+
+def gnn_csr_to_hyb(n, t, rowptr, col, val, rest_ptr, ell_col, ell_val, coo_row, coo_col, coo_val):
+    _check(lib.gnn_csr_to_hyb(n, t, _ptr(rowptr), _ptr(col), _ptr(val), _ptr(rest_ptr), _ptr(ell_col), _ptr(ell_val),
+                              _ptr(coo_row), _ptr(coo_col), _ptr(coo_val), _stream()), "gnn_csr_to_hyb")
+
+
+def gnn_spmm_ell(n, t, ell_col, ell_val, B, f, C):
+    _check(lib.gnn_spmm_ell(n, t, _ptr(ell_col), _ptr(ell_val), _ptr(B), f, _ptr(C), _stream()), "gnn_spmm_ell")
+
+
+def gnn_spmm_coo(n, nnz, row, col, val, B, f, C, accumulate=False):
+    _check(lib.gnn_spmm_coo(n, nnz, _ptr(row), _ptr(col), _ptr(val), _ptr(B), f, _ptr(C), int(accumulate),
+                            _stream()), "gnn_spmm_coo")
+
+
+def gnn_spmm_hyb(n, t, ell_col, ell_val, rest_nnz, coo_row, coo_col, coo_val, B, f, C):
+    _check(lib.gnn_spmm_hyb(n, t, _ptr(ell_col), _ptr(ell_val), rest_nnz, _ptr(coo_row), _ptr(coo_col),
+                            _ptr(coo_val), _ptr(B), f, _ptr(C), _stream()), "gnn_spmm_hyb")
 
 
 def gnn_profile_spmm_events(start_event, stop_event):

@@ -275,6 +275,62 @@ size_t gnn_gemm_workspace_bytes(int32_t trans_a, int32_t trans_b, int64_t M, int
     return gemm_workspace_bytes(trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K);
 }
 
+size_t gnn_hyb_workspace_bytes(int32_t n) { return n < 0 ? 0 : scan_workspace_bytes(n) + kAlign; }
+
+gnn_status_t gnn_csr_hyb_count(int32_t n, const int32_t *rowptr, int32_t t, int32_t *rest_ptr_out,
+                               int32_t *rest_nnz_out_host, int32_t *max_row_out_host,
+                               void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (n < 0 || t < 0 || !rowptr || !rest_ptr_out || !workspace || bad_align(workspace)) return GNN_ERR_INVALID_ARG;
+    if (workspace_bytes < gnn_hyb_workspace_bytes(n)) return GNN_ERR_BUFFER_TOO_SMALL;
+    hipStream_t st = as_stream(hip_stream);
+    int32_t *max_len = static_cast<int32_t *>(workspace);
+    void *scan_ws = static_cast<char *>(workspace) + kAlign;
+    GNN_TRY(hyb_count_launch(n, rowptr, t, rest_ptr_out, max_len, scan_ws, st));
+    if (rest_nnz_out_host &&
+        hipMemcpyAsync(rest_nnz_out_host, rest_ptr_out + n, sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return GNN_ERR_HIP;
+    if (max_row_out_host &&
+        hipMemcpyAsync(max_row_out_host, max_len, sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess)
+        return GNN_ERR_HIP;
+    return hipStreamSynchronize(st) == hipSuccess ? GNN_OK : GNN_ERR_HIP;
+}
+
+gnn_status_t gnn_csr_to_hyb(int32_t n, int32_t t, const int32_t *rowptr, const int32_t *col, const float *val,
+                            const int32_t *rest_ptr, int32_t *ell_col, float *ell_val,
+                            int32_t *coo_row, int32_t *coo_col, float *coo_val, void *hip_stream) {
+    if (n < 0 || t < 0 || !rowptr) return GNN_ERR_INVALID_ARG;
+    if (n > 0 && t > 0 && (!ell_col || !ell_val)) return GNN_ERR_INVALID_ARG;
+    if (rest_ptr && (!coo_row || !coo_col || !coo_val)) return GNN_ERR_INVALID_ARG;
+    if (t == 0 && !rest_ptr) return GNN_ERR_INVALID_ARG;
+    return hyb_fill_launch(n, t, rowptr, col, val, rest_ptr, ell_col, ell_val, coo_row, coo_col, coo_val,
+                           as_stream(hip_stream));
+}
+
+gnn_status_t gnn_spmm_ell(int32_t n, int32_t t, const int32_t *ell_col, const float *ell_val,
+                          const float *B, int32_t f, float *C, void *hip_stream) {
+    if (n < 0 || t < 0 || f < 0) return GNN_ERR_INVALID_ARG;
+    if (n == 0 || f == 0) return GNN_OK;
+    if (!B || !C || (t > 0 && (!ell_col || !ell_val))) return GNN_ERR_INVALID_ARG;
+    return spmm_ell_launch(n, t, ell_col, ell_val, B, f, C, as_stream(hip_stream));
+}
+
+gnn_status_t gnn_spmm_coo(int32_t n, int64_t nnz, const int32_t *row, const int32_t *col, const float *val,
+                          const float *B, int32_t f, float *C, int32_t accumulate, void *hip_stream) {
+    if (n < 0 || nnz < 0 || f < 0) return GNN_ERR_INVALID_ARG;
+    if (n == 0 || f == 0) return GNN_OK;
+    if (!B || !C || (nnz > 0 && (!row || !col))) return GNN_ERR_INVALID_ARG;
+    hipStream_t st = as_stream(hip_stream);
+    if (!accumulate) GNN_TRY(fill_zero_launch((int64_t)n * f, C, st));
+    return spmm_coo_launch(nnz, row, col, val, B, f, C, st);
+}
+
+gnn_status_t gnn_spmm_hyb(int32_t n, int32_t t, const int32_t *ell_col, const float *ell_val,
+                          int64_t rest_nnz, const int32_t *coo_row, const int32_t *coo_col, const float *coo_val,
+                          const float *B, int32_t f, float *C, void *hip_stream) {
+    GNN_TRY(gnn_spmm_ell(n, t, ell_col, ell_val, B, f, C, hip_stream));
+    return gnn_spmm_coo(n, rest_nnz, coo_row, coo_col, coo_val, B, f, C, 1, hip_stream);
+}
+
 gnn_status_t gnn_gemm(int32_t trans_a, int32_t trans_b, int64_t M, int64_t N, int64_t K,
                       const float *A, const float *B, float *C, const float *bias, int32_t relu,
                       void *workspace, size_t workspace_bytes, void *hip_stream) {

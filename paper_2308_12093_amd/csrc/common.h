@@ -79,6 +79,8 @@ gnn_status_t softmax_xent_launch(int n, int c, const float *Z, const int32_t *la
 
 // ---- preprocessing (prep.hip) -------------------------------------------------------
 size_t scan_workspace_bytes(int64_t n);
+// in-place exclusive scan of `count` <= n + 1 integers; workspace scan_workspace_bytes(n)
+gnn_status_t exclusive_scan_launch(int32_t *data, long count, void *workspace, hipStream_t st);
 size_t transpose_workspace_bytes(int n, int nnz);
 gnn_status_t add_self_loops_launch(int n, int nnz, const int32_t *rowptr, const int32_t *col, int32_t *rowptr_out,
                                    int32_t *col_out, int32_t *deg_out, void *workspace, hipStream_t st);
@@ -88,6 +90,19 @@ gnn_status_t transpose_launch(int n, int nnz, const int32_t *rowptr, const int32
                               int32_t *row, int32_t *perm, void *workspace, hipStream_t st);
 gnn_status_t expand_ptr_launch(int n, int nnz, const int32_t *ptr, int32_t *out, hipStream_t st);
 gnn_status_t gather_f32_launch(int64_t count, const float *in, const int32_t *perm, float *out, hipStream_t st);
+
+// ---- other storage formats (formats.hip) ----------------------------------------------
+// rest_ptr [n + 1]: exclusive scan of max(0, row length - t); max_len_dev: one device word
+gnn_status_t hyb_count_launch(int n, const int32_t *rowptr, int t, int32_t *rest_ptr, int32_t *max_len_dev,
+                              void *scan_ws, hipStream_t st);
+gnn_status_t hyb_fill_launch(int n, int t, const int32_t *rowptr, const int32_t *col, const float *val,
+                             const int32_t *rest_ptr, int32_t *ell_col, float *ell_val, int32_t *coo_row,
+                             int32_t *coo_col, float *coo_val, hipStream_t st);
+gnn_status_t fill_zero_launch(int64_t count, float *p, hipStream_t st);
+gnn_status_t spmm_ell_launch(int n, int t, const int32_t *ell_col, const float *ell_val, const float *B, int f,
+                             float *C, hipStream_t st);
+gnn_status_t spmm_coo_launch(int64_t nnz, const int32_t *row, const int32_t *col, const float *val, const float *B,
+                             int f, float *C, hipStream_t st);
 
 // ---- GAT kernels (gat.hip) -----------------------------------------------------------
 int gat_segment_len(int64_t nnz, int h);

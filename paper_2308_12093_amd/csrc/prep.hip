@@ -254,6 +254,10 @@ size_t scan_ws_ints(long count) {
 
 size_t scan_workspace_bytes(int64_t n) { return align_up(scan_ws_ints(n + 1) * sizeof(int32_t)); }
 
+gnn_status_t exclusive_scan_launch(int32_t *data, long count, void *workspace, hipStream_t st) {
+    return exclusive_scan_inplace(data, count, static_cast<int32_t *>(workspace), st);
+}
+
 gnn_status_t add_self_loops_launch(int n, int nnz, const int32_t *rowptr, const int32_t *col, int32_t *rowptr_out,
                                    int32_t *col_out, int32_t *deg_out, void *workspace, hipStream_t st) {
     (void)nnz;

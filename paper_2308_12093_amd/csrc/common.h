@@ -16,6 +16,9 @@ constexpr size_t kAlign = 256;       // alignment of every carved workspace / ca
 constexpr int kActNone = 0, kActRelu = 1, kActElu = 2;
 // fp32 GEMM only, or-ed into its `relu` argument: add the product to what C already holds (before the activation)
 constexpr int kActAccumulate = 4;
+// set by the GEMM launcher itself for outputs beyond kStreamBytes: non-temporal stores
+constexpr int kActStream = 8;
+constexpr size_t kStreamBytes = (size_t)64 << 20;
 
 static inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

@@ -419,10 +419,12 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
                 return reinterpret_cast<float *>(reinterpret_cast<char *>(c0 + (size_t)(x * 32 + 8 * (v / 4) + (v % 4)) * N + y * 32) + lane_st);
             };
             auto put = [&](int x, int y, int v, float o) __attribute__((always_inline)) {
-                *at(x, y, v) = o;
+                // an output far larger than the caches is streamed past them
+                if (relu & kActStream) __builtin_nontemporal_store(o, at(x, y, v));
+                else *at(x, y, v) = o;
                 acc[x][y][v] = 0.f;
             };
-            if (!bias && !relu) {
+            if (!bias && !(relu & ~kActStream)) {
 #pragma unroll
                 for (int y = 0; y < TN; ++y)
 #pragma unroll
@@ -634,6 +636,8 @@ gnn_status_t gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const 
         }
         const int vec_a = aligned16(A) && K % 4 == 0;
         const int vec_b = aligned16(Bt) && K % 4 == 0;
+        relu &= kActRelu | kActAccumulate;
+        if ((size_t)M * N * sizeof(float) > kStreamBytes && !(relu & kActAccumulate)) relu |= kActStream;
         // persistent blocks: 64 per XCD (2 per CU), each owning a contiguous range of tiles
         const long total = (long)tiles_m * tiles_n;
         if (total > INT32_MAX / 2 || total * ceil_div(K > 0 ? K : 1, 32) > INT32_MAX / 2) return GNN_ERR_UNSUPPORTED;

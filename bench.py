@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg4", "cfg5", "gatnet"],
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "gatnet"],
                     help="gatnet: two GAT layers (8 heads, ELU between, squared error) on the cfg4 graph")
     ap.add_argument("--hidden", type=int, default=8, help="gatnet: features per head of both layers (paper: 8..128)")
     ap.add_argument("--selection", default="rule", choices=["rule", "calibrated"],
@@ -231,6 +231,60 @@ def bench_gat_network(args, torch, B, graphs, synth):
     print(json.dumps(out))
 
 
+def bench_gcn_network(args, torch, B, graphs, synth):
+    """Two-layer GCN (R-MAT 2^20, degree 50, 100 -> 256 -> 47, ReLU between the layers, sum-reduced softmax
+    cross-entropy): one training step without the optimiser, adaptive plans or the fixed
+    transform-first / fused-propagate scheme (--scheme tf_fp)."""
+    w = synth.config3(scale=args.scale or 20)
+    t, (f0, f1, f2) = w.tensors, w.dims["dims"]
+    g = graphs.gcn_graph(w.rowptr, w.col, "cuda")
+    n, q = g.n, g.nnz
+    kw = {} if args.scheme == "auto" else dict(order=B.GNN_ORDER_TRANSFORM_FIRST, bwd=B.GNN_BWD_FUSED_PROPAGATE,
+                                               cache=B.GNN_CACHE_NONE)
+    if args.scheme not in ("auto", "tf_fp"):
+        sys.exit("bench.py: cfg3 takes --scheme auto or tf_fp")
+    sel = B.GNN_SELECT_CALIBRATED if args.selection == "calibrated" else B.GNN_SELECT_PAPER_RULE
+    p1 = B.Plan(B.GNN_LAYER_GCN, n, q, f0, f1, need_input_grad=False, fuse_relu=True, selection=sel,
+                constant_input=args.constant_input, **kw)
+    p2 = B.Plan(B.GNN_LAYER_GCN, n, q, f1, f2, need_input_grad=True, selection=sel, **kw)
+    ws = B.alloc(max(p1.info.workspace_bytes, p2.info.workspace_bytes, 4 * ((n + 255) // 256)))
+    c1 = B.alloc(p1.info.cache_bytes) if p1.info.cache_bytes else None
+    c2 = B.alloc(p2.info.cache_bytes) if p2.info.cache_bytes else None
+    d = {key: torch.from_numpy(v).cuda() for key, v in t.items()}
+    e = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
+    H1, Z, dZ, dH1, dW1, dW2, loss = e(n, f1), e(n, f2), e(n, f2), e(n, f1), e(f0, f1), e(f1, f2), e(1)
+
+    def step():
+        B.gcn_layer_fwd(p1, g, d["X"], d["W1"], None, H1, c1, ws)
+        B.gcn_layer_fwd(p2, g, H1, d["W2"], None, Z, c2, ws)
+        B.gnn_softmax_xent(n, f2, Z, d["labels"], dZ, loss, ws)
+        B.gcn_layer_bwd(p2, g, H1, d["W2"], None, dZ, dW2, None, dH1, c2, ws)
+        B.gcn_layer_bwd(p1, g, None if p1.info.cache == B.GNN_CACHE_AX else d["X"], d["W1"], H1, dH1, dW1, None,
+                        None, c1, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    edge_feat = q * (f0 + f1) + q * (f1 + f2)
+    widths = [int(p.info.spmm_width_fwd + p.info.spmm_width_bwd) for p in (p1, p2)]
+    out = {"metric": "two-layer GCN training step edge-feat/s", "value": edge_feat / (ms * 1e-3),
+           "unit": "edge*feat/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"{w.name}: R-MAT n={n}, nnz={q} (self-loops incl.), {f0}->{f1}->{f2}, ReLU, "
+                                  f"softmax cross-entropy, fwd+bwd, scheme={args.scheme}, selection={args.selection}, "
+                                  f"constant_input={args.constant_input}",
+                      "schemes": [{"order": int(p.info.order), "bwd": int(p.info.bwd), "cache": int(p.info.cache)}
+                                  for p in (p1, p2)],
+                      "spmm_width_sum": widths, "loss": float(loss.item())},
+           "roofline": None, "cpu_baseline": None}
+    print(json.dumps(out))
+
+
 def bench_gat(args, torch, B, graphs, synth):
     """GAT layer workload (R-MAT 2^17 directed, 8 heads x 8, F_in = 256): fwd + bwd of one layer."""
     w = synth.config4(scale=args.scale or 17)
@@ -301,6 +355,8 @@ def main():
         return format_study(args, torch, B, graphs, synth)
     if args.workload == "cfg4":
         return bench_gat(args, torch, B, graphs, synth)
+    if args.workload == "cfg3":
+        return bench_gcn_network(args, torch, B, graphs, synth)
     if args.workload == "gatnet":
         return bench_gat_network(args, torch, B, graphs, synth)
     if args.workload == "cfg1":

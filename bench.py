@@ -516,6 +516,23 @@ def main():
                "sample": f"one full step (fwd+bwd for F_out in {list(f_outs)}) of the same workload, {dt:.1f} s",
                "ms_per_step": dt * 1e3}
 
+    # ---- per-layer forward / backward times, the paper's protocol (Sec. 4 "Experimental Setup": blocks of
+    # runs between two events, median over the blocks), with fewer runs per block to keep the run short ----
+    layer_times = {}
+    for L in layers:
+        rec = {}
+        for name, fn, blocks, runs in (("fwd", fwd, 10, 20), ("bwd", bwd, 5, 20)):
+            per_run = []
+            for _ in range(blocks):
+                ev.record(e0, stream)
+                for _ in range(runs):
+                    fn(L)
+                ev.record(e1, stream)
+                per_run.append(ev.elapsed_ms(e0, e1) / runs)
+            rec[name + "_ms"] = {"median": round(float(np.median(per_run)), 5), "min": round(float(np.min(per_run)), 5),
+                                 "max": round(float(np.max(per_run)), 5)}
+        layer_times[str(L["k"])] = rec
+
     if args.breakdown:
         for L in layers:
             for name, fn in (("fwd", fwd), ("bwd", bwd)):
@@ -540,7 +557,8 @@ def main():
                                f"input_grad={need_dx}, selection={args.selection}, constant_input={args.constant_input}, "
                                f"layer={args.layer}, aggregator={args.aggregator}, hip_graph={args.graph}",
                    "schemes": {str(L["k"]): {"order": int(L["plan"].info.order), "bwd": int(L["plan"].info.bwd),
-                                             "cache": int(L["plan"].info.cache)} for L in layers}},
+                                             "cache": int(L["plan"].info.cache)} for L in layers},
+                   "layer_times_ms": layer_times},
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

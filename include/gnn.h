@@ -19,7 +19,7 @@
  *  - All argument checks run before the first launch, so a call that returns
  *    an error has had no side effect.  No entry point aborts or throws.
  *  - Dense tensors are row-major fp32.  Index arrays are int32.  Outputs are
- *    overwritten, not accumulated into.
+ *    overwritten, not accumulated into, unless an entry point's flag asks for it.
  *  - Sparse matrices are square n x n in CSR (App. D.1, 0-based): rowptr[0] = 0,
  *    rowptr[n] = nnz, column indices strictly ascending inside a row.  Row i is
  *    the aggregating node, col[e] the neighbour whose features it reads.

@@ -2,6 +2,7 @@
 chooses schemes by the paper's tables and rejects bad arguments before any launch."""
 import ctypes
 import os
+import subprocess
 import re
 
 import pytest
@@ -38,6 +39,16 @@ def test_sage_plans_resolve_like_gcn_plans():
         B.Plan(B.GNN_LAYER_SAGE, 1000, 9000, 8, 8, fuse_elu=True)
     with pytest.raises(B.GnnError):
         B.Plan(3, 1000, 9000, 8, 8)
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as strict C99 and as C++ with no HIP or torch include."""
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "gnn.h"\nint main(void) { gnn_plan_desc_t d; gnn_graph_t g; (void)d; (void)g; return 0; }\n')
+    inc = os.path.join(ROOT, "include")
+    for cmd in (["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror"], ["g++", "-x", "c++", "-std=c++11", "-Wall", "-Werror"]):
+        r = subprocess.run(cmd + ["-I", inc, "-c", str(src), "-o", str(tmp_path / "o.o")], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
 
 
 def test_status_strings():

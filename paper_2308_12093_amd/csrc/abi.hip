@@ -302,6 +302,7 @@ gnn_status_t gnn_csr_to_hyb(int32_t n, int32_t t, const int32_t *rowptr, const i
     if (n > 0 && t > 0 && (!ell_col || !ell_val)) return GNN_ERR_INVALID_ARG;
     if (rest_ptr && (!coo_row || !coo_col || !coo_val)) return GNN_ERR_INVALID_ARG;
     if (t == 0 && !rest_ptr) return GNN_ERR_INVALID_ARG;
+    if ((int64_t)n * t / 256 >= INT32_MAX) return GNN_ERR_UNSUPPORTED;        // one thread per ELLPACK slot
     return hyb_fill_launch(n, t, rowptr, col, val, rest_ptr, ell_col, ell_val, coo_row, coo_col, coo_val,
                            as_stream(hip_stream));
 }

@@ -259,6 +259,25 @@ def test_config4_full_size(B, G):
                                        err_msg=f"cfg4 {variant} vs NONE: {name}")
 
 
+@pytest.mark.parametrize("variant", ["NONE", "GAT_FEAT_EDGE"])
+def test_large_logits_do_not_overflow(B, G, variant):
+    """Attention vectors scaled by 40: logits reach +-280, far beyond what exp takes in fp32 without the
+    row maximum being subtracted first; the softmax saturates towards one neighbour per row."""
+    h, k = 4, 8
+    rowptr, col, t = make_case(40, 9, 8, 16, h, k)
+    t["a_src"], t["a_dst"] = t["a_src"] * 40, t["a_dst"] * 40
+    rp, c = oracle_graph(rowptr, col)
+    fw = oracle.gat_forward(rp, c, t["X"], t["W"], t["a_src"], t["a_dst"], t["b"], h, 0.2)
+    rows = np.repeat(np.arange(rp.size - 1), np.diff(rp))
+    assert np.abs(fw["s"][rows] + fw["d"][c]).max() > 200 and ambiguous_logits(fw, rp, c, 1e-3) == 0
+    bw = oracle.gat_backward(rp, c, t["X"], t["W"], t["a_src"], t["a_dst"], t["dY"], h, 0.2)
+    layer = Layer(B, G, rowptr, col, t, h, getattr(B, "GNN_CACHE_" + variant))
+    assert_close(layer.forward(), fw["Y"], "Y")
+    got = layer.backward()
+    for name in ("dW", "da_src", "da_dst", "dX"):
+        assert_close(got[name], bw[name].reshape(got[name].shape), f"{variant} {name}")
+
+
 @pytest.mark.parametrize("n", [1, 3])
 def test_graph_without_edges_attends_to_itself_only(B, G, n):
     """Every row holds its self-loop only: alpha = 1, so the layer is X Theta + b, the attention

@@ -106,10 +106,11 @@ colsum_final_kernel(int f, int blocks, const double *__restrict__ part, float *_
     }
 }
 
-// One thread per node: stable softmax, loss term, dZ = softmax - onehot.
+// One thread per node: stable softmax, loss term, dZ = softmax - onehot.  Rows are read with a
+// stride of c words between neighbouring threads; kept for rows too long for the tiled kernel.
 __global__ void __launch_bounds__(256)
-softmax_xent_kernel(int n, int c, const float *__restrict__ Z, const int32_t *__restrict__ labels,
-                    float *__restrict__ dZ, float *__restrict__ block_loss) {
+softmax_xent_rows_kernel(int n, int c, const float *__restrict__ Z, const int32_t *__restrict__ labels,
+                         float *__restrict__ dZ, float *__restrict__ block_loss) {
     __shared__ float red[256];
     const int i = blockIdx.x * 256 + threadIdx.x;
     float loss = 0.f;
@@ -133,11 +134,69 @@ softmax_xent_kernel(int n, int c, const float *__restrict__ Z, const int32_t *__
     }
 }
 
-__global__ void sum_serial_kernel(int count, const float *__restrict__ in, float *__restrict__ out) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) {
-        double s = 0.0;
-        for (int i = 0; i < count; ++i) s += (double)in[i];
-        out[0] = (float)s;
+constexpr int kXentLdsFloats = 12288;          // 48 KB tile of logits
+
+// The same per 256-node block, tiled through LDS: a pass copies R = 256 / G whole rows (contiguous in
+// memory, so the copy is coalesced), G = 2^g lanes share a row (elements lane, lane + G, ...; maximum and
+// sum by a fixed xor tree), the gradients replace the logits in LDS and go out coalesced again.
+__global__ void __launch_bounds__(256)
+softmax_xent_tiled_kernel(int n, int c, int G, const float *__restrict__ Z, const int32_t *__restrict__ labels,
+                          float *__restrict__ dZ, float *__restrict__ block_loss) {
+    __shared__ float tile[kXentLdsFloats];
+    __shared__ float red[256];
+    const int R = 256 / G;
+    const int r = threadIdx.x / G, g = threadIdx.x % G;
+    const int first = blockIdx.x * 256;
+    float loss = 0.f;
+    for (int p0 = 0; p0 < 256 && first + p0 < n; p0 += R) {
+        const int rows = min(R, n - first - p0);
+        const size_t base = (size_t)(first + p0) * c;
+        const int count = rows * c;
+        for (int i = threadIdx.x; i < count; i += 256) tile[i] = Z[base + i];
+        __syncthreads();
+        float mx = -INFINITY, sum = 0.f, zl = 0.f;
+        int lab = -1;
+        float *z = tile + r * c;
+        if (r < rows) {
+            for (int t = g; t < c; t += G) mx = fmaxf(mx, z[t]);
+            for (int o = G >> 1; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+            for (int t = g; t < c; t += G) sum += expf(z[t] - mx);
+            for (int o = G >> 1; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+            lab = labels[first + p0 + r];
+            zl = z[lab];
+        }
+        __syncthreads();                                   // every read of the logits precedes the overwrite
+        if (r < rows) {
+            if (g == 0) loss += logf(sum) + mx - zl;
+            const float inv = 1.f / sum;
+            for (int t = g; t < c; t += G) z[t] = expf(z[t] - mx) * inv - (t == lab ? 1.f : 0.f);
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < count; i += 256) dZ[base + i] = tile[i];
+        __syncthreads();
+    }
+    red[threadIdx.x] = loss;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float s = 0.f;
+        for (int k = 0; k < 256; ++k) s += red[k];
+        block_loss[blockIdx.x] = s;
+    }
+}
+
+// out[0] = sum of `count` partials: thread t adds partials t, t + 256, ... in double, thread 0 adds the
+// 256 results in order (a fixed association, whatever the count)
+__global__ void __launch_bounds__(256)
+sum_partials_kernel(int count, const float *__restrict__ in, float *__restrict__ out) {
+    __shared__ double red[256];
+    double s = 0.0;
+    for (int i = threadIdx.x; i < count; i += 256) s += (double)in[i];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        for (int k = 0; k < 256; ++k) t += red[k];
+        out[0] = (float)t;
     }
 }
 
@@ -217,9 +276,14 @@ gnn_status_t softmax_xent_launch(int n, int c, const float *Z, const int32_t *la
     if (n <= 0) return GNN_OK;
     const int blocks = (int)ceil_div(n, 256);
     float *part = static_cast<float *>(workspace);
-    hipLaunchKernelGGL(softmax_xent_kernel, dim3(blocks), dim3(256), 0, st, n, c, Z, labels, dZ, part);
+    int G = 1;                                             // lanes per row: about 16 elements each
+    while (G < 64 && G * 16 < c) G <<= 1;
+    if ((long)(256 / G) * c <= kXentLdsFloats)
+        hipLaunchKernelGGL(softmax_xent_tiled_kernel, dim3(blocks), dim3(256), 0, st, n, c, G, Z, labels, dZ, part);
+    else
+        hipLaunchKernelGGL(softmax_xent_rows_kernel, dim3(blocks), dim3(256), 0, st, n, c, Z, labels, dZ, part);
     GNN_TRY(launch_status());
-    hipLaunchKernelGGL(sum_serial_kernel, dim3(1), dim3(64), 0, st, blocks, part, loss);
+    hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(256), 0, st, blocks, part, loss);
     return launch_status();
 }
 
@@ -230,7 +294,7 @@ gnn_status_t squared_error_launch(int64_t count, const float *Z, const float *T,
     if (blocks > 1024) blocks = 1024;
     hipLaunchKernelGGL(squared_error_kernel, dim3(blocks), dim3(256), 0, st, (long)count, Z, T, dZ, part);
     GNN_TRY(launch_status());
-    hipLaunchKernelGGL(sum_serial_kernel, dim3(1), dim3(64), 0, st, blocks, part, loss);
+    hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(256), 0, st, blocks, part, loss);
     return launch_status();
 }
 

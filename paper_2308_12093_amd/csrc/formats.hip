@@ -168,21 +168,21 @@ spmm_ell_kernel(int n, int t, const int32_t *__restrict__ ell_col, const float *
 }
 
 // Coordinate SpMM: C += A B, entry by entry (App. D.2).  A group of LANES threads takes
-// kCooRun consecutive entries (in batches of kCooBatch gathers in flight) and a tile of
+// a run of consecutive entries (kCooRun, or kCooBatch for a small matrix; kCooBatch gathers in flight) and a tile of
 // LANES * VEC features; it adds up products while the row stays the same and sends the
 // sum to C with floating-point atomics when the row changes, so sorted input costs one
 // atomic per (row run, feature) and unsorted input still works.  The order of the atomic
 // additions varies from run to run: the result is reproducible only up to fp32 rounding.
 template <int LANES, int VEC>
 __global__ void __launch_bounds__(256)
-spmm_coo_kernel(long nnz, const int32_t *__restrict__ row, const int32_t *__restrict__ col,
+spmm_coo_kernel(long nnz, int run, const int32_t *__restrict__ row, const int32_t *__restrict__ col,
                 const float *__restrict__ val, const float *__restrict__ B, int f, float *__restrict__ C) {
     constexpr int G = 256 / LANES;
     const int g = threadIdx.x / LANES, lane = threadIdx.x % LANES;
     const int c0 = (blockIdx.y * LANES + lane) * VEC;
-    const long first = ((long)blockIdx.x * G + g) * kCooRun;
+    const long first = ((long)blockIdx.x * G + g) * run;
     if (c0 >= f || first >= nnz) return;
-    const long end = min(first + kCooRun, nnz);
+    const long end = min(first + run, nnz);
 
     float acc[VEC];
 #pragma unroll
@@ -290,8 +290,9 @@ gnn_status_t spmm_ell_launch(int n, int t, const int32_t *ell_col, const float *
 
 #define COO_CASE(L, V)                                                                                          \
     if (lanes == L && vec == V) {                                                                               \
-        dim3 grid((unsigned)ceil_div(nnz, (long)(256 / L) * kCooRun), (unsigned)ceil_div(f, L * V));             \
-        hipLaunchKernelGGL((spmm_coo_kernel<L, V>), grid, dim3(256), 0, st, (long)nnz, row, col, val, B, f, C); \
+        dim3 grid((unsigned)ceil_div(nnz, (long)(256 / L) * run), (unsigned)ceil_div(f, L * V));                 \
+        hipLaunchKernelGGL((spmm_coo_kernel<L, V>), grid, dim3(256), 0, st, (long)nnz, run, row, col, val, B,   \
+                           f, C);                                                                               \
         return launch_status();                                                                                 \
     }
 
@@ -300,6 +301,8 @@ gnn_status_t spmm_coo_launch(int64_t nnz, const int32_t *row, const int32_t *col
     if (nnz <= 0 || f <= 0) return GNN_OK;
     const int vec = f % 4 == 0 && aligned16(B) ? 4 : 1;
     const int lanes = pick_lanes(f, vec, 32);
+    // long runs save atomics on sorted input; short ones keep a small matrix spread over the chip
+    const int run = nnz >= (long)kCooRun * (256 / lanes) * 2048 ? kCooRun : kCooBatch;      // >= 2048 blocks
     COO_CASE(4, 4) COO_CASE(8, 4) COO_CASE(16, 4) COO_CASE(32, 4)
     COO_CASE(4, 1) COO_CASE(8, 1) COO_CASE(16, 1) COO_CASE(32, 1)
     return GNN_ERR_UNSUPPORTED;

@@ -192,9 +192,12 @@ def test_gemm_tn_split_reduction(B, K, M, N):
     assert np.array_equal(got, run_gemm(B, 1, 0, A, H)), "split-K reduction must be reproducible"
 
 
-def test_softmax_xent(B):
-    rng = np.random.default_rng(7)
-    n, c = 5000, 47
+@pytest.mark.parametrize("n,c", [(5000, 47), (1, 1), (3, 2), (257, 16), (1000, 17), (513, 100), (300, 1000),
+                                 (70, 3072), (40, 4000), (100000, 47)])
+def test_softmax_xent(B, n, c):
+    """One lane per row up to 16 classes, lane groups of 2 ... 64 beyond, one thread per row above 3072 classes;
+    node counts that end inside a 256-row block and inside a pass."""
+    rng = np.random.default_rng(7 + n + c)
     Z = (rng.standard_normal((n, c)) * 3).astype(np.float32)
     lab = rng.integers(0, c, size=n).astype(np.int32)
     dZ = torch.empty((n, c), dtype=torch.float32, device="cuda")

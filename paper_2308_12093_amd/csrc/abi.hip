@@ -239,8 +239,7 @@ gnn_status_t gnn_gather_f32(int64_t count, const float *in, const int32_t *perm,
 // ---- operators ----------------------------------------------------------------------
 
 size_t gnn_spmm_workspace_bytes(int32_t n, int32_t nnz, int32_t f) {
-    (void)n;
-    return spmm_workspace_bytes(nnz > 0 ? nnz : 0, f > 0 ? f : 1);
+    return spmm_workspace_bytes(n > 0 ? n : 0, nnz > 0 ? nnz : 0, f > 0 ? f : 1);
 }
 
 gnn_status_t gnn_spmm_csr(int32_t n, int32_t nnz, const int32_t *rowptr, const int32_t *col, const float *val,
@@ -252,9 +251,9 @@ gnn_status_t gnn_spmm_csr(int32_t n, int32_t nnz, const int32_t *rowptr, const i
     if (nnz > 0 && (!col || !B)) return GNN_ERR_INVALID_ARG;
     if (erow && nnz > 0) {
         if (!workspace || bad_align(workspace)) return GNN_ERR_INVALID_ARG;
-        if (workspace_bytes < spmm_workspace_bytes(nnz, f)) return GNN_ERR_BUFFER_TOO_SMALL;
+        if (workspace_bytes < spmm_workspace_bytes(n, nnz, f)) return GNN_ERR_BUFFER_TOO_SMALL;
     }
-    return spmm_launch(n, nnz, rowptr, col, erow, EdgeWeights{val, nullptr, 1, f}, B, f, C, bias, relu, workspace,
+    return spmm_launch(n, nnz, rowptr, col, erow, EdgeWeights{val, nullptr, 1, f}, B, n, f, C, bias, relu, workspace,
                        as_stream(hip_stream));
 }
 

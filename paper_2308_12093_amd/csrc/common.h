@@ -56,9 +56,11 @@ struct EdgeWeights {
 };
 
 int spmm_segment_len(int64_t nnz, int f);
-size_t spmm_workspace_bytes(int64_t nnz, int f);
+size_t spmm_workspace_bytes(int64_t n, int64_t nnz, int f);
+// b_rows: rows of B (n when the column indices are node numbers), or 0 = unknown: then a width that is
+// not a multiple of 4 is not run on a padded copy of B.  workspace: spmm_workspace_bytes(b_rows, nnz, f)
 gnn_status_t spmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *col, const int32_t *erow,
-                         EdgeWeights w, const float *B, int f, float *C, const float *bias, int relu,
+                         EdgeWeights w, const float *B, long b_rows, int f, float *C, const float *bias, int relu,
                          void *workspace, hipStream_t st);
 
 void spmm_profile_events(hipEvent_t start, hipEvent_t stop);

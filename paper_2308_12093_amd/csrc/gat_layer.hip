@@ -46,7 +46,7 @@ gnn_status_t gat_forward(Plan &p, const gnn_graph_t &g, const float *X, const fl
     GNN_TRY(gat_edge_softmax_launch(n, q, h, g.csr_rowptr, g.csr_erow, g.csr_col, B.s, B.d, d.leaky_slope, B.stat,
                                     B.alpha, B.mask, at<char>(workspace, L.w_walk), st));
     // Y_i = sum_e alpha_e M_j (+ b): SpMM with one weight per entry and head
-    GNN_TRY(spmm_launch(n, q, g.csr_rowptr, g.csr_col, g.csr_erow, EdgeWeights{B.alpha, nullptr, h, k}, B.M, f, Y,
+    GNN_TRY(spmm_launch(n, q, g.csr_rowptr, g.csr_col, g.csr_erow, EdgeWeights{B.alpha, nullptr, h, k}, B.M, n, f, Y,
                         d.has_bias ? b : nullptr, d.fuse_elu ? kActElu : kActNone, at<char>(workspace, L.w_spmm), st));
     p.cache_filled = true;
     return GNN_OK;
@@ -89,10 +89,10 @@ gnn_status_t gat_backward(Plan &p, const gnn_graph_t &g, const float *X, const f
     GNN_TRY(gat_edge_backward_launch(n, q, h, g.csr_rowptr, g.csr_erow, g.csr_col, B.alpha, B.mask, B.s, B.d,
                                      d.leaky_slope, gy, sums, ds, at<char>(workspace, L.w_walk), st));
     // dd_j = sum over column j of g_y: a row sum over the CSC arrays, gathering g_y rows through perm
-    GNN_TRY(spmm_launch(n, q, g.csc_colptr, g.csc_perm, g.csc_ecol, EdgeWeights{nullptr, nullptr, 1, h}, gy, h, dd,
+    GNN_TRY(spmm_launch(n, q, g.csc_colptr, g.csc_perm, g.csc_ecol, EdgeWeights{nullptr, nullptr, 1, h}, gy, 0, h, dd,
                         nullptr, 0, at<char>(workspace, L.w_spmm_h), st));
     // dM = A^T G (weights alpha through perm) + ds a_src + dd a_dst
-    GNN_TRY(spmm_launch(n, q, g.csc_colptr, g.csc_row, g.csc_ecol, EdgeWeights{B.alpha, g.csc_perm, h, k}, dY, f, dM,
+    GNN_TRY(spmm_launch(n, q, g.csc_colptr, g.csc_row, g.csc_ecol, EdgeWeights{B.alpha, g.csc_perm, h, k}, dY, n, f, dM,
                         nullptr, 0, at<char>(workspace, L.w_spmm), st));
     GNN_TRY(gat_add_rank1_launch(n, h, k, ds, dd, a_src, a_dst, dM, st));
     // da_src = M^T ds, da_dst = M^T dd

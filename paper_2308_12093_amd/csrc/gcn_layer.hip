@@ -28,7 +28,7 @@ SparseView transposed_view(const gnn_graph_t &g, int f) {
 
 gnn_status_t spmm(const gnn_graph_t &g, const SparseView &v, const float *B, int f, float *C, const float *bias,
                   int relu, void *ws, hipStream_t st) {
-    return spmm_launch(g.n, g.nnz, v.ptr, v.idx, v.eidx, v.w, B, f, C, bias, relu, ws, st);
+    return spmm_launch(g.n, g.nnz, v.ptr, v.idx, v.eidx, v.w, B, g.n, f, C, bias, relu, ws, st);
 }
 
 }  // namespace
@@ -42,7 +42,7 @@ gnn_status_t gcn_forward(Plan &p, const gnn_graph_t &g, const float *X, const fl
     if (p.info.order == GNN_ORDER_TRANSFORM_FIRST) {
         // T = X W, then Y = A' T (+ b, ReLU) fused into the SpMM write
         float *T = ws.take<float>((size_t)n * k);
-        void *sp = ws.take<char>(spmm_workspace_bytes(d.nnz, k));
+        void *sp = ws.take<char>(spmm_workspace_bytes(n, d.nnz, k));
         void *wt = ws.take<char>(gemm_workspace_bytes(0, 0, n, k, m));
         GNN_TRY(gemm_launch(0, 0, n, k, m, X, W, T, nullptr, 0, wt, st));
         GNN_TRY(spmm(g, forward_view(g, k), T, k, Y, bias, d.fuse_relu, sp, st));
@@ -50,7 +50,7 @@ gnn_status_t gcn_forward(Plan &p, const gnn_graph_t &g, const float *X, const fl
         // P = A' X (kept in the cache slot when the plan caches it), then Y = P W (+ b, ReLU)
         const bool cached = p.info.cache == GNN_CACHE_AX;
         float *P = cached ? static_cast<float *>(cache) : ws.take<float>((size_t)n * m);
-        void *sp = ws.take<char>(spmm_workspace_bytes(d.nnz, m));
+        void *sp = ws.take<char>(spmm_workspace_bytes(n, d.nnz, m));
         void *wt = ws.take<char>(gemm_workspace_bytes(0, 0, n, k, m));
         // a constant input (promised by the caller) needs its A'X only once
         if (!(cached && d.constant_input && p.cache_filled))
@@ -84,7 +84,7 @@ gnn_status_t gcn_backward(Plan &p, const gnn_graph_t &g, const float *X, const f
     if (p.info.bwd == GNN_BWD_FUSED_PROPAGATE) {
         // H = A'^T G once; dW = X^T H; dX = H W^T
         float *H = ws.take<float>((size_t)n * k);
-        void *sp = ws.take<char>(spmm_workspace_bytes(d.nnz, k));
+        void *sp = ws.take<char>(spmm_workspace_bytes(n, d.nnz, k));
         GNN_TRY(spmm(g, transposed_view(g, k), G, k, H, nullptr, 0, sp, st));
         GNN_TRY(gemm_launch(1, 0, m, k, n, X, H, dW, nullptr, 0, gemm_ws, st));
         if (dx) GNN_TRY(gemm_launch(0, 1, n, m, k, H, W, dX, nullptr, 0, nullptr, st));
@@ -94,7 +94,7 @@ gnn_status_t gcn_backward(Plan &p, const gnn_graph_t &g, const float *X, const f
         const float *P = static_cast<const float *>(cache);
         float *Pw = cached ? nullptr : ws.take<float>((size_t)n * m);
         float *U = dx ? ws.take<float>((size_t)n * m) : nullptr;
-        void *sp = ws.take<char>(spmm_workspace_bytes(d.nnz, m));
+        void *sp = ws.take<char>(spmm_workspace_bytes(n, d.nnz, m));
         if (!cached) {
             GNN_TRY(spmm(g, forward_view(g, m), X, m, Pw, nullptr, 0, sp, st));
             P = Pw;
@@ -119,7 +119,7 @@ gnn_status_t sage_forward(Plan &p, const gnn_graph_t &g, const float *X, const f
     Carver ws(workspace);
     if (p.info.order == GNN_ORDER_TRANSFORM_FIRST) {
         float *T = ws.take<float>((size_t)n * k);
-        void *sp = ws.take<char>(spmm_workspace_bytes(d.nnz, k));
+        void *sp = ws.take<char>(spmm_workspace_bytes(n, d.nnz, k));
         void *wt = ws.take<char>(gemm_workspace_bytes(0, 0, n, k, m));
         GNN_TRY(gemm_launch(0, 0, n, k, m, X, Wn, T, nullptr, 0, wt, st));
         GNN_TRY(spmm(g, forward_view(g, k), T, k, Y, nullptr, 0, sp, st));
@@ -127,7 +127,7 @@ gnn_status_t sage_forward(Plan &p, const gnn_graph_t &g, const float *X, const f
     } else {
         const bool cached = p.info.cache == GNN_CACHE_AX;
         float *P = cached ? static_cast<float *>(cache) : ws.take<float>((size_t)n * m);
-        void *sp = ws.take<char>(spmm_workspace_bytes(d.nnz, m));
+        void *sp = ws.take<char>(spmm_workspace_bytes(n, d.nnz, m));
         void *wt = ws.take<char>(gemm_workspace_bytes(0, 0, n, k, m));
         if (!(cached && d.constant_input && p.cache_filled))
             GNN_TRY(spmm(g, forward_view(g, m), X, m, P, nullptr, 0, sp, st));
@@ -162,7 +162,7 @@ gnn_status_t sage_backward(Plan &p, const gnn_graph_t &g, const float *X, const 
     if (p.info.bwd == GNN_BWD_FUSED_PROPAGATE) {
         // H = A'^T G once; dWn = X^T H; dX = G Ws^T + H Wn^T
         float *H = ws.take<float>((size_t)n * k);
-        void *sp = ws.take<char>(spmm_workspace_bytes(d.nnz, k));
+        void *sp = ws.take<char>(spmm_workspace_bytes(n, d.nnz, k));
         GNN_TRY(spmm(g, transposed_view(g, k), G, k, H, nullptr, 0, sp, st));
         GNN_TRY(gemm_launch(1, 0, m, k, n, X, H, dWn, nullptr, 0, gemm_ws, st));
         if (dx) {
@@ -175,7 +175,7 @@ gnn_status_t sage_backward(Plan &p, const gnn_graph_t &g, const float *X, const 
         const float *P = static_cast<const float *>(cache);
         float *Pw = cached ? nullptr : ws.take<float>((size_t)n * m);
         float *U = dx ? ws.take<float>((size_t)n * m) : nullptr;
-        void *sp = ws.take<char>(spmm_workspace_bytes(d.nnz, m));
+        void *sp = ws.take<char>(spmm_workspace_bytes(n, d.nnz, m));
         if (!cached) {
             GNN_TRY(spmm(g, forward_view(g, m), X, m, Pw, nullptr, 0, sp, st));
             P = Pw;

@@ -79,12 +79,12 @@ void size_gcn(Plan &p) {
     // forward
     size_t fwd = gemm_workspace_bytes(0, 0, n, k, m);
     if (tf) {
-        fwd += align_up((size_t)n * k * fl) + spmm_workspace_bytes(q, (int)k);
+        fwd += align_up((size_t)n * k * fl) + spmm_workspace_bytes(n, q, (int)k);
         p.info.transient_fwd = n * k;
         p.info.spmm_width_fwd = k;
     } else {
         if (!cached) fwd += align_up((size_t)n * m * fl);
-        fwd += spmm_workspace_bytes(q, (int)m);
+        fwd += spmm_workspace_bytes(n, q, (int)m);
         p.info.transient_fwd = n * m;
         p.info.spmm_width_fwd = m;
     }
@@ -94,14 +94,14 @@ void size_gcn(Plan &p) {
     if (d.has_bias) bwd += colsum_workspace_bytes(n, (int)k);
     bwd += gemm_workspace_bytes(1, 0, m, k, n);
     if (fp) {
-        bwd += align_up((size_t)n * k * fl) + spmm_workspace_bytes(q, (int)k);
+        bwd += align_up((size_t)n * k * fl) + spmm_workspace_bytes(n, q, (int)k);
         p.info.transient_bwd = n * k;
         p.info.spmm_width_bwd = k;
     } else {
         int64_t tr = 0, width = 0;
         if (!cached) { bwd += align_up((size_t)n * m * fl); tr += n * m; width += m; }
         if (dx) { bwd += align_up((size_t)n * m * fl); tr += n * m; width += m; }
-        bwd += spmm_workspace_bytes(q, (int)m);
+        bwd += spmm_workspace_bytes(n, q, (int)m);
         p.info.transient_bwd = tr;
         p.info.spmm_width_bwd = width;
     }
@@ -160,13 +160,13 @@ GatLayout gat_layout(const Plan &p) {
     if (L.c_alpha == (size_t)-1) L.w_alpha = take(q * h * fl);
     L.w_stat = take(n * h * 2 * fl);
     L.w_walk = take(gat_walker_workspace_bytes(q, (int)h));
-    L.w_spmm = take(spmm_workspace_bytes(q, (int)f));
+    L.w_spmm = take(spmm_workspace_bytes(n, q, (int)f));
     L.w_gemm_nn = take(gemm_workspace_bytes(0, 0, n, f, m));
     L.w_gy = take(q * h * fl);
     L.w_sums = take(n * h * 3 * fl);
     L.w_ds = take(n * h * fl);
     L.w_dd = take(n * h * fl);
-    L.w_spmm_h = take(spmm_workspace_bytes(q, (int)h));
+    L.w_spmm_h = take(spmm_workspace_bytes(0, q, (int)h));        // its dense operand has q rows: never padded
     L.w_dM = take(n * f * fl);
     L.w_red = take(colsum_workspace_bytes(n, (int)f));
     L.w_gemm_tn = take(gemm_workspace_bytes(1, 0, m, f, n));

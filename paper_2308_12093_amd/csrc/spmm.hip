@@ -38,6 +38,9 @@ __device__ __forceinline__ float epilogue(float x, const float *bias, int c, int
     return x;
 }
 
+// four floats at a 4-byte aligned address: global dwordx4 accesses need no more than that
+typedef float float4u __attribute__((ext_vector_type(4), aligned(4)));
+
 template <int N> struct IntVec;
 template <> struct IntVec<8> { int4 a, b; __device__ int get(int i) const { const int4 &q = i < 4 ? a : b; i &= 3; return i == 0 ? q.x : i == 1 ? q.y : i == 2 ? q.z : q.w; } };
 template <> struct IntVec<4> { int4 a; __device__ int get(int i) const { return i == 0 ? a.x : i == 1 ? a.y : i == 2 ? a.z : a.w; } };
@@ -60,9 +63,13 @@ struct SegInfo {
     int32_t active;        // the segment exists
 };
 
-template <int VEC, int LPE, int NT, int U, bool HEADS>
+// B has a row stride of ldb floats.  UA (VEC = 4 only) serves an f that is not a multiple of 4: B is then a
+// copy padded to ldb = f rounded up (16-byte aligned rows, zeros in the padding), while the rows of C and
+// `part` keep the stride f: whole groups of four go out as one 4-byte aligned 16-byte store, the lane that
+// holds the ragged end of a row stores its one to three values one by one.
+template <int VEC, int LPE, int NT, int U, bool HEADS, bool UA = false>
 __global__ void __launch_bounds__(256)
-spmm_seg_kernel(int nnz, int f, int seg, long nseg, const int32_t *__restrict__ erow,
+spmm_seg_kernel(int nnz, int f, int ldb, int seg, long nseg, const int32_t *__restrict__ erow,
                 const int32_t *__restrict__ col, EdgeWeights w, const float *__restrict__ B,
                 float *__restrict__ C, float *__restrict__ part, const float *__restrict__ bias, int relu) {
     extern __shared__ __align__(16) int32_t smem[];
@@ -134,7 +141,21 @@ spmm_seg_kernel(int nnz, int f, int seg, long nseg, const int32_t *__restrict__ 
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             if (!fok[t]) continue;
-            if constexpr (VEC == 4) {
+            if constexpr (VEC == 4 && UA) {
+                if (foff[t] + 4 <= f) {
+                    float4u o;
+                    o.x = with_epilogue ? epilogue(acc[t][0], bias, foff[t] + 0, relu) : acc[t][0];
+                    o.y = with_epilogue ? epilogue(acc[t][1], bias, foff[t] + 1, relu) : acc[t][1];
+                    o.z = with_epilogue ? epilogue(acc[t][2], bias, foff[t] + 2, relu) : acc[t][2];
+                    o.w = with_epilogue ? epilogue(acc[t][3], bias, foff[t] + 3, relu) : acc[t][3];
+                    *reinterpret_cast<float4u *>(dst + foff[t]) = o;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 3; ++i)
+                        if (foff[t] + i < f)
+                            dst[foff[t] + i] = with_epilogue ? epilogue(acc[t][i], bias, foff[t] + i, relu) : acc[t][i];
+                }
+            } else if constexpr (VEC == 4) {
                 float4 o;
                 o.x = with_epilogue ? epilogue(acc[t][0], bias, foff[t] + 0, relu) : acc[t][0];
                 o.y = with_epilogue ? epilogue(acc[t][1], bias, foff[t] + 1, relu) : acc[t][1];
@@ -178,7 +199,7 @@ spmm_seg_kernel(int nnz, int f, int seg, long nseg, const int32_t *__restrict__ 
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
                     if (fok[t]) {
-                        const float *src = B + (size_t)c[u] * f + foff[t];
+                        const float *src = B + (size_t)c[u] * ldb + foff[t];
                         if constexpr (VEC == 4) {
                             const float4 q = *reinterpret_cast<const float4 *>(src);
                             b[u][t][0] = q.x; b[u][t][1] = q.y; b[u][t][2] = q.z; b[u][t][3] = q.w;
@@ -294,7 +315,7 @@ spmm_fixup_kernel(int n, int nnz, int f, int span, long nspan, int lpf, const in
     if (s > 0 && erow[s - 1] == r) return;                 // the row began earlier: its first span owns it
     const long g_end = ((long)rowptr[r + 1] - 1) / span;
 
-    const int fc = f / VEC;                                // VEC-wide chunks of one row
+    const int fc = (f + VEC - 1) / VEC;                    // VEC-wide chunks of one row (the last may be ragged)
     const int slots = kWave / lpf, slot = lane / lpf, l = lane % lpf;
     for (int cb = 0; cb < fc; cb += lpf) {
         const int c = (cb + l) * VEC;
@@ -310,10 +331,12 @@ spmm_fixup_kernel(int n, int nnz, int f, int span, long nspan, int lpf, const in
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
-                    for (int i = 0; i < VEC; ++i) a[j][i] += part[(size_t)(2 * (x + (long)j * slots)) * f + c + i];
+                    for (int i = 0; i < VEC; ++i)
+                        if (c + i < f) a[j][i] += part[(size_t)(2 * (x + (long)j * slots)) * f + c + i];
             for (; x <= g_end; x += slots)                   // fewer than four left
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) a[0][i] += part[(size_t)(2 * x) * f + c + i];
+                for (int i = 0; i < VEC; ++i)
+                    if (c + i < f) a[0][i] += part[(size_t)(2 * x) * f + c + i];
         }
         float t[VEC];
 #pragma unroll
@@ -324,7 +347,8 @@ spmm_fixup_kernel(int n, int nnz, int f, int span, long nspan, int lpf, const in
         if (ok && slot == 0)
 #pragma unroll
             for (int i = 0; i < VEC; ++i)
-                C[(size_t)r * f + c + i] = epilogue(part[(size_t)(2 * g + 1) * f + c + i] + t[i], bias, c + i, relu);
+                if (c + i < f)
+                    C[(size_t)r * f + c + i] = epilogue(part[(size_t)(2 * g + 1) * f + c + i] + t[i], bias, c + i, relu);
     }
 }
 
@@ -361,6 +385,18 @@ struct Shape {
     int vec, lpe, nt, tiles_y;
 };
 
+// widths that are not a multiple of 4 (and wide enough to gain from it) run on a padded copy of B
+bool padded_operand(int f) { return f % 4 != 0 && f > 4; }
+
+__global__ void __launch_bounds__(256)
+pad_rows_kernel(long n, int f, int fp, const float *__restrict__ B, float *__restrict__ Bp) {
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n * fp) return;
+    const long r = i / fp;
+    const int c = (int)(i - r * fp);
+    Bp[i] = c < f ? B[r * f + c] : 0.f;
+}
+
 Shape pick_shape(int f, bool vec4) {
     Shape sh;
     sh.vec = vec4 ? 4 : 1;
@@ -380,7 +416,7 @@ Shape pick_shape(int f, bool vec4) {
 // about eight wavefronts per SIMD (256 CUs x 4 SIMDs x 8 = 8192 wavefronts), and short
 // enough that the index data of a block's segments fits a 24 KB LDS staging area.
 int spmm_segment_len(int64_t nnz, int f) {
-    const Shape sh = pick_shape(f, f % 4 == 0);
+    const Shape sh = pick_shape(f, f % 4 == 0 || padded_operand(f));
     const int64_t groups_per_wave = kWave / sh.lpe;
     const int64_t want_groups = 8192 * groups_per_wave;
     const int64_t seg = nnz / (want_groups > 0 ? want_groups : 1);
@@ -392,13 +428,20 @@ int spmm_segment_len(int64_t nnz, int f) {
 
 // Two partial rows per block of the first kernel.  The block count depends on whether the
 // float4 path can be taken (pointer alignment is only known at launch): size for the larger.
-size_t spmm_workspace_bytes(int64_t nnz, int f) {
+static size_t partials_bytes(int64_t nnz, int f) {
     if (nnz <= 0) return kAlign;
     const int seg = spmm_segment_len(nnz, f);
-    const int64_t span4 = (int64_t)(256 / pick_shape(f, f % 4 == 0).lpe) * seg;
+    const int64_t span4 = (int64_t)(256 / pick_shape(f, f % 4 == 0 || padded_operand(f)).lpe) * seg;
     const int64_t span1 = (int64_t)(256 / pick_shape(f, false).lpe) * seg;
     const int64_t span = span4 < span1 ? span4 : span1;
     return align_up((size_t)(2 * ceil_div(nnz, span)) * (size_t)f * sizeof(float));
+}
+
+// ... followed, for a ragged width, by the padded copy of the dense operand
+size_t spmm_workspace_bytes(int64_t n, int64_t nnz, int f) {
+    size_t bytes = partials_bytes(nnz, f);
+    if (padded_operand(f) && nnz > 0 && n > 0) bytes += align_up((size_t)n * ((f + 3) / 4 * 4) * sizeof(float));
+    return bytes;
 }
 
 #define SPMM_CASE(VEC_, LPE_, NT_, U_)                                                                       \
@@ -409,15 +452,18 @@ size_t spmm_workspace_bytes(int64_t nnz, int f) {
                            (size_t)2 * GPB_ * (LPE_ * VEC_ * NT_) * sizeof(float) + GPB_ * sizeof(SegInfo);  \
         if (heads)                                                                                           \
             hipLaunchKernelGGL((spmm_seg_kernel<VEC_, LPE_, NT_, U_, true>), grid, dim3(256), lds, st, nnz,  \
-                               f, seg, nseg, erow, col, w, B, C, part, bias, relu);                          \
+                               f, f, seg, nseg, erow, col, w, B, C, part, bias, relu);                       \
+        else if (VEC_ == 4 && ragged)                                                                        \
+            hipLaunchKernelGGL((spmm_seg_kernel<VEC_, LPE_, NT_, U_, false, VEC_ == 4>), grid, dim3(256),    \
+                               lds, st, nnz, f, fp, seg, nseg, erow, col, w, Bp, C, part, bias, relu);       \
         else                                                                                                 \
             hipLaunchKernelGGL((spmm_seg_kernel<VEC_, LPE_, NT_, U_, false>), grid, dim3(256), lds, st, nnz, \
-                               f, seg, nseg, erow, col, w, B, C, part, bias, relu);                          \
+                               f, f, seg, nseg, erow, col, w, B, C, part, bias, relu);                       \
         launched = true;                                                                                     \
     }
 
 gnn_status_t spmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *col, const int32_t *erow,
-                         EdgeWeights w, const float *B, int f, float *C, const float *bias, int relu,
+                         EdgeWeights w, const float *B, long b_rows, int f, float *C, const float *bias, int relu,
                          void *workspace, hipStream_t st) {
     if (n <= 0 || f <= 0) return GNN_OK;
     if (w.heads < 1) w.heads = 1;
@@ -431,9 +477,20 @@ gnn_status_t spmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *c
     }
 
     float *part = static_cast<float *>(workspace);
-    const bool vec4 = f % 4 == 0 && aligned16(B) && aligned16(C) && aligned16(part) &&
-                      (!heads || w.head_dim % 4 == 0);
+    const bool aligned = f % 4 == 0 && aligned16(B) && aligned16(C) && aligned16(part);
+    // a ragged width still takes four features per lane, on a padded copy of B (one weight per entry only:
+    // a lane's four features must share a head)
+    const bool ragged = padded_operand(f) && !heads && b_rows > 0;
+    const bool vec4 = ragged || (aligned && (!heads || w.head_dim % 4 == 0));
     const Shape sh = pick_shape(f, vec4);
+    const int fp = (f + 3) / 4 * 4;
+    float *Bp = nullptr;
+    if (ragged) {
+        Bp = reinterpret_cast<float *>(static_cast<char *>(workspace) + partials_bytes(nnz, f));
+        hipLaunchKernelGGL(pad_rows_kernel, dim3((unsigned)ceil_div(b_rows * fp, 256)), dim3(256), 0, st, b_rows, f,
+                           fp, B, Bp);
+        GNN_TRY(launch_status());
+    }
     const int seg = spmm_segment_len(nnz, f);
     const long nseg = ceil_div(nnz, seg);
 
@@ -450,7 +507,7 @@ gnn_status_t spmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *c
     // second kernel: one wavefront per block span of the first, and per 64 rows for the empty-row fill
     const int span = (256 / sh.lpe) * seg;
     const long nspan = ceil_div(nnz, span);
-    int lpf = pow2_at_least(f / sh.vec);                   // lanes per slot: one per VEC-wide chunk of a row
+    int lpf = pow2_at_least((f + sh.vec - 1) / sh.vec);    // lanes per slot: one per VEC-wide chunk of a row
     if (lpf > kWave) lpf = kWave;
     const long waves = nspan > ceil_div(n, kWave) ? nspan : ceil_div(n, kWave);
     if (sh.vec == 4)

@@ -101,6 +101,34 @@ def test_spmm_matches_oracle(B, f, balanced):
     assert_close(run_spmm(B, rp, c, val, Bm, balanced=balanced), ref, f"spmm f={f}")
 
 
+@pytest.mark.parametrize("f", [4, 5, 7, 30, 47, 130, 301])
+def test_spmm_rows_that_are_not_16_byte_aligned(B, f):
+    """Ragged widths, and operands that start 4 bytes into an allocation: the four-wide kernel moves whole
+    rows with unaligned 16-byte accesses and the ragged end of a row value by value; bias and ReLU included."""
+    rowptr, col = rmat_small()
+    rp, c, deg = oracle.add_self_loops_degree(rowptr, col)
+    n = rp.size - 1
+    val = oracle.gcn_normalize(rp, c, deg).astype(np.float32)
+    rng = np.random.default_rng(100 + f)
+    Bm = rng.standard_normal((n, f), dtype=np.float32)
+    bias = rng.standard_normal(f, dtype=np.float32)
+    ref = np.maximum(oracle.spmm(rp, c, val, Bm) + bias, 0.0)
+    d_rp, d_c, d_val = dev(rp), dev(c), dev(val)
+    erow = torch.empty(c.size, dtype=torch.int32, device="cuda")
+    B.gnn_expand_ptr(n, c.size, d_rp, erow)
+    ws = B.alloc(B.gnn_spmm_workspace_bytes(n, c.size, f))
+    for shift_b, shift_c in ((0, 0), (1, 0), (0, 1), (1, 3)):
+        Bbuf = torch.zeros(n * f + 4, dtype=torch.float32, device="cuda")
+        Cbuf = torch.full((n * f + 4,), float("nan"), dtype=torch.float32, device="cuda")
+        Bv, Cv = Bbuf[shift_b:shift_b + n * f].view(n, f), Cbuf[shift_c:shift_c + n * f].view(n, f)
+        Bv.copy_(dev(Bm))
+        B.gnn_spmm_csr(n, c.size, d_rp, d_c, d_val, erow, Bv, f, Cv, dev(bias), True, ws)
+        torch.cuda.synchronize()
+        assert_close(host(Cv), ref, f"f={f} shifts {shift_b},{shift_c}")
+        out = host(Cbuf)
+        assert np.all(np.isnan(out[:shift_c])) and np.all(np.isnan(out[shift_c + n * f:]))   # nothing written outside
+
+
 def test_spmm_epilogue_unit_weights_and_empty_rows(B):
     rowptr, col = rmat_small(11, 6, directed=True)                 # no self-loops: many empty rows
     assert (np.diff(rowptr) == 0).sum() > 100

@@ -436,14 +436,19 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
                 for (int y = 0; y < TN; ++y) {
                     const float bj = FAST ? (bias ? bcol[y] : 0.f) : (bias ? bias[cn0 + (wn * TN + y) * 32 + l32] : 0.f);
 #pragma unroll
-                    for (int x = 0; x < TM; ++x)
+                    for (int x = 0; x < TM; ++x) {
+                        // what C holds, a whole 32 x 32 tile's worth of loads in flight before the first store
+                        // (loads and stores go through the same pointer, so the compiler would not reorder them)
+                        float held[16];
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) held[v] = (relu & kActAccumulate) ? *at(x, y, v) : 0.f;
 #pragma unroll
                         for (int v = 0; v < 16; ++v) {
-                            float o = acc[x][y][v] + bj;
-                            if (relu & kActAccumulate) o += *at(x, y, v);
+                            float o = acc[x][y][v] + bj + held[v];
                             if (relu & kActRelu) o = fmaxf(o, 0.f);
                             put(x, y, v, o);
                         }
+                    }
                 }
             }
         } else {

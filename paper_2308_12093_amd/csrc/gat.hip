@@ -22,33 +22,45 @@ namespace {
 __device__ __forceinline__ float leaky(float y, float slope) { return y > 0.f ? y : slope * y; }
 
 // ---- s_i = <a_src, m_i>, d_i = <a_dst, m_i> per head (App. B) ------------------------
-// One thread per (node, head); VEC = 4 reads the k features as float4.
-template <int VEC>
+// VEC = 1: one thread per (node, head).  VEC = 4: L lanes per (node, head), lane l takes the float4 chunks
+// l, l + L, ... of the k features (L * 4 <= k, so a wavefront reads consecutive memory), partial dot
+// products are combined by a fixed xor tree.
+template <int VEC, int L>
 __global__ void __launch_bounds__(256)
 node_attention_kernel(long count, int h, int k, const float *__restrict__ M, const float *__restrict__ a_src,
                       const float *__restrict__ a_dst, float *__restrict__ s, float *__restrict__ d) {
-    const long t = (long)blockIdx.x * 256 + threadIdx.x;      // t = i * h + p
-    if (t >= count) return;
-    const int p = count < (1L << 31) ? (int)((unsigned)t % (unsigned)h) : (int)(t % h);
-    const float *m = M + (size_t)t * k;
-    const float *as = a_src + (size_t)p * k, *ad = a_dst + (size_t)p * k;
+    const long t = ((long)blockIdx.x * 256 + threadIdx.x) / L;      // t = i * h + p
+    const int l = threadIdx.x % L;
+    const bool live = t < count;
     float ss = 0.f, dd = 0.f;
-    if constexpr (VEC == 4) {
-        for (int c = 0; c < k; c += 4) {
-            const float4 v = *reinterpret_cast<const float4 *>(m + c);
-            const float4 u = *reinterpret_cast<const float4 *>(as + c), w = *reinterpret_cast<const float4 *>(ad + c);
-            ss = fmaf(u.x, v.x, ss); ss = fmaf(u.y, v.y, ss); ss = fmaf(u.z, v.z, ss); ss = fmaf(u.w, v.w, ss);
-            dd = fmaf(w.x, v.x, dd); dd = fmaf(w.y, v.y, dd); dd = fmaf(w.z, v.z, dd); dd = fmaf(w.w, v.w, dd);
-        }
-    } else {
-        for (int c = 0; c < k; ++c) {
-            const float v = m[c];
-            ss = fmaf(as[c], v, ss);
-            dd = fmaf(ad[c], v, dd);
+    if (live) {
+        const int p = count < (1L << 31) ? (int)((unsigned)t % (unsigned)h) : (int)(t % h);
+        const float *m = M + (size_t)t * k;
+        const float *as = a_src + (size_t)p * k, *ad = a_dst + (size_t)p * k;
+        if constexpr (VEC == 4) {
+            for (int c = 4 * l; c < k; c += 4 * L) {
+                const float4 v = *reinterpret_cast<const float4 *>(m + c);
+                const float4 u = *reinterpret_cast<const float4 *>(as + c), w = *reinterpret_cast<const float4 *>(ad + c);
+                ss = fmaf(u.x, v.x, ss); ss = fmaf(u.y, v.y, ss); ss = fmaf(u.z, v.z, ss); ss = fmaf(u.w, v.w, ss);
+                dd = fmaf(w.x, v.x, dd); dd = fmaf(w.y, v.y, dd); dd = fmaf(w.z, v.z, dd); dd = fmaf(w.w, v.w, dd);
+            }
+        } else {
+            for (int c = 0; c < k; ++c) {
+                const float v = m[c];
+                ss = fmaf(as[c], v, ss);
+                dd = fmaf(ad[c], v, dd);
+            }
         }
     }
-    s[t] = ss;
-    d[t] = dd;
+#pragma unroll
+    for (int o = L >> 1; o > 0; o >>= 1) {
+        ss += __shfl_xor(ss, o);
+        dd += __shfl_xor(dd, o);
+    }
+    if (live && l == 0) {
+        s[t] = ss;
+        d[t] = dd;
+    }
 }
 
 // ---- entry-balanced reduction over the rows, one lane per head -----------------------
@@ -503,12 +515,19 @@ gnn_status_t gat_node_attention_launch(int n, int h, int k, const float *M, cons
                                        float *s, float *d, hipStream_t st) {
     const long count = (long)n * h;
     if (count <= 0) return GNN_OK;
-    if (k % 4 == 0 && aligned16(M) && aligned16(a_src) && aligned16(a_dst))
-        hipLaunchKernelGGL(node_attention_kernel<4>, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count, h,
-                           k, M, a_src, a_dst, s, d);
-    else
-        hipLaunchKernelGGL(node_attention_kernel<1>, dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count, h,
-                           k, M, a_src, a_dst, s, d);
+    if (k % 4 == 0 && aligned16(M) && aligned16(a_src) && aligned16(a_dst)) {
+        int L = 1;                                          // lanes per (node, head): a power of two <= min(k / 4, 16)
+        while (L < 16 && 8 * L <= k) L <<= 1;
+#define NODE_ATT_CASE(L_)                                                                                         \
+        if (L == L_)                                                                                              \
+            hipLaunchKernelGGL((node_attention_kernel<4, L_>), dim3((unsigned)ceil_div(count * L_, 256)), dim3(256), \
+                               0, st, count, h, k, M, a_src, a_dst, s, d);
+        NODE_ATT_CASE(1) NODE_ATT_CASE(2) NODE_ATT_CASE(4) NODE_ATT_CASE(8) NODE_ATT_CASE(16)
+#undef NODE_ATT_CASE
+    } else {
+        hipLaunchKernelGGL((node_attention_kernel<1, 1>), dim3((unsigned)ceil_div(count, 256)), dim3(256), 0, st, count,
+                           h, k, M, a_src, a_dst, s, d);
+    }
     return launch_status();
 }
 

@@ -168,7 +168,7 @@ spmm_ell_kernel(int n, int t, const int32_t *__restrict__ ell_col, const float *
 }
 
 // Coordinate SpMM: C += A B, entry by entry (App. D.2).  A group of LANES threads takes
-// a run of consecutive entries (kCooRun, or kCooBatch for a small matrix; kCooBatch gathers in flight) and a tile of
+// kCooRun consecutive entries (in batches of kCooBatch gathers in flight) and a tile of
 // LANES * VEC features; it adds up products while the row stays the same and sends the
 // sum to C with floating-point atomics when the row changes, so sorted input costs one
 // atomic per (row run, feature) and unsorted input still works.  The order of the atomic
@@ -301,8 +301,7 @@ gnn_status_t spmm_coo_launch(int64_t nnz, const int32_t *row, const int32_t *col
     if (nnz <= 0 || f <= 0) return GNN_OK;
     const int vec = f % 4 == 0 && aligned16(B) ? 4 : 1;
     const int lanes = pick_lanes(f, vec, 32);
-    // long runs save atomics on sorted input; short ones keep a small matrix spread over the chip
-    const int run = nnz >= (long)kCooRun * (256 / lanes) * 2048 ? kCooRun : kCooBatch;      // >= 2048 blocks
+    const int run = kCooRun;      // shorter runs for small matrices were measured: more atomics, never faster
     COO_CASE(4, 4) COO_CASE(8, 4) COO_CASE(16, 4) COO_CASE(32, 4)
     COO_CASE(4, 1) COO_CASE(8, 1) COO_CASE(16, 1) COO_CASE(32, 1)
     return GNN_ERR_UNSUPPORTED;

@@ -294,7 +294,7 @@ spmm_seg_kernel(int nnz, int f, int ldb, int seg, long nseg, const int32_t *__re
 //      are then combined by a fixed shuffle tree: a hub row that spans hundreds of
 //      blocks is summed in parallel, and always in the same order.
 //  (2) lane i of wavefront w gives row 64 w + i the epilogue of zero if it is empty.
-template <int VEC>
+template <int VEC, bool RAGGED>                           // RAGGED: f is not a multiple of VEC
 __global__ void __launch_bounds__(256)
 spmm_fixup_kernel(int n, int nnz, int f, int span, long nspan, int lpf, const int32_t *__restrict__ erow,
                   const int32_t *__restrict__ rowptr, const float *__restrict__ part, float *__restrict__ C,
@@ -332,11 +332,11 @@ spmm_fixup_kernel(int n, int nnz, int f, int span, long nspan, int lpf, const in
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int i = 0; i < VEC; ++i)
-                        if (c + i < f) a[j][i] += part[(size_t)(2 * (x + (long)j * slots)) * f + c + i];
+                        if (!RAGGED || c + i < f) a[j][i] += part[(size_t)(2 * (x + (long)j * slots)) * f + c + i];
             for (; x <= g_end; x += slots)                   // fewer than four left
 #pragma unroll
                 for (int i = 0; i < VEC; ++i)
-                    if (c + i < f) a[0][i] += part[(size_t)(2 * x) * f + c + i];
+                    if (!RAGGED || c + i < f) a[0][i] += part[(size_t)(2 * x) * f + c + i];
         }
         float t[VEC];
 #pragma unroll
@@ -347,7 +347,7 @@ spmm_fixup_kernel(int n, int nnz, int f, int span, long nspan, int lpf, const in
         if (ok && slot == 0)
 #pragma unroll
             for (int i = 0; i < VEC; ++i)
-                if (c + i < f)
+                if (!RAGGED || c + i < f)
                     C[(size_t)r * f + c + i] = epilogue(part[(size_t)(2 * g + 1) * f + c + i] + t[i], bias, c + i, relu);
     }
 }
@@ -510,12 +510,15 @@ gnn_status_t spmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *c
     int lpf = pow2_at_least((f + sh.vec - 1) / sh.vec);    // lanes per slot: one per VEC-wide chunk of a row
     if (lpf > kWave) lpf = kWave;
     const long waves = nspan > ceil_div(n, kWave) ? nspan : ceil_div(n, kWave);
-    if (sh.vec == 4)
-        hipLaunchKernelGGL(spmm_fixup_kernel<4>, dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, st, n, nnz, f, span,
-                           nspan, lpf, erow, rowptr, part, C, bias, relu);
+    if (sh.vec == 4 && ragged)
+        hipLaunchKernelGGL((spmm_fixup_kernel<4, true>), dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, st, n, nnz, f,
+                           span, nspan, lpf, erow, rowptr, part, C, bias, relu);
+    else if (sh.vec == 4)
+        hipLaunchKernelGGL((spmm_fixup_kernel<4, false>), dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, st, n, nnz, f,
+                           span, nspan, lpf, erow, rowptr, part, C, bias, relu);
     else
-        hipLaunchKernelGGL(spmm_fixup_kernel<1>, dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, st, n, nnz, f, span,
-                           nspan, lpf, erow, rowptr, part, C, bias, relu);
+        hipLaunchKernelGGL((spmm_fixup_kernel<1, false>), dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, st, n, nnz, f,
+                           span, nspan, lpf, erow, rowptr, part, C, bias, relu);
     return launch_status();
 }
 

@@ -308,7 +308,9 @@ gnn_status_t gnn_gather_f32(int64_t count, const float *in, const int32_t *perm,
  * gnn_spmm_csr - C = A B (App. E.1).  B, C [n, f].  val NULL = all ones.
  *   erow: optional expanded row index (see gnn_graph_t); selects the entry-balanced kernel.
  *   bias [f] or NULL, relu: fused epilogue C = relu(A B + 1 b^T).
- *   workspace: gnn_spmm_workspace_bytes(n, nnz, f) bytes (only used with erow).
+ *   workspace: gnn_spmm_workspace_bytes(n, nnz, f) bytes (only used with erow): partial rows of the
+ *   blocks and, when f is not a multiple of 4, a copy of B with rows padded to the next multiple of 4.
+ *   B and C may start at any 4-byte aligned address; 16-byte aligned rows take the fastest kernel.
  */
 gnn_status_t gnn_spmm_csr(int32_t n, int32_t nnz, const int32_t *rowptr, const int32_t *col, const float *val,
                           const int32_t *erow, const float *B, int32_t f, float *C,

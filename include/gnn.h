@@ -97,7 +97,7 @@ typedef enum {
  *              required by gat_layer_bwd).
  *              Needed by every backward pass unless `symmetric` is set.
  *   symmetric  nonzero promises A'^T == A' (pattern and values); the CSC arrays
- *              are then ignored and may be NULL.  Only meaningful for GCN.
+ *              are then ignored and may be NULL.  Only meaningful for GCN and SAGE.
  */
 typedef struct {
     int32_t n, nnz;
@@ -115,16 +115,16 @@ typedef struct {
     int32_t n, nnz;           /* nodes, stored entries (self-loops included)                    */
     int32_t f_in;             /* m                                                              */
     int32_t f_out;            /* k, per head for GAT                                            */
-    int32_t heads;            /* GAT only (GCN: 1)                                              */
+    int32_t heads;            /* GAT only (GCN, SAGE: 1)                                        */
     int32_t need_input_grad;  /* 0: backward skips dX (first layer of a network)                */
     int32_t has_bias;         /* forward adds b, backward writes db                             */
-    int32_t fuse_relu;        /* GCN only: forward applies ReLU, backward masks dY by [Y > 0]   */
+    int32_t fuse_relu;        /* GCN, SAGE: forward applies ReLU, backward masks dY by [Y > 0]  */
     float leaky_slope;        /* GAT only: beta of LeakyReLU                                    */
     gnn_order_t order;        /* AUTO or a forced choice                                        */
     gnn_bwd_t bwd;
     gnn_cache_t cache;
-    gnn_select_t selection;   /* GCN: how AUTO decides                                          */
-    int32_t constant_input;   /* GCN with the A'X cache: the caller promises that X and the graph
+    gnn_select_t selection;   /* GCN, SAGE: how AUTO decides                                    */
+    int32_t constant_input;   /* GCN, SAGE with the A'X cache: the caller promises that X and the graph
                                  are the same in every forward call until gnn_plan_reset_cache
                                  (a first layer whose input features never change).  Forward then
                                  computes A'X only while the cache is empty, and AUTO counts that

@@ -128,7 +128,7 @@ typedef struct {
                                  are the same in every forward call until gnn_plan_reset_cache
                                  (a first layer whose input features never change).  Forward then
                                  computes A'X only while the cache is empty, and AUTO counts that
-                                 SpMM as free.  X itself is only read by that first call.          */
+                                 SpMM as free.  A GCN layer reads X only in that first call.       */
     int32_t fuse_elu;         /* GAT only: forward applies ELU (alpha = 1) after the bias, backward
                                  multiplies dY by its derivative taken from the output Y            */
 } gnn_plan_desc_t;

@@ -12,7 +12,9 @@
  *    gnn_graph_t themselves are HOST structs (holding device pointers).
  *  - The library allocates no device memory.  Every scratch byte comes from the
  *    caller's `workspace` (size reported by gnn_plan_query / the *_workspace_bytes
- *    helpers; must be 256-byte aligned).
+ *    helpers; must be 256-byte aligned).  Every call that takes a `cache` or a
+ *    `workspace` also takes its size in bytes and returns GNN_ERR_BUFFER_TOO_SMALL,
+ *    before any launch, when that is below what gnn_plan_query reported for the plan.
  *  - Every call only enqueues kernels on `hip_stream` (a hipStream_t passed as
  *    void*; NULL = the default stream) and returns; there is no host
  *    synchronisation unless the entry point says otherwise.
@@ -186,13 +188,15 @@ double gnn_spmm_time_model_us(int64_t n, int64_t nnz, int32_t f);
 /*
  * gcn_layer_fwd - Y = A' X W + 1 b^T (Eq. gcn-fwd), optionally ReLU.
  *   X [n, f_in], W [f_in, f_out], b [f_out] or NULL, Y [n, f_out]           (device)
- *   cache      cache_bytes; written when the plan caches A'X, may be NULL otherwise
- *   workspace  workspace_bytes
+ *   cache      cache_bytes >= the plan's; written when the plan caches A'X, may be NULL (size 0) otherwise
+ *   workspace  workspace_bytes >= the plan's
  * Errors: INVALID_ARG (NULL X / W / Y, b missing while has_bias), BAD_GRAPH
- * (n / nnz differ from the plan, csr arrays or csr_val NULL).
+ * (n / nnz differ from the plan, csr arrays or csr_val NULL), BUFFER_TOO_SMALL (cache or
+ * workspace smaller than gnn_plan_query reports).
  */
 gnn_status_t gcn_layer_fwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W,
-                           const float *b, float *Y, void *cache, void *workspace, void *hip_stream);
+                           const float *b, float *Y, void *cache, size_t cache_bytes,
+                           void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * gcn_layer_bwd - dW = X^T A'^T dY, db = dY^T 1, dX = A'^T dY W^T (Eqs. gcn-bwd-*).
@@ -206,7 +210,8 @@ gnn_status_t gcn_layer_fwd(gnn_plan_t *plan, const gnn_graph_t *graph, const flo
  */
 gnn_status_t gcn_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W,
                            const float *Y, const float *dY, float *dW, float *db, float *dX,
-                           void *cache, void *workspace, void *hip_stream);
+                           void *cache, size_t cache_bytes, void *workspace, size_t workspace_bytes,
+                           void *hip_stream);
 
 /*
  * sage_layer_fwd / sage_layer_bwd - a GraphSAGE layer, the other layer that Sec. 3.1 "Generalizability"
@@ -220,11 +225,12 @@ gnn_status_t gcn_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const flo
  * cache / workspace sizes: gnn_plan_query.  Errors as gcn_layer_fwd / gcn_layer_bwd.
  */
 gnn_status_t sage_layer_fwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W_self,
-                            const float *W_neigh, const float *b, float *Y, void *cache, void *workspace,
-                            void *hip_stream);
+                            const float *W_neigh, const float *b, float *Y, void *cache, size_t cache_bytes,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
 gnn_status_t sage_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W_self,
                             const float *W_neigh, const float *Y, const float *dY, float *dW_self,
-                            float *dW_neigh, float *db, float *dX, void *cache, void *workspace, void *hip_stream);
+                            float *dW_neigh, float *db, float *dX, void *cache, size_t cache_bytes,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * gat_layer_fwd - multi-head GAT forward (Eqs. gat-fwd, gat-fwd-att), heads concatenated.
@@ -241,7 +247,8 @@ gnn_status_t sage_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const fl
  */
 gnn_status_t gat_layer_fwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W,
                            const float *a_src, const float *a_dst, const float *b, float *Y,
-                           void *cache, void *workspace, void *hip_stream);
+                           void *cache, size_t cache_bytes, void *workspace, size_t workspace_bytes,
+                           void *hip_stream);
 
 /*
  * gat_layer_bwd - gradients of Sec. "GAT Backward Pass": dW [f_in, h*k], da_src / da_dst [h, k],
@@ -252,7 +259,8 @@ gnn_status_t gat_layer_fwd(gnn_plan_t *plan, const gnn_graph_t *graph, const flo
 gnn_status_t gat_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W,
                            const float *a_src, const float *a_dst, const float *Y, const float *dY,
                            float *dW, float *da_src, float *da_dst, float *db, float *dX,
-                           void *cache, void *workspace, void *hip_stream);
+                           void *cache, size_t cache_bytes, void *workspace, size_t workspace_bytes,
+                           void *hip_stream);
 
 /* ---- preprocessing: integer kernels and the normalisation (Sec. "GCN Forward Pass") ---- */
 
@@ -307,7 +315,7 @@ gnn_status_t gnn_gather_f32(int64_t count, const float *in, const int32_t *perm,
 /*
  * gnn_spmm_csr - C = A B (App. E.1).  B, C [n, f].  val NULL = all ones.
  *   erow: optional expanded row index (see gnn_graph_t); selects the entry-balanced kernel.
- *   bias [f] or NULL, relu: fused epilogue C = relu(A B + 1 b^T).
+ *   bias [f] or NULL, relu (0 or 1; anything else is GNN_ERR_INVALID_ARG): fused epilogue C = relu(A B + 1 b^T).
  *   workspace: gnn_spmm_workspace_bytes(n, nnz, f) bytes (only used with erow): partial rows of the
  *   blocks and, when f is not a multiple of 4, a copy of B with rows padded to the next multiple of 4.
  *   B and C may start at any 4-byte aligned address; 16-byte aligned rows take the fastest kernel.
@@ -353,15 +361,6 @@ gnn_status_t gnn_spmm_coo(int32_t n, int64_t nnz, const int32_t *row, const int3
 gnn_status_t gnn_spmm_hyb(int32_t n, int32_t t, const int32_t *ell_col, const float *ell_val,
                           int64_t rest_nnz, const int32_t *coo_row, const int32_t *coo_col, const float *coo_val,
                           const float *B, int32_t f, float *C, void *hip_stream);
-
-/*
- * gnn_profile_spmm_events - profiling aid (App. E.1 kernel timing).  While both arguments are
- * non-NULL hipEvent_t handles, every later launch of the entry-balanced SpMM kernel (from
- * gnn_spmm_csr or from a layer) records `start_event` right before and `stop_event` right
- * after that one kernel on the launch stream, so a caller can time the kernel alone.
- * Pass NULL, NULL to switch it off.  Process-wide, not thread-safe; the events stay the caller's.
- */
-void gnn_profile_spmm_events(void *start_event, void *stop_event);
 
 /*
  * gnn_sddmm_csr - D_e = val_e * <B_i, Ct_j> for every stored entry e = (i, j) (App. E.2),

@@ -62,6 +62,7 @@ class gnn_plan_info_t(ctypes.Structure):
                 ("spmm_width_fwd", _i64), ("spmm_width_bwd", _i64)]
 
 
+_BUFS = [_vp, _sz, _vp, _sz, _vp]
 # every symbol the header declares, with its prototype
 _PROTOS = {
     "gnn_status_string": (ctypes.c_char_p, [ctypes.c_int]),
@@ -70,12 +71,13 @@ _PROTOS = {
     "gnn_plan_destroy": (None, [_vp]),
     "gnn_plan_reset_cache": (ctypes.c_int, [_vp]),
     "gnn_spmm_time_model_us": (ctypes.c_double, [_i64, _i64, _i32]),
-    "gcn_layer_fwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 7),
-    "gcn_layer_bwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 10),
-    "sage_layer_fwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 8),
-    "sage_layer_bwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 12),
-    "gat_layer_fwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 9),
-    "gat_layer_bwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 14),
+    # layer calls end with (cache, cache_bytes, workspace, workspace_bytes, hip_stream)
+    "gcn_layer_fwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 4 + _BUFS),
+    "gcn_layer_bwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 7 + _BUFS),
+    "sage_layer_fwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 5 + _BUFS),
+    "sage_layer_bwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 9 + _BUFS),
+    "gat_layer_fwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 6 + _BUFS),
+    "gat_layer_bwd": (ctypes.c_int, [_vp, ctypes.POINTER(gnn_graph_t)] + [_vp] * 11 + _BUFS),
     "gnn_add_self_loops_degree": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(_i32), _vp, _sz, _vp]),
     "gnn_scan_workspace_bytes": (_sz, [_i32]),
     "gnn_gcn_normalize": (ctypes.c_int, [_i32, _vp, _vp, _vp, _vp, _vp]),
@@ -92,7 +94,6 @@ _PROTOS = {
     "gnn_gather_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
     "gnn_spmm_csr": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _sz, _vp]),
     "gnn_spmm_workspace_bytes": (_sz, [_i32, _i32, _i32]),
-    "gnn_profile_spmm_events": (None, [_vp, _vp]),
     "gnn_sddmm_csr": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp]),
     "gnn_gemm": (ctypes.c_int, [_i32, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]),
     "gnn_gemm_workspace_bytes": (_sz, [_i32, _i32, _i64, _i64, _i64]),
@@ -127,6 +128,11 @@ def _stream():
 
 def _nbytes(t):
     return 0 if t is None else t.numel() * t.element_size()
+
+
+def _bufs(cache, workspace):
+    """(cache, cache_bytes, workspace, workspace_bytes, stream): the tail of every layer call."""
+    return _ptr(cache), _nbytes(cache), _ptr(workspace), _nbytes(workspace), _stream()
 
 
 def alloc(nbytes: int, device="cuda"):
@@ -198,35 +204,34 @@ def gnn_status_string(status: int) -> str:
 # ---- layers --------------------------------------------------------------------
 def gcn_layer_fwd(plan: Plan, graph: Graph, X, W, b, Y, cache, workspace):
     _check(lib.gcn_layer_fwd(plan.handle, ctypes.byref(graph.c), _ptr(X), _ptr(W), _ptr(b), _ptr(Y),
-                             _ptr(cache), _ptr(workspace), _stream()), "gcn_layer_fwd")
+                             *_bufs(cache, workspace)), "gcn_layer_fwd")
 
 
 def gcn_layer_bwd(plan: Plan, graph: Graph, X, W, Y, dY, dW, db, dX, cache, workspace):
     _check(lib.gcn_layer_bwd(plan.handle, ctypes.byref(graph.c), _ptr(X), _ptr(W), _ptr(Y), _ptr(dY), _ptr(dW),
-                             _ptr(db), _ptr(dX), _ptr(cache), _ptr(workspace), _stream()), "gcn_layer_bwd")
+                             _ptr(db), _ptr(dX), *_bufs(cache, workspace)), "gcn_layer_bwd")
 
 
 def sage_layer_fwd(plan: Plan, graph: Graph, X, W_self, W_neigh, b, Y, cache, workspace):
     _check(lib.sage_layer_fwd(plan.handle, ctypes.byref(graph.c), _ptr(X), _ptr(W_self), _ptr(W_neigh), _ptr(b),
-                              _ptr(Y), _ptr(cache), _ptr(workspace), _stream()), "sage_layer_fwd")
+                              _ptr(Y), *_bufs(cache, workspace)), "sage_layer_fwd")
 
 
 def sage_layer_bwd(plan: Plan, graph: Graph, X, W_self, W_neigh, Y, dY, dW_self, dW_neigh, db, dX, cache, workspace):
     _check(lib.sage_layer_bwd(plan.handle, ctypes.byref(graph.c), _ptr(X), _ptr(W_self), _ptr(W_neigh), _ptr(Y),
-                              _ptr(dY), _ptr(dW_self), _ptr(dW_neigh), _ptr(db), _ptr(dX), _ptr(cache),
-                              _ptr(workspace), _stream()), "sage_layer_bwd")
+                              _ptr(dY), _ptr(dW_self), _ptr(dW_neigh), _ptr(db), _ptr(dX), *_bufs(cache, workspace)), "sage_layer_bwd")
 
 
 def gat_layer_fwd(plan: Plan, graph: Graph, X, W, a_src, a_dst, b, Y, cache, workspace):
     _check(lib.gat_layer_fwd(plan.handle, ctypes.byref(graph.c), _ptr(X), _ptr(W), _ptr(a_src), _ptr(a_dst),
-                             _ptr(b), _ptr(Y), _ptr(cache), _ptr(workspace), _stream()), "gat_layer_fwd")
+                             _ptr(b), _ptr(Y), *_bufs(cache, workspace)), "gat_layer_fwd")
 
 
 def gat_layer_bwd(plan: Plan, graph: Graph, X, W, a_src, a_dst, dY, dW, da_src, da_dst, db, dX, cache, workspace,
                   Y=None):
     _check(lib.gat_layer_bwd(plan.handle, ctypes.byref(graph.c), _ptr(X), _ptr(W), _ptr(a_src), _ptr(a_dst),
                              _ptr(Y), _ptr(dY), _ptr(dW), _ptr(da_src), _ptr(da_dst), _ptr(db), _ptr(dX),
-                             _ptr(cache), _ptr(workspace), _stream()), "gat_layer_bwd")
+                             *_bufs(cache, workspace)), "gat_layer_bwd")
 
 
 # ---- preprocessing ---------------------------------------------------------------
@@ -313,10 +318,6 @@ def gnn_spmm_coo(n, nnz, row, col, val, B, f, C, accumulate=False):
 def gnn_spmm_hyb(n, t, ell_col, ell_val, rest_nnz, coo_row, coo_col, coo_val, B, f, C):
     _check(lib.gnn_spmm_hyb(n, t, _ptr(ell_col), _ptr(ell_val), rest_nnz, _ptr(coo_row), _ptr(coo_col),
                             _ptr(coo_val), _ptr(B), f, _ptr(C), _stream()), "gnn_spmm_hyb")
-
-
-def gnn_profile_spmm_events(start_event, stop_event):
-    lib.gnn_profile_spmm_events(start_event, stop_event)
 
 
 def gnn_sddmm_csr(n, nnz, erow, col, val, B, Ct, heads, f, D):

@@ -10,6 +10,16 @@ hipStream_t as_stream(void *s) { return static_cast<hipStream_t>(s); }
 
 bool bad_align(const void *p) { return (reinterpret_cast<uintptr_t>(p) % kAlign) != 0; }
 
+// cache / workspace of a layer call against what the plan reported
+gnn_status_t check_buffers(const gnn_plan_t *plan, bool cache_used, const void *cache, size_t cache_bytes,
+                           const void *workspace, size_t workspace_bytes) {
+    if (!workspace || (cache_used && !cache)) return GNN_ERR_INVALID_ARG;
+    if (bad_align(workspace) || (cache && bad_align(cache))) return GNN_ERR_INVALID_ARG;
+    if (workspace_bytes < plan->info.workspace_bytes) return GNN_ERR_BUFFER_TOO_SMALL;
+    if (cache_used && cache_bytes < plan->info.cache_bytes) return GNN_ERR_BUFFER_TOO_SMALL;
+    return GNN_OK;
+}
+
 gnn_status_t check_graph(const gnn_plan_t *plan, const gnn_graph_t *g, bool need_val, bool need_transpose,
                          bool need_perm) {
     if (!g) return GNN_ERR_INVALID_ARG;
@@ -59,80 +69,77 @@ gnn_status_t gnn_plan_reset_cache(gnn_plan_t *plan) {
 double gnn_spmm_time_model_us(int64_t n, int64_t nnz, int32_t f) { return spmm_time_model_us(n, nnz, f); }
 
 gnn_status_t gcn_layer_fwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W,
-                           const float *b, float *Y, void *cache, void *workspace, void *hip_stream) {
+                           const float *b, float *Y, void *cache, size_t cache_bytes,
+                           void *workspace, size_t workspace_bytes, void *hip_stream) {
     if (!plan || plan->desc.layer != GNN_LAYER_GCN) return GNN_ERR_INVALID_ARG;
     GNN_TRY(check_graph(plan, graph, true, false, false));
-    if (!X || !W || !Y || !workspace) return GNN_ERR_INVALID_ARG;
+    if (!X || !W || !Y) return GNN_ERR_INVALID_ARG;
     if (plan->desc.has_bias && !b) return GNN_ERR_INVALID_ARG;
-    if (plan->info.cache == GNN_CACHE_AX && !cache) return GNN_ERR_INVALID_ARG;
-    if (bad_align(workspace) || (cache && bad_align(cache))) return GNN_ERR_INVALID_ARG;
+    GNN_TRY(check_buffers(plan, plan->info.cache == GNN_CACHE_AX, cache, cache_bytes, workspace, workspace_bytes));
     if (plan->desc.n == 0) return GNN_OK;
     return gcn_forward(*plan, *graph, X, W, b, Y, cache, workspace, as_stream(hip_stream));
 }
 
 gnn_status_t gcn_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W,
                            const float *Y, const float *dY, float *dW, float *db, float *dX,
-                           void *cache, void *workspace, void *hip_stream) {
+                           void *cache, size_t cache_bytes, void *workspace, size_t workspace_bytes,
+                           void *hip_stream) {
     if (!plan || plan->desc.layer != GNN_LAYER_GCN) return GNN_ERR_INVALID_ARG;
     const bool cached = plan->info.cache == GNN_CACHE_AX;
     const bool needs_t = !graph || !graph->symmetric;
     const bool runs_spmm_t = plan->info.bwd == GNN_BWD_FUSED_PROPAGATE || plan->desc.need_input_grad;
     GNN_TRY(check_graph(plan, graph, true, needs_t && runs_spmm_t, graph && !graph->csc_val));
-    if (!W || !dY || !dW || !workspace) return GNN_ERR_INVALID_ARG;
+    if (!W || !dY || !dW) return GNN_ERR_INVALID_ARG;
     if (!cached && !X) return GNN_ERR_INVALID_ARG;
     if (plan->desc.fuse_relu && !Y) return GNN_ERR_INVALID_ARG;
     if (plan->desc.has_bias && !db) return GNN_ERR_INVALID_ARG;
     if (plan->desc.need_input_grad && !dX) return GNN_ERR_INVALID_ARG;
-    if (cached && !cache) return GNN_ERR_INVALID_ARG;
-    if (bad_align(workspace) || (cache && bad_align(cache))) return GNN_ERR_INVALID_ARG;
+    GNN_TRY(check_buffers(plan, cached, cache, cache_bytes, workspace, workspace_bytes));
     if (cached && !plan->cache_filled) return GNN_ERR_STATE;
     if (plan->desc.n == 0) {
-        // an empty graph has zero gradients; dW / db still have to be written
+        // an empty graph has zero gradients; dW / db still have to be written (by a kernel of the library:
+        // a memset node would not survive HIP graph capture of the call)
         hipStream_t st = as_stream(hip_stream);
-        if (hipMemsetAsync(dW, 0, sizeof(float) * plan->desc.f_in * plan->desc.f_out, st) != hipSuccess)
-            return GNN_ERR_HIP;
-        if (plan->desc.has_bias && hipMemsetAsync(db, 0, sizeof(float) * plan->desc.f_out, st) != hipSuccess)
-            return GNN_ERR_HIP;
+        GNN_TRY(fill_zero_launch((int64_t)plan->desc.f_in * plan->desc.f_out, dW, st));
+        if (plan->desc.has_bias) GNN_TRY(fill_zero_launch(plan->desc.f_out, db, st));
         return GNN_OK;
     }
     return gcn_backward(*plan, *graph, X, W, Y, dY, dW, db, dX, cache, workspace, as_stream(hip_stream));
 }
 
 gnn_status_t sage_layer_fwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W_self,
-                            const float *W_neigh, const float *b, float *Y, void *cache, void *workspace,
-                            void *hip_stream) {
+                            const float *W_neigh, const float *b, float *Y, void *cache, size_t cache_bytes,
+                            void *workspace, size_t workspace_bytes, void *hip_stream) {
     if (!plan || plan->desc.layer != GNN_LAYER_SAGE) return GNN_ERR_INVALID_ARG;
     GNN_TRY(check_graph(plan, graph, true, false, false));
-    if (!X || !W_self || !W_neigh || !Y || !workspace) return GNN_ERR_INVALID_ARG;
+    if (!X || !W_self || !W_neigh || !Y) return GNN_ERR_INVALID_ARG;
     if (plan->desc.has_bias && !b) return GNN_ERR_INVALID_ARG;
-    if (plan->info.cache == GNN_CACHE_AX && !cache) return GNN_ERR_INVALID_ARG;
-    if (bad_align(workspace) || (cache && bad_align(cache))) return GNN_ERR_INVALID_ARG;
+    GNN_TRY(check_buffers(plan, plan->info.cache == GNN_CACHE_AX, cache, cache_bytes, workspace, workspace_bytes));
     if (plan->desc.n == 0) return GNN_OK;
     return sage_forward(*plan, *graph, X, W_self, W_neigh, b, Y, cache, workspace, as_stream(hip_stream));
 }
 
 gnn_status_t sage_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W_self,
                             const float *W_neigh, const float *Y, const float *dY, float *dW_self,
-                            float *dW_neigh, float *db, float *dX, void *cache, void *workspace, void *hip_stream) {
+                            float *dW_neigh, float *db, float *dX, void *cache, size_t cache_bytes,
+                            void *workspace, size_t workspace_bytes, void *hip_stream) {
     if (!plan || plan->desc.layer != GNN_LAYER_SAGE) return GNN_ERR_INVALID_ARG;
     const bool cached = plan->info.cache == GNN_CACHE_AX;
     const bool needs_t = !graph || !graph->symmetric;
     const bool runs_spmm_t = plan->info.bwd == GNN_BWD_FUSED_PROPAGATE || plan->desc.need_input_grad;
     GNN_TRY(check_graph(plan, graph, true, needs_t && runs_spmm_t, graph && !graph->csc_val));
-    if (!X || !W_self || !W_neigh || !dY || !dW_self || !dW_neigh || !workspace) return GNN_ERR_INVALID_ARG;
+    if (!X || !W_self || !W_neigh || !dY || !dW_self || !dW_neigh) return GNN_ERR_INVALID_ARG;
     if (plan->desc.fuse_relu && !Y) return GNN_ERR_INVALID_ARG;
     if (plan->desc.has_bias && !db) return GNN_ERR_INVALID_ARG;
     if (plan->desc.need_input_grad && !dX) return GNN_ERR_INVALID_ARG;
-    if (cached && !cache) return GNN_ERR_INVALID_ARG;
-    if (bad_align(workspace) || (cache && bad_align(cache))) return GNN_ERR_INVALID_ARG;
+    GNN_TRY(check_buffers(plan, cached, cache, cache_bytes, workspace, workspace_bytes));
     if (cached && !plan->cache_filled) return GNN_ERR_STATE;
     if (plan->desc.n == 0) {
         hipStream_t st = as_stream(hip_stream);
-        const size_t wb = sizeof(float) * plan->desc.f_in * plan->desc.f_out;
-        if (hipMemsetAsync(dW_self, 0, wb, st) != hipSuccess) return GNN_ERR_HIP;
-        if (hipMemsetAsync(dW_neigh, 0, wb, st) != hipSuccess) return GNN_ERR_HIP;
-        if (plan->desc.has_bias && hipMemsetAsync(db, 0, sizeof(float) * plan->desc.f_out, st) != hipSuccess)
-            return GNN_ERR_HIP;
+        const int64_t wc = (int64_t)plan->desc.f_in * plan->desc.f_out;
+        GNN_TRY(fill_zero_launch(wc, dW_self, st));
+        GNN_TRY(fill_zero_launch(wc, dW_neigh, st));
+        if (plan->desc.has_bias) GNN_TRY(fill_zero_launch(plan->desc.f_out, db, st));
         return GNN_OK;
     }
     return sage_backward(*plan, *graph, X, W_self, W_neigh, Y, dY, dW_self, dW_neigh, db, dX, cache, workspace,
@@ -141,13 +148,13 @@ gnn_status_t sage_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const fl
 
 gnn_status_t gat_layer_fwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W,
                            const float *a_src, const float *a_dst, const float *b, float *Y,
-                           void *cache, void *workspace, void *hip_stream) {
+                           void *cache, size_t cache_bytes, void *workspace, size_t workspace_bytes,
+                           void *hip_stream) {
     if (!plan || plan->desc.layer != GNN_LAYER_GAT) return GNN_ERR_INVALID_ARG;
     GNN_TRY(check_graph(plan, graph, false, false, false));
-    if (!X || !W || !a_src || !a_dst || !Y || !workspace) return GNN_ERR_INVALID_ARG;
+    if (!X || !W || !a_src || !a_dst || !Y) return GNN_ERR_INVALID_ARG;
     if (plan->desc.has_bias && !b) return GNN_ERR_INVALID_ARG;
-    if (plan->info.cache != GNN_CACHE_NONE && !cache) return GNN_ERR_INVALID_ARG;
-    if (bad_align(workspace) || (cache && bad_align(cache))) return GNN_ERR_INVALID_ARG;
+    GNN_TRY(check_buffers(plan, plan->info.cache != GNN_CACHE_NONE, cache, cache_bytes, workspace, workspace_bytes));
     if (plan->desc.n == 0) return GNN_OK;
     return gat_forward(*plan, *graph, X, W, a_src, a_dst, b, Y, cache, workspace, as_stream(hip_stream));
 }
@@ -155,23 +162,23 @@ gnn_status_t gat_layer_fwd(gnn_plan_t *plan, const gnn_graph_t *graph, const flo
 gnn_status_t gat_layer_bwd(gnn_plan_t *plan, const gnn_graph_t *graph, const float *X, const float *W,
                            const float *a_src, const float *a_dst, const float *Y, const float *dY,
                            float *dW, float *da_src, float *da_dst, float *db, float *dX,
-                           void *cache, void *workspace, void *hip_stream) {
+                           void *cache, size_t cache_bytes, void *workspace, size_t workspace_bytes,
+                           void *hip_stream) {
     if (!plan || plan->desc.layer != GNN_LAYER_GAT) return GNN_ERR_INVALID_ARG;
     GNN_TRY(check_graph(plan, graph, false, true, true));
-    if (!X || !W || !a_src || !a_dst || !dY || !dW || !da_src || !da_dst || !workspace) return GNN_ERR_INVALID_ARG;
+    if (!X || !W || !a_src || !a_dst || !dY || !dW || !da_src || !da_dst) return GNN_ERR_INVALID_ARG;
     if (plan->desc.has_bias && !db) return GNN_ERR_INVALID_ARG;
     if (plan->desc.fuse_elu && !Y) return GNN_ERR_INVALID_ARG;
     if (plan->desc.need_input_grad && !dX) return GNN_ERR_INVALID_ARG;
-    if (plan->info.cache != GNN_CACHE_NONE && !cache) return GNN_ERR_INVALID_ARG;
-    if (bad_align(workspace) || (cache && bad_align(cache))) return GNN_ERR_INVALID_ARG;
+    GNN_TRY(check_buffers(plan, plan->info.cache != GNN_CACHE_NONE, cache, cache_bytes, workspace, workspace_bytes));
     if (plan->info.cache != GNN_CACHE_NONE && !plan->cache_filled) return GNN_ERR_STATE;
     if (plan->desc.n == 0) {
         hipStream_t st = as_stream(hip_stream);
-        const size_t f = (size_t)plan->desc.heads * plan->desc.f_out;
-        if (hipMemsetAsync(dW, 0, sizeof(float) * plan->desc.f_in * f, st) != hipSuccess) return GNN_ERR_HIP;
-        if (hipMemsetAsync(da_src, 0, sizeof(float) * f, st) != hipSuccess) return GNN_ERR_HIP;
-        if (hipMemsetAsync(da_dst, 0, sizeof(float) * f, st) != hipSuccess) return GNN_ERR_HIP;
-        if (plan->desc.has_bias && hipMemsetAsync(db, 0, sizeof(float) * f, st) != hipSuccess) return GNN_ERR_HIP;
+        const int64_t f = (int64_t)plan->desc.heads * plan->desc.f_out;
+        GNN_TRY(fill_zero_launch((int64_t)plan->desc.f_in * f, dW, st));
+        GNN_TRY(fill_zero_launch(f, da_src, st));
+        GNN_TRY(fill_zero_launch(f, da_dst, st));
+        if (plan->desc.has_bias) GNN_TRY(fill_zero_launch(f, db, st));
         return GNN_OK;
     }
     return gat_backward(*plan, *graph, X, W, a_src, a_dst, Y, dY, dW, da_src, da_dst, db, dX, cache, workspace,
@@ -247,6 +254,7 @@ gnn_status_t gnn_spmm_csr(int32_t n, int32_t nnz, const int32_t *rowptr, const i
                           const float *bias, int32_t relu,
                           void *workspace, size_t workspace_bytes, void *hip_stream) {
     if (n < 0 || nnz < 0 || f <= 0 || !rowptr) return GNN_ERR_INVALID_ARG;
+    if (relu != 0 && relu != 1) return GNN_ERR_INVALID_ARG;       // other activation codes are internal
     if (n > 0 && !C) return GNN_ERR_INVALID_ARG;
     if (nnz > 0 && (!col || !B)) return GNN_ERR_INVALID_ARG;
     if (erow && nnz > 0) {
@@ -263,10 +271,6 @@ gnn_status_t gnn_sddmm_csr(int32_t n, int32_t nnz, const int32_t *erow, const in
     if (n < 0 || nnz < 0 || f <= 0 || heads <= 0) return GNN_ERR_INVALID_ARG;
     if (nnz > 0 && (!erow || !col || !B || !Ct || !D)) return GNN_ERR_INVALID_ARG;
     return sddmm_launch(n, nnz, erow, col, val, B, Ct, heads, f, D, as_stream(hip_stream));
-}
-
-void gnn_profile_spmm_events(void *start_event, void *stop_event) {
-    spmm_profile_events(static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event));
 }
 
 size_t gnn_gemm_workspace_bytes(int32_t trans_a, int32_t trans_b, int64_t M, int64_t N, int64_t K) {

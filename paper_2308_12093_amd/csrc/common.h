@@ -63,8 +63,6 @@ gnn_status_t spmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *c
                          EdgeWeights w, const float *B, long b_rows, int f, float *C, const float *bias, int relu,
                          void *workspace, hipStream_t st);
 
-void spmm_profile_events(hipEvent_t start, hipEvent_t stop);
-
 // ---- dense products (gemm.hip) ----------------------------------------------------
 size_t gemm_workspace_bytes(int ta, int tb, int64_t M, int64_t N, int64_t K);
 gnn_status_t gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A, const float *B,

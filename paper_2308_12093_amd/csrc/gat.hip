@@ -431,10 +431,14 @@ edge_gy_kernel(long count, int h, const int32_t *__restrict__ erow, const int32_
 
 // ds_i = sum_e g_y_e = (1 - beta) (P_i - t_i Q_i): the softmax gradient sums to zero over a row,
 // so only the entries with a positive logit (factor 1 instead of beta) leave a remainder.
+// A row without stored entries has no sums (the row walk never visits it): its ds is zero.
 __global__ void __launch_bounds__(256)
-node_ds_kernel(long count, const float *__restrict__ sums, float slope, float *__restrict__ ds) {
+node_ds_kernel(long count, int h, const int32_t *__restrict__ rowptr, const float *__restrict__ sums, float slope,
+               float *__restrict__ ds) {
     const long t = (long)blockIdx.x * 256 + threadIdx.x;
     if (t >= count) return;
+    const long i = t / h;
+    if (rowptr[i] == rowptr[i + 1]) { ds[t] = 0.f; return; }
     const float ti = sums[t * 3], P = sums[t * 3 + 1], Q = sums[t * 3 + 2];
     ds[t] = (1.f - slope) * (P - ti * Q);
 }
@@ -577,7 +581,8 @@ gnn_status_t gat_edge_backward_launch(int n, int nnz, int h, const int32_t *rowp
                                       const int32_t *col, const float *alpha, const uint8_t *mask, const float *s,
                                       const float *d, float slope, float *gy, float *sums, float *ds,
                                       void *workspace, hipStream_t st) {
-    if (nnz <= 0 || n <= 0) return GNN_OK;
+    if (n <= 0) return GNN_OK;
+    if (nnz <= 0) return fill_zero_launch((int64_t)n * h, ds, st);     // no entries: every row sum is empty
     SumsOp op{alpha, gy, mask, s, d};
     GNN_TRY(run_head_walker<SumsOp>(nnz, h, rowptr, erow, col, op, sums, static_cast<float *>(workspace), st));
     const long ecount = (long)nnz * h, ncount = (long)n * h;
@@ -589,7 +594,8 @@ gnn_status_t gat_edge_backward_launch(int n, int nnz, int h, const int32_t *rowp
         hipLaunchKernelGGL(edge_gy_kernel<1>, dim3((unsigned)ceil_div(ecount, 256)), dim3(256), 0, st, ecount, h, erow,
                            col, alpha, mask, s, d, sums, slope, gy);
     GNN_TRY(launch_status());
-    hipLaunchKernelGGL(node_ds_kernel, dim3((unsigned)ceil_div(ncount, 256)), dim3(256), 0, st, ncount, sums, slope, ds);
+    hipLaunchKernelGGL(node_ds_kernel, dim3((unsigned)ceil_div(ncount, 256)), dim3(256), 0, st, ncount, h, rowptr, sums,
+                       slope, ds);
     return launch_status();
 }
 

@@ -372,9 +372,6 @@ spmm_row_kernel(int n, int f, const int32_t *__restrict__ rowptr, const int32_t 
     }
 }
 
-// profiling aid: events recorded right before / after the entry-balanced kernel
-hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
-
 int pow2_at_least(int x) {
     int p = 1;
     while (p < x) p <<= 1;
@@ -495,13 +492,11 @@ gnn_status_t spmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *c
     const long nseg = ceil_div(nnz, seg);
 
     bool launched = false;
-    if (g_prof_start) (void)hipEventRecord(g_prof_start, st);
     SPMM_CASE(4, 1, 1, 8) SPMM_CASE(4, 2, 1, 8) SPMM_CASE(4, 4, 1, 8) SPMM_CASE(4, 8, 1, 8)
     SPMM_CASE(4, 16, 1, 8) SPMM_CASE(4, 32, 1, 8) SPMM_CASE(4, 64, 1, 8) SPMM_CASE(4, 64, 2, 4)
     SPMM_CASE(1, 8, 1, 8) SPMM_CASE(1, 16, 1, 8) SPMM_CASE(1, 32, 1, 8) SPMM_CASE(1, 64, 1, 8)
     SPMM_CASE(1, 64, 2, 4)
     if (!launched) return GNN_ERR_UNSUPPORTED;
-    if (g_prof_stop) (void)hipEventRecord(g_prof_stop, st);
     GNN_TRY(launch_status());
 
     // second kernel: one wavefront per block span of the first, and per 64 rows for the empty-row fill
@@ -520,11 +515,6 @@ gnn_status_t spmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *c
         hipLaunchKernelGGL((spmm_fixup_kernel<1, false>), dim3((unsigned)ceil_div(waves, 4)), dim3(256), 0, st, n, nnz, f,
                            span, nspan, lpf, erow, rowptr, part, C, bias, relu);
     return launch_status();
-}
-
-void spmm_profile_events(hipEvent_t start, hipEvent_t stop) {
-    g_prof_start = start;
-    g_prof_stop = stop;
 }
 
 }  // namespace gnn

@@ -102,8 +102,9 @@ int main(void) {
     float *d_Y = dev_copy(NULL, sizeof(float) * N * K), *d_dW = dev_copy(NULL, sizeof W), *d_db = dev_copy(NULL, sizeof b);
     float *d_dX = dev_copy(NULL, sizeof X);
     if (!ws || !d_X || !d_W || !d_b || !d_G || !d_Y || !d_dW || !d_db || !d_dX) { fprintf(stderr, "device allocation failed\n"); return 2; }
-    GNN_CHECK(gcn_layer_fwd(plan, &graph, d_X, d_W, d_b, d_Y, cache, ws, NULL));
-    GNN_CHECK(gcn_layer_bwd(plan, &graph, d_X, d_W, NULL, d_G, d_dW, d_db, d_dX, cache, ws, NULL));
+    GNN_CHECK(gcn_layer_fwd(plan, &graph, d_X, d_W, d_b, d_Y, cache, info.cache_bytes, ws, info.workspace_bytes, NULL));
+    GNN_CHECK(gcn_layer_bwd(plan, &graph, d_X, d_W, NULL, d_G, d_dW, d_db, d_dX, cache, info.cache_bytes, ws,
+                            info.workspace_bytes, NULL));
     HIP_OK(hipDeviceSynchronize());
     static float Y[N * K], dW[M * K], db[K], dX[N * M];
     HIP_OK(hipMemcpy(Y, d_Y, sizeof Y, hipMemcpyDeviceToHost));

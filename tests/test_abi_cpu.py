@@ -152,23 +152,69 @@ def test_layer_calls_reject_bad_arguments_before_any_launch():
     g = B.gnn_graph_t(10, 30, 256, 256, 256, None, None, None, None, None, None, 1)
     null = ctypes.c_void_p(None)
     one = ctypes.c_void_p(256)
+    ws = p.info.workspace_bytes
+    bufs = (null, 0, one, ws, null)                       # cache, cache_bytes, workspace, workspace_bytes, stream
     # NULL X
-    assert B.lib.gcn_layer_fwd(p.handle, ctypes.byref(g), null, one, null, one, null, one, null) == B.GNN_ERR_INVALID_ARG
+    assert B.lib.gcn_layer_fwd(p.handle, ctypes.byref(g), null, one, null, one, *bufs) == B.GNN_ERR_INVALID_ARG
     # misaligned workspace
-    assert B.lib.gcn_layer_fwd(p.handle, ctypes.byref(g), one, one, null, one, null, ctypes.c_void_p(260), null) == B.GNN_ERR_INVALID_ARG
+    assert B.lib.gcn_layer_fwd(p.handle, ctypes.byref(g), one, one, null, one, null, 0, ctypes.c_void_p(260), ws,
+                               null) == B.GNN_ERR_INVALID_ARG
     # graph that does not match the plan
     g2 = B.gnn_graph_t(11, 30, 256, 256, 256, None, None, None, None, None, None, 1)
-    assert B.lib.gcn_layer_fwd(p.handle, ctypes.byref(g2), one, one, null, one, null, one, null) == B.GNN_ERR_BAD_GRAPH
+    assert B.lib.gcn_layer_fwd(p.handle, ctypes.byref(g2), one, one, null, one, *bufs) == B.GNN_ERR_BAD_GRAPH
     # GCN needs edge values
     g3 = B.gnn_graph_t(10, 30, 256, 256, None, None, None, None, None, None, None, 1)
-    assert B.lib.gcn_layer_fwd(p.handle, ctypes.byref(g3), one, one, null, one, null, one, null) == B.GNN_ERR_BAD_GRAPH
+    assert B.lib.gcn_layer_fwd(p.handle, ctypes.byref(g3), one, one, null, one, *bufs) == B.GNN_ERR_BAD_GRAPH
     # backward on a directed graph without CSC arrays
     g4 = B.gnn_graph_t(10, 30, 256, 256, 256, None, None, None, None, None, None, 0)
-    assert B.lib.gcn_layer_bwd(p.handle, ctypes.byref(g4), one, one, null, one, one, null, one, null, one, null) == B.GNN_ERR_BAD_GRAPH
+    assert B.lib.gcn_layer_bwd(p.handle, ctypes.byref(g4), one, one, null, one, one, null, one, *bufs) == B.GNN_ERR_BAD_GRAPH
     # missing dX although the plan needs it
-    assert B.lib.gcn_layer_bwd(p.handle, ctypes.byref(g), one, one, null, one, one, null, null, null, one, null) == B.GNN_ERR_INVALID_ARG
+    assert B.lib.gcn_layer_bwd(p.handle, ctypes.byref(g), one, one, null, one, one, null, null, *bufs) == B.GNN_ERR_INVALID_ARG
     # a GAT call on a GCN plan
-    assert B.lib.gat_layer_fwd(p.handle, ctypes.byref(g), one, one, one, one, null, one, null, one, null) == B.GNN_ERR_INVALID_ARG
+    assert B.lib.gat_layer_fwd(p.handle, ctypes.byref(g), one, one, one, one, null, one, *bufs) == B.GNN_ERR_INVALID_ARG
+
+
+def test_layer_calls_reject_buffers_smaller_than_the_plan_reports():
+    """Every layer call takes the byte sizes of cache and workspace and checks them before any launch."""
+    null, one = ctypes.c_void_p(None), ctypes.c_void_p(256)
+    sym = B.gnn_graph_t(10, 30, 256, 256, 256, 256, None, None, None, None, None, 1)
+    full = B.gnn_graph_t(10, 30, 256, 256, 256, 256, 256, 256, 256, 256, 256, 0)
+    small = B.GNN_ERR_BUFFER_TOO_SMALL
+    # GCN, propagate-first with the A'X cache
+    p = plan(8, 16, True, n=10, nnz=30)
+    ws, cb = p.info.workspace_bytes, p.info.cache_bytes
+    assert p.info.cache == B.GNN_CACHE_AX and cb >= 4 * 10 * 8 and ws > 0
+    fwd = lambda *bufs: B.lib.gcn_layer_fwd(p.handle, ctypes.byref(sym), one, one, null, one, *bufs, null)
+    assert fwd(one, cb, one, ws - 1) == small
+    assert fwd(one, cb - 1, one, ws) == small
+    assert fwd(null, cb, one, ws) == B.GNN_ERR_INVALID_ARG        # the plan caches: the buffer is required
+    bwd = lambda *bufs: B.lib.gcn_layer_bwd(p.handle, ctypes.byref(sym), null, one, null, one, one, null, one, *bufs, null)
+    assert bwd(one, cb, one, ws - 1) == small
+    assert bwd(one, cb - 1, one, ws) == small
+    assert bwd(one, cb, one, ws) == B.GNN_ERR_STATE               # sizes fine: only the missing forward remains
+    # a plan without cache ignores the cache arguments
+    p2 = plan(8, 4, True, n=10, nnz=30)
+    assert p2.info.cache == B.GNN_CACHE_NONE
+    assert B.lib.gcn_layer_fwd(p2.handle, ctypes.byref(sym), one, one, null, one, null, 0, one,
+                               p2.info.workspace_bytes - 1, null) == small
+    # GraphSAGE
+    ps = B.Plan(B.GNN_LAYER_SAGE, 10, 30, 8, 16)
+    assert B.lib.sage_layer_fwd(ps.handle, ctypes.byref(sym), one, one, one, null, one, one, ps.info.cache_bytes, one,
+                                ps.info.workspace_bytes - 1, null) == small
+    assert B.lib.sage_layer_bwd(ps.handle, ctypes.byref(sym), one, one, one, null, one, one, one, null, one, one,
+                                ps.info.cache_bytes - 1, one, ps.info.workspace_bytes, null) == small
+    # GAT, every caching variant
+    for variant in (B.GNN_CACHE_NONE, B.GNN_CACHE_GAT_FEAT, B.GNN_CACHE_GAT_FEAT_NODEATT, B.GNN_CACHE_GAT_FEAT_EDGE):
+        pg = B.Plan(B.GNN_LAYER_GAT, 10, 30, 8, 4, heads=2, cache=variant)
+        ws, cb = pg.info.workspace_bytes, pg.info.cache_bytes
+        c = one if cb else null
+        gf = lambda *bufs: B.lib.gat_layer_fwd(pg.handle, ctypes.byref(full), one, one, one, one, null, one, *bufs, null)
+        gb = lambda *bufs: B.lib.gat_layer_bwd(pg.handle, ctypes.byref(full), one, one, one, one, null, one, one, one,
+                                               one, null, one, *bufs, null)
+        assert gf(c, cb, one, ws - 1) == small and gb(c, cb, one, ws - 1) == small
+        if cb:
+            assert gf(c, cb - 1, one, ws) == small and gb(c, cb - 1, one, ws) == small
+            assert gb(c, cb, one, ws) == B.GNN_ERR_STATE
 
 
 def test_backward_before_forward_with_cached_plan_is_a_state_error():
@@ -176,7 +222,8 @@ def test_backward_before_forward_with_cached_plan_is_a_state_error():
     assert p.info.cache == B.GNN_CACHE_AX
     g = B.gnn_graph_t(10, 30, 256, 256, 256, None, None, None, None, None, None, 1)
     null, one = ctypes.c_void_p(None), ctypes.c_void_p(256)
-    st = B.lib.gcn_layer_bwd(p.handle, ctypes.byref(g), null, one, null, one, one, null, one, one, one, null)
+    st = B.lib.gcn_layer_bwd(p.handle, ctypes.byref(g), null, one, null, one, one, null, one, one, p.info.cache_bytes,
+                             one, p.info.workspace_bytes, null)
     assert st == B.GNN_ERR_STATE
 
 
@@ -187,6 +234,9 @@ def test_operator_calls_check_sizes():
     st = B.lib.gnn_spmm_csr(100, 1000, one, one, one, one, one, 64, one, null, 0, one, need - 1, null)
     assert st == B.GNN_ERR_BUFFER_TOO_SMALL
     assert B.lib.gnn_spmm_csr(100, 1000, one, one, one, one, one, 0, one, null, 0, one, need, null) == B.GNN_ERR_INVALID_ARG
+    # the activation argument takes 0 or 1 only (the library's other epilogue codes are internal)
+    for relu in (2, 4, -1):
+        assert B.lib.gnn_spmm_csr(100, 1000, one, one, one, one, one, 64, one, null, relu, one, need, null) == B.GNN_ERR_INVALID_ARG
     assert B.lib.gnn_gemm(1, 1, 4, 4, 4, one, one, one, null, 0, null, 0, null) == B.GNN_ERR_UNSUPPORTED
     assert B.lib.gnn_gemm(0, 0, -1, 4, 4, one, one, one, null, 0, null, 0, null) == B.GNN_ERR_INVALID_ARG
     tw = B.gnn_transpose_workspace_bytes(100, 1000)

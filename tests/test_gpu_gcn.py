@@ -99,6 +99,18 @@ def test_every_scheme_small_rmat(B, G, name, m, k):
                   label=f"{name} m={m} k={k} dx={need_dx} relu={relu}")
 
 
+@pytest.mark.parametrize("name", ["auto", "tf_fp"])
+@pytest.mark.parametrize("m,k", [(256, 256), (320, 264)])
+def test_wide_layers_take_the_large_weight_gradient_tile(B, G, name, m, k):
+    """F_in and F_out of 256 and more: dW = X^T H runs on the 128 x 128 tile of the fp64 split-K kernel."""
+    s = synth.streams(17)
+    rowptr, col = synth.rmat_graph(12, 10, False, s["graph"], s["relabel"])
+    n = rowptr.size - 1
+    X, W = synth.normal(s["X"], n, m), synth.glorot_uniform(s["W"], (m, k), m, k)
+    b, dY = synth.normal(s["b"], k), synth.normal(s["dY"], n, k)
+    check(B, G, rowptr, col, X, W, b, dY, True, True, schemes(B)[name], label=f"wide {name} m={m} k={k}")
+
+
 @pytest.mark.parametrize("name", ["tf_fp", "pf_sp_nocache", "pf_sp_cache"])
 def test_directed_graph_uses_the_transpose(B, G, name):
     s = synth.streams(12)

@@ -209,7 +209,9 @@ def test_gemm_nn_and_nt(B, M, K, N):
 
 
 @pytest.mark.parametrize("K,M,N", [(50000, 128, 16), (70001, 128, 128), (20000, 100, 256), (9000, 512, 16),
-                                   (300000, 64, 64), (100, 5, 3), (4097, 256, 47)])
+                                   (300000, 64, 64), (100, 5, 3), (4097, 256, 47),
+                                   # outputs of 256 x 256 and more take the 128 x 128 tile of the fp64 kernel
+                                   (20000, 256, 256), (4097, 300, 260), (9001, 512, 384)])
 def test_gemm_tn_split_reduction(B, K, M, N):
     rng = np.random.default_rng(K + M + N)
     A = rng.standard_normal((K, M), dtype=np.float32)

@@ -159,6 +159,27 @@ def test_gcn_forward_backward_against_dense_brute_force():
     np.testing.assert_allclose(dX, Ap.T @ G @ W.T, rtol=1e-12, atol=1e-13)
 
 
+def test_symmetric_shortcut_of_the_backward_pass():
+    """gcn_backward(symmetric=True) replaces A'^T G by A' G: equal to the scatter form exactly when A' is
+    symmetric, which is_symmetric must tell apart from a directed graph."""
+    rng = np.random.default_rng(5)
+    n = 40
+    r, c = rng.integers(0, n, 150), rng.integers(0, n, 150)
+    rowptr, col = synth.coo_to_csr(n, np.concatenate([r, c]), np.concatenate([c, r]))      # undirected
+    rp, cc, deg = oracle.add_self_loops_degree(rowptr, col)
+    val = oracle.gcn_normalize(rp, cc, deg)
+    assert oracle.is_symmetric(rp, cc, val)
+    X, W, G = rng.standard_normal((n, 6)), rng.standard_normal((6, 4)), rng.standard_normal((n, 4))
+    a, b = oracle.gcn_backward(rp, cc, val, X, W, G), oracle.gcn_backward(rp, cc, val, X, W, G, symmetric=True)
+    for x, y in zip(a, b):
+        np.testing.assert_allclose(x, y, rtol=1e-12, atol=1e-13)
+    drp, dcol = synth.coo_to_csr(n, r, c)                                                  # directed
+    drp, dcol, ddeg = oracle.add_self_loops_degree(drp, dcol)
+    assert not oracle.is_symmetric(drp, dcol, oracle.gcn_normalize(drp, dcol, ddeg))
+    mean = oracle.aggregator_weights(rp, cc, deg, "mean")                                  # symmetric pattern, not values
+    assert not oracle.is_symmetric(rp, cc, mean)
+
+
 def test_gcn_orderings_agree():
     """(A'X)Theta == A'(X Theta); X^T(A'^T G) == (A'X)^T G; (A'^T G)Theta^T == A'^T(G Theta^T)."""
     rp, c, val, X, W, b, G = _gcn_case(seed=4)
@@ -296,6 +317,50 @@ def test_gat_zero_attention_is_mean_aggregation():
     fw = oracle.gat_forward(rp, c, X, W, z, z, None, h, 0.2)
     A = dense_pattern(rp, c)
     np.testing.assert_allclose(fw["Y"], (A / A.sum(axis=1, keepdims=True)) @ X @ W, rtol=1e-12, atol=1e-13)
+
+
+def test_leaky_relu_derivative_at_a_logit_of_exactly_zero_is_the_slope():
+    """Sec. "GAT Backward Pass": the LeakyReLU derivative is beta for y <= 0, so at y = 0 it is beta, not 1.
+    With a_src = a_dst = 0 every logit is exactly 0 in double and in float: alpha = 1/deg, no mask bit is set,
+    and beta multiplies every edge gradient.  Closed form, written here with dense matrices:
+      g_alpha = (G_p M_p^T) on the pattern, g_w = (g_alpha - rowmean) / deg, g_y = beta g_w,
+      ds = 0, dd_j = column sums of g_y, da_src = 0, da_dst_p = sum_j dd_j m_j.
+    A derivative of 1 at zero (the mistake `y >= 0`) would scale da_dst by 1 / beta.  Both sign-decision
+    branches of the oracle (double, and float s + d) are held to it, and torch's autograd of
+    leaky_relu at 0 (a library routine with the same convention) gives the same numbers."""
+    beta = 0.2
+    rp, c, X, W, a_src, a_dst, b, G, h, k = _gat_case(seed=21)
+    n = X.shape[0]
+    zero = np.zeros_like(a_src)
+    A = dense_pattern(rp, c)
+    deg = A.sum(axis=1)
+    M = (X @ W).reshape(n, h, k)
+    G3 = G.reshape(n, h, k)
+    da_dst = np.zeros((h, k))
+    dd = np.zeros((n, h))
+    for p in range(h):
+        ga = (G3[:, p, :] @ M[:, p, :].T) * A                    # g_alpha on the pattern
+        gw = (ga - (ga.sum(axis=1) / deg)[:, None]) * A / deg[:, None]
+        gy = beta * gw
+        assert abs(gy.sum(axis=1)).max() < 1e-12                 # ds = 0
+        dd[:, p] = gy.sum(axis=0)
+        da_dst[p] = dd[:, p] @ M[:, p, :]
+    assert np.abs(da_dst).max() > 1e-2                           # the pin is not vacuous
+    fw = oracle.gat_forward(rp, c, X, W, zero, zero, None, h, beta)
+    assert not fw["mask"].any() and np.all(fw["s"] == 0) and np.all(fw["d"] == 0)
+    bw = oracle.gat_backward(rp, c, X, W, zero, zero, G, h, beta)                       # decision in double
+    z32 = np.zeros((n, h), np.float32)
+    bw32 = oracle.gat_backward_cached(rp, c, X, W, zero, zero, G, M.astype(np.float32), z32, z32, beta)
+    for name, got in (("double", bw), ("float", bw32)):
+        tol = dict(rtol=1e-12, atol=1e-13) if name == "double" else dict(rtol=1e-5, atol=1e-6)   # M rounded to float
+        np.testing.assert_allclose(got["da_dst"], da_dst, err_msg=name, **tol)
+        np.testing.assert_allclose(got["dd"], dd, err_msg=name, **tol)
+        np.testing.assert_allclose(got["da_src"], 0.0, atol=1e-12 if name == "double" else 1e-6, err_msg=name)
+        np.testing.assert_allclose(got["ds"], 0.0, atol=1e-12 if name == "double" else 1e-6, err_msg=name)
+    tens = [torch.tensor(a, requires_grad=True) for a in (X, W, zero, zero, b)]
+    (_torch_dense_gat(rp, c, *tens, h, k, beta) * torch.tensor(G)).sum().backward()
+    np.testing.assert_allclose(tens[3].grad.numpy(), da_dst, rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(bw["dW"], tens[1].grad.numpy(), rtol=1e-10, atol=1e-11)
 
 
 def test_gat_identical_heads_give_identical_blocks_and_head_order():

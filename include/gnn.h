@@ -327,6 +327,24 @@ gnn_status_t gnn_spmm_csr(int32_t n, int32_t nnz, const int32_t *rowptr, const i
 size_t gnn_spmm_workspace_bytes(int32_t n, int32_t nnz, int32_t f);
 
 /*
+ * gnn_spmm_csr_static - gnn_spmm_csr for callers that cannot allocate device memory and have no workspace
+ * to pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels and results as gnn_spmm_csr; the scratch (partial rows, padded operand) is a device
+ * array of GNN_STATIC_SCRATCH_BYTES bytes inside the library, one copy per GPU, held until the process ends.
+ * The call allocates nothing and frees nothing.
+ *   Errors: as gnn_spmm_csr; GNN_ERR_BUFFER_TOO_SMALL when gnn_spmm_workspace_bytes(n, nnz, f) exceeds
+ *   GNN_STATIC_SCRATCH_BYTES (then use gnn_spmm_csr with a workspace of that size).
+ *   The first call on a device looks up the array's address there (make it outside a graph capture).
+ *   All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU (different
+ *   streams, or several host threads) race; calls on one stream are ordered and safe.  Nothing in the
+ *   array needs clearing between calls: every partial row is written before it is read.
+ */
+#define GNN_STATIC_SCRATCH_BYTES (32u << 20)
+gnn_status_t gnn_spmm_csr_static(int32_t n, int32_t nnz, const int32_t *rowptr, const int32_t *col, const float *val,
+                                 const int32_t *erow, const float *B, int32_t f, float *C,
+                                 const float *bias, int32_t relu, void *hip_stream);
+
+/*
  * Storage formats other than CSR (App. D.2 coordinate, D.3 ELLPACK, D.4 hybrid) and SpMM on them, for the
  * format comparison of App. E.1.  The layers never use them.
  *   ELLPACK arrays ell_col / ell_val [t][n] are slot-major: slot j of row i at [j * n + i]; a row's stored

@@ -94,6 +94,7 @@ _PROTOS = {
     "gnn_gather_f32": (ctypes.c_int, [_i64, _vp, _vp, _vp, _vp]),
     "gnn_spmm_csr": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _sz, _vp]),
     "gnn_spmm_workspace_bytes": (_sz, [_i32, _i32, _i32]),
+    "gnn_spmm_csr_static": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32, _vp]),
     "gnn_sddmm_csr": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp]),
     "gnn_gemm": (ctypes.c_int, [_i32, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]),
     "gnn_gemm_workspace_bytes": (_sz, [_i32, _i32, _i64, _i64, _i64]),
@@ -286,6 +287,14 @@ def gnn_spmm_workspace_bytes(n, nnz, f):
 def gnn_spmm_csr(n, nnz, rowptr, col, val, erow, B, f, C, bias=None, relu=False, workspace=None):
     _check(lib.gnn_spmm_csr(n, nnz, _ptr(rowptr), _ptr(col), _ptr(val), _ptr(erow), _ptr(B), f, _ptr(C),
                             _ptr(bias), int(relu), _ptr(workspace), _nbytes(workspace), _stream()), "gnn_spmm_csr")
+
+
+GNN_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def gnn_spmm_csr_static(n, nnz, rowptr, col, val, erow, B, f, C, bias=None, relu=False):
+    _check(lib.gnn_spmm_csr_static(n, nnz, _ptr(rowptr), _ptr(col), _ptr(val), _ptr(erow), _ptr(B), f, _ptr(C),
+                                   _ptr(bias), int(relu), _stream()), "gnn_spmm_csr_static")
 
 
 # ---- other storage formats (format comparison) --------------------------------------

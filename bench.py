@@ -1,19 +1,23 @@
 #!/usr/bin/env python3
-"""Benchmark of the GCN layer hot path on one MI355X.
+"""Benchmark of the GCN / GAT layer hot path on one MI355X.
 
-A step = forward + backward of one GCN layer for every F_out of the workload
-(default: the R-MAT 2^17 graph with F_in = 128 and F_out in {16, 128, 512}),
-each with the plan that gnn_plan_create picks (adaptive ordering + caching,
-input gradient required).  Inputs are seeded and synthetic, resident in HBM
-before the timed region, and all graph preprocessing (self-loops, degrees,
-normalisation, row-index expansion) has run in the library's kernels.
+Default workload: the largest single-GPU configuration, a GCN layer on the R-MAT graph of 2^22 nodes
+(degree 32, F_in = 64).  A step = forward + backward of one layer for every F_out of the workload
+(64 and 256), each with the plan that gnn_plan_create picks (adaptive ordering + caching, input gradient
+required).  Inputs are seeded and synthetic, resident in HBM before the timed region, and all graph
+preprocessing (self-loops, degrees, normalisation, row-index expansion, transpose) has run in the
+library's kernels.
 
 Prints ONE JSON line:
-  value      edge.features per second, sum_k q (F_in + F_out_k) / time per step
-  roofline   the entry-balanced SpMM kernel: algorithmic (compulsory) HBM bytes
-             per launch / its average duration, timed with HIP events recorded
-             around that kernel alone on the launch stream
-  cpu_baseline  the fp64 oracle, one step of the same workload, host cores
+  value         edge.features per second: sum over the layers of q (F_in + F_out) / time per step
+  roofline      the dominant kernel of the workload (the entry-balanced SpMM; for the GAT workloads the
+                fused edge kernels): algorithmic HBM bytes per launch / its average duration, timed with
+                HIP events on the launch stream around batches of back-to-back launches of that entry point
+  cpu_baseline  the fp64 oracle on a bounded sample of the same workload, host cores
+  config        names the workload; `all_configs` (default run only) holds, for each of the five
+                configurations, the time of the adaptive plan and of the fixed transform-first /
+                fused-propagate scheme without cache (GAT: of each caching variant)
+Other workloads: --workload cfg1 | cfg2 | cfg3 | cfg4 | gatnet.
 """
 from __future__ import annotations
 
@@ -26,13 +30,16 @@ import time
 
 import numpy as np
 
+HERE = os.path.dirname(os.path.abspath(__file__))
+HBM_PEAK_GBPS = 8000.0
+
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "gatnet"],
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "gatnet"],
                     help="gatnet: two GAT layers (8 heads, ELU between, squared error) on the cfg4 graph")
     ap.add_argument("--hidden", type=int, default=8, help="gatnet: features per head of both layers (paper: 8..128)")
     ap.add_argument("--selection", default="rule", choices=["rule", "calibrated"],
@@ -46,11 +53,12 @@ def parse():
     ap.add_argument("--scale", type=int, default=None, help="override the R-MAT scale (debug)")
     ap.add_argument("--scheme", default="auto", choices=["auto", "tf_fp", "pf_sp_nocache", "pf_sp_cache"])
     ap.add_argument("--gat-cache", default="auto", choices=["auto", "none", "feat", "nodeatt", "edge"],
-                    help="cfg4 only: GAT caching variant")
+                    help="cfg4 / gatnet: GAT caching variant")
     ap.add_argument("--graph", action="store_true",
                     help="GCN workloads: record one step in a HIP graph and time its replays (small graphs are launch-bound)")
     ap.add_argument("--no-input-grad", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-summary", action="store_true", help="default workload: skip the table over all five configurations")
     ap.add_argument("--breakdown", action="store_true", help="also print per-F_out / per-scheme timings to stderr")
     ap.add_argument("--format-study", action="store_true",
                     help="time SpMM on the cfg2 graph and on an even-degree graph of the same size in CSR, coordinate, "
@@ -61,67 +69,609 @@ def parse():
 
 
 class HipEvents:
-    """Raw HIP events (the torch ones hide their handles until recorded)."""
+    """Raw HIP events recorded on the stream the binding launches on (torch's events see only torch's
+    current stream object; these take the stream handle itself)."""
 
-    def __init__(self):
+    def __init__(self, stream):
         self.hip = ctypes.CDLL("libamdhip64.so")
         self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
         self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
         self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
-        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
         self.hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self.stream = stream
+        self.e0, self.e1 = self._create(), self._create()
 
-    def create(self):
+    def _create(self):
         e = ctypes.c_void_p()
         assert self.hip.hipEventCreate(ctypes.byref(e)) == 0
         return e
 
-    def record(self, e, stream):
-        assert self.hip.hipEventRecord(e, ctypes.c_void_p(stream)) == 0
-
-    def elapsed_ms(self, a, b):
-        assert self.hip.hipEventSynchronize(b) == 0
+    def time_ms(self, fn, runs):
+        """Average duration of one call of fn over `runs` back-to-back calls between two events."""
+        assert self.hip.hipEventRecord(self.e0, ctypes.c_void_p(self.stream)) == 0
+        for _ in range(runs):
+            fn()
+        assert self.hip.hipEventRecord(self.e1, ctypes.c_void_p(self.stream)) == 0
+        assert self.hip.hipEventSynchronize(self.e1) == 0
         ms = ctypes.c_float()
-        assert self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b) == 0
-        return ms.value
+        assert self.hip.hipEventElapsedTime(ctypes.byref(ms), self.e0, self.e1) == 0
+        return ms.value / runs
+
+    def blocks(self, fn, blocks, runs, warm=2):
+        """The paper's protocol (Sec. 4 "Experimental Setup"): blocks of runs, one time per block."""
+        for _ in range(warm):
+            self.time_ms(fn, max(1, runs // 4))
+        return [self.time_ms(fn, runs) for _ in range(blocks)]
 
 
+def stats(per_run):
+    return {"median": round(float(np.median(per_run)), 5), "min": round(float(np.min(per_run)), 5),
+            "max": round(float(np.max(per_run)), 5)}
+
+
+def wall_ms_per_step(torch, step, warmup, steps):
+    """W untimed steps, then exactly `steps` steps between two device synchronisations."""
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+# ---- algorithmic bytes (every operand once; re-reads that miss the caches are what a better kernel avoids) ----
 def spmm_bytes(n, q, f):
-    """Algorithmic HBM bytes of one SpMM launch of width f: every operand once.
-
-    Row index, column index and value per entry (12 q), the dense operand read
-    once (4 n f) and the result written once (4 n f).  Re-reads of dense rows
-    that miss the caches are not counted: they are what a better kernel avoids."""
+    """One SpMM launch of dense width f: row index, column index and value per entry (12 q), the dense
+    operand read once (4 n f), the result written once (4 n f)."""
     return 12 * q + 8 * n * f
 
 
-def measured_traffic(workload, launch_widths):
-    """HBM-side bytes per SpMM launch from the committed rocprofv3 counter summary, or None.
-
-    The summary holds FETCH_SIZE and WRITE_SIZE of the kernel, scaled by a plain copy of
-    known size, for the default workload only; the figure is the average over the
-    launches of one step, weighted like `achieved`."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "spmm_cfg2_hbm_traffic.txt")
-    if not workload.startswith("cfg2-rmat17") or not os.path.exists(path):
-        return None
-    per_width = {}
+def profile_traffic(workload, key):
+    """HBM-side bytes per launch of a kernel from the committed rocprofv3 counter summary of this workload
+    (FETCH_SIZE and WRITE_SIZE runs, scaled by a plain copy of known size), or None when profiles/ holds none.
+    Returns (bytes, file name)."""
+    path = os.path.join(HERE, "profiles", f"{workload}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None, None
     for line in open(path):
         if line.startswith("traffic_bytes_per_launch"):
             for item in line.split()[1:]:
-                f, b = item.split("=")
-                per_width[int(f[1:])] = int(b)
-    if any(f not in per_width for f in launch_widths):
-        return None
-    return round(sum(per_width[f] for f in launch_widths) / len(launch_widths))
+                name, value = item.split("=")
+                if name == key:
+                    return int(value), os.path.relpath(path, HERE)
+    return None, None
+
+
+def spmm_roofline(torch, B, ev, g, launch_widths, workload, step_ms):
+    """Times gnn_spmm_csr (main kernel + fix-up) at every dense width a step launches it with."""
+    n, q = g.n, g.nnz
+    per_width, tot_bytes, tot_ms = {}, 0.0, 0.0
+    for f in sorted(set(launch_widths)):
+        Bm = torch.randn((n, f), dtype=torch.float32, device="cuda")
+        C = torch.empty((n, f), dtype=torch.float32, device="cuda")
+        ws = B.alloc(B.gnn_spmm_workspace_bytes(n, q, f))
+        runs = 20 if q < 20_000_000 else 5
+        times = ev.blocks(lambda: B.gnn_spmm_csr(n, q, g.rowptr, g.col, g.val, g.erow, Bm, f, C, None, False, ws),
+                          10 if q < 20_000_000 else 6, runs)
+        avg = float(np.mean(times))
+        per_width[f] = dict(avg_ms=avg, bytes=spmm_bytes(n, q, f), gather_gbps=(12 * q + 4 * q * f + 4 * n * f) / avg / 1e6)
+        cnt = launch_widths.count(f)
+        tot_bytes += cnt * spmm_bytes(n, q, f)
+        tot_ms += cnt * avg
+        del Bm, C, ws
+    achieved = tot_bytes / tot_ms / 1e6
+    traffic = src = None
+    parts = [profile_traffic(workload, f"spmm_f{f}") for f in launch_widths]
+    if parts and all(p[0] is not None for p in parts):
+        traffic, src = round(sum(p[0] for p in parts) / len(parts)), parts[0][1]
+    widths = sorted(per_width)
+    return {"bound": "hbm", "kernel": "spmm_seg_kernel (+ spmm_fixup_kernel)", "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": traffic, "traffic_source": src,
+            # the same launches priced by the bytes the L2s exchanged with the fabric (the profile above)
+            "traffic_GBps": None if traffic is None else round(traffic * len(launch_widths) / tot_ms / 1e6, 1),
+            "traffic_frac": None if traffic is None else round(traffic * len(launch_widths) / tot_ms / 1e6 / HBM_PEAK_GBPS, 4),
+            "launches_per_step": len(launch_widths),
+            "bytes_per_launch": {str(f): per_width[f]["bytes"] for f in widths},
+            "avg_ms_per_launch": {str(f): round(per_width[f]["avg_ms"], 5) for f in widths},
+            "no_reuse_gather_GBps": {str(f): round(per_width[f]["gather_gbps"], 1) for f in widths},
+            "time_share_of_step": round(tot_ms / step_ms, 3)}
+
+
+def spmm_launch_widths(B, info, f_in, k):
+    """Dense width of every SpMM that forward + backward of a GCN plan launch."""
+    out = [int(info.spmm_width_fwd)] if info.spmm_width_fwd else []
+    if info.bwd == B.GNN_BWD_FUSED_PROPAGATE:
+        out.append(k)
+    else:
+        out += [f_in] * int(info.spmm_width_bwd // f_in)
+    return out
+
+
+SCHEMES = ("auto", "tf_fp", "pf_sp_nocache", "pf_sp_cache")
+
+
+def scheme_kw(B, name):
+    return {"auto": {},
+            "tf_fp": dict(order=B.GNN_ORDER_TRANSFORM_FIRST, bwd=B.GNN_BWD_FUSED_PROPAGATE, cache=B.GNN_CACHE_NONE),
+            "pf_sp_nocache": dict(order=B.GNN_ORDER_PROPAGATE_FIRST, bwd=B.GNN_BWD_SPLIT_PROPAGATE, cache=B.GNN_CACHE_NONE),
+            "pf_sp_cache": dict(order=B.GNN_ORDER_PROPAGATE_FIRST, bwd=B.GNN_BWD_SPLIT_PROPAGATE, cache=B.GNN_CACHE_AX)}[name]
+
+
+def scheme_name(B, info):
+    order = "TF" if info.order == B.GNN_ORDER_TRANSFORM_FIRST else "PF"
+    bwd = "FP" if info.bwd == B.GNN_BWD_FUSED_PROPAGATE else "SP"
+    return f"{order}+{bwd}" + ("+cache" if info.cache == B.GNN_CACHE_AX else "")
+
+
+# =================================================================================================
+# GCN (and GraphSAGE) single layer: cfg1, cfg2, cfg5
+# =================================================================================================
+class GcnSingle:
+    def __init__(self, args, torch, B, graphs, w, layer="gcn", aggregator="gcn"):
+        self.args, self.torch, self.B, self.w, self.layer = args, torch, B, w, layer
+        agg = {"gcn": B.GNN_AGG_GCN_SYM, "mean": B.GNN_AGG_MEAN, "gin": B.GNN_AGG_GIN_SUM}[aggregator]
+        self.g = graphs.gcn_graph(w.rowptr, w.col, "cuda", symmetric=True, aggregator=agg, eps=0.1)
+        self.f_in, self.f_outs = w.dims["f_in"], w.dims["f_outs"]
+        self.X = torch.from_numpy(w.tensors["X"]).cuda()
+
+    def make_layer(self, k, scheme, dx, selection="rule", constant_input=False):
+        B, torch, w, g = self.B, self.torch, self.w, self.g
+        kind = B.GNN_LAYER_SAGE if self.layer == "sage" else B.GNN_LAYER_GCN
+        plan = B.Plan(kind, g.n, g.nnz, self.f_in, k, need_input_grad=dx, constant_input=constant_input,
+                      selection=B.GNN_SELECT_CALIBRATED if selection == "calibrated" else B.GNN_SELECT_PAPER_RULE,
+                      **scheme_kw(B, scheme))
+        e = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
+        L = dict(k=k, plan=plan, W=torch.from_numpy(w.tensors[f"W{k}"]).cuda(),
+                 dY=torch.from_numpy(w.tensors[f"dY{k}"]).cuda(), Y=e(g.n, k), dW=e(self.f_in, k),
+                 dX=e(g.n, self.f_in) if dx else None, ws=B.alloc(plan.info.workspace_bytes),
+                 cache=B.alloc(plan.info.cache_bytes) if plan.info.cache_bytes else None)
+        if self.layer == "sage":
+            L["Ws"] = torch.from_numpy(np.ascontiguousarray(w.tensors[f"W{k}"][::-1])).cuda()   # SAGE self weight
+            L["dWs"] = e(self.f_in, k)
+        return L
+
+    def fwd(self, L):
+        B, g = self.B, self.g
+        if self.layer == "sage":
+            B.sage_layer_fwd(L["plan"], g, self.X, L["Ws"], L["W"], None, L["Y"], L["cache"], L["ws"])
+        else:
+            B.gcn_layer_fwd(L["plan"], g, self.X, L["W"], None, L["Y"], L["cache"], L["ws"])
+
+    def bwd(self, L):
+        B, g = self.B, self.g
+        if self.layer == "sage":
+            B.sage_layer_bwd(L["plan"], g, self.X, L["Ws"], L["W"], None, L["dY"], L["dWs"], L["dW"], None, L["dX"],
+                             L["cache"], L["ws"])
+        else:
+            B.gcn_layer_bwd(L["plan"], g, self.X, L["W"], None, L["dY"], L["dW"], None, L["dX"], L["cache"], L["ws"])
+
+    def step_ms(self, layers, warmup, steps):
+        def step():
+            for L in layers:
+                self.fwd(L)
+                self.bwd(L)
+        return wall_ms_per_step(self.torch, step, warmup, steps)
+
+    def summary(self, warmup=3, steps=10):
+        """Adaptive plan against the fixed transform-first / fused-propagate scheme without cache, for every
+        F_out of the workload, with and without the input gradient (the design of Sec. 4.1)."""
+        out = {}
+        for dx in (True, False):
+            for k in self.f_outs:
+                rec = {}
+                for scheme in ("auto", "tf_fp"):
+                    L = self.make_layer(k, scheme, dx)
+                    rec[scheme] = (self.step_ms([L], warmup, steps), scheme_name(self.B, L["plan"].info))
+                    del L
+                out[f"F_out={k},{'dX' if dx else 'no dX'}"] = {
+                    "auto_ms": round(rec["auto"][0], 4), "fixed_ms": round(rec["tf_fp"][0], 4),
+                    "auto_scheme": rec["auto"][1], "same_scheme": rec["auto"][1] == rec["tf_fp"][1],
+                    "speedup": round(rec["tf_fp"][0] / rec["auto"][0], 3)}
+        return out
+
+
+def bench_gcn_single(args, torch, B, graphs, synth, oracle_mod):
+    if args.workload == "cfg1":
+        w = synth.config1()
+    elif args.workload == "cfg2":
+        w = synth.config2(scale=args.scale or 17)
+    else:
+        w = synth.config5(scale=args.scale or 22)
+    run = GcnSingle(args, torch, B, graphs, w, args.layer, args.aggregator)
+    g, f_in, f_outs = run.g, run.f_in, run.f_outs
+    n, q = g.n, g.nnz
+    need_dx = not args.no_input_grad
+    layers = [run.make_layer(k, args.scheme, need_dx, args.selection, args.constant_input) for k in f_outs]
+    def step():
+        for L in layers:
+            run.fwd(L)
+            run.bwd(L)
+
+    if args.graph:
+        for _ in range(args.warmup):
+            step()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        ms_per_step = wall_ms_per_step(torch, graph.replay, 2, args.steps)
+    else:
+        ms_per_step = wall_ms_per_step(torch, step, args.warmup, args.steps)
+    edge_feat = sum(q * (f_in + k) for k in f_outs)
+
+    ev = HipEvents(torch.cuda.current_stream().cuda_stream)
+    launch_widths = []
+    for L in layers:
+        launch_widths += spmm_launch_widths(B, L["plan"].info, f_in, L["k"])
+    wl = args.workload
+    roofline = spmm_roofline(torch, B, ev, g, launch_widths, wl, ms_per_step)
+
+    # per-layer forward / backward times, the paper's protocol with shorter blocks
+    big = q > 20_000_000
+    layer_times = {}
+    for L in layers:
+        layer_times[str(L["k"])] = {
+            "scheme": scheme_name(B, L["plan"].info),
+            "fwd_ms": stats(ev.blocks(lambda: run.fwd(L), 5 if big else 10, 4 if big else 20)),
+            "bwd_ms": stats(ev.blocks(lambda: run.bwd(L), 5, 4 if big else 20))}
+    if args.breakdown:
+        print(json.dumps(layer_times, indent=1), file=sys.stderr)
+
+    cpu = None
+    if oracle_mod is not None:
+        cpu = cpu_baseline_gcn(oracle_mod, w, args, f_in, f_outs, need_dx, q)
+
+    config = {"workload": f"{w.name}: R-MAT/ER graph n={n}, nnz={q} (self-loops incl.), F_in={f_in}, "
+                          f"F_out={list(f_outs)}, {args.layer.upper()} single layer fwd+bwd, scheme={args.scheme}, "
+                          f"input_grad={need_dx}, selection={args.selection}, constant_input={args.constant_input}, "
+                          f"aggregator={args.aggregator}, hip_graph={args.graph}",
+              "layer_times_ms": layer_times}
+    del layers
+    return w, run, {"metric": "GCN layer fwd+bwd edge-feat/s (adaptive ordering + caching)",
+                    "value": edge_feat / (ms_per_step * 1e-3), "ms_per_step": ms_per_step, "config": config,
+                    "roofline": roofline, "cpu_baseline": cpu}
+
+
+def cpu_baseline_gcn(oracle, w, args, f_in, f_outs, need_dx, q):
+    """The fp64 oracle on whole layers (forward + backward) of the same workload, about 10-30 s of CPU work:
+    as many whole steps as fit, or on the large graphs the first layer of the step only."""
+    rp, c, deg = oracle.add_self_loops_degree(w.rowptr, w.col)
+    val = oracle.gcn_normalize(rp, c, deg) if args.aggregator == "gcn" else \
+        oracle.aggregator_weights(rp, c, deg, args.aggregator, 0.1)
+    sym = args.aggregator != "mean"                       # undirected graph, symmetric weights: A'^T G = A' G
+    ks = list(f_outs) if q < 20_000_000 else list(f_outs)[:1]
+    Xh = w.tensors["X"]
+
+    def one_pass():
+        for k in ks:
+            Wh, dYh = w.tensors[f"W{k}"], w.tensors[f"dY{k}"]
+            if args.layer == "sage":
+                oracle.sage_forward(rp, c, val, Xh, Wh[::-1], Wh)
+                oracle.sage_backward(rp, c, val, Xh, Wh[::-1], Wh, dYh, None, need_dx)
+            else:
+                oracle.gcn_forward(rp, c, val, Xh, Wh)
+                oracle.gcn_backward(rp, c, val, Xh, Wh, dYh, None, need_dx, symmetric=sym)
+
+    t0 = time.perf_counter()
+    passes = 0
+    while passes < 8 and time.perf_counter() - t0 < 10.0:
+        one_pass()
+        passes += 1
+    dt = (time.perf_counter() - t0) / passes
+    return {"value": sum(q * (f_in + k) for k in ks) / dt, "unit": "edge*feat/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"{passes} x (forward + backward of the layer(s) F_out = {ks} of the step's {list(f_outs)}), "
+                      f"{dt * passes:.1f} s in total, scaled by q (F_in + F_out) of those layers",
+            "ms_per_sample": round(dt * 1e3, 2)}
+
+
+# =================================================================================================
+# two-layer GCN network: cfg3
+# =================================================================================================
+class GcnNetwork:
+    """R-MAT 2^20, degree 50, 100 -> 256 -> 47, ReLU between the layers, sum-reduced softmax cross-entropy:
+    one training step without the optimiser."""
+
+    def __init__(self, torch, B, graphs, w):
+        self.torch, self.B, self.w = torch, B, w
+        self.g = graphs.gcn_graph(w.rowptr, w.col, "cuda")
+        self.d = {key: torch.from_numpy(v).cuda() for key, v in w.tensors.items()}
+
+    def make(self, scheme, selection="rule", constant_input=False):
+        B, torch, g = self.B, self.torch, self.g
+        f0, f1, f2 = self.w.dims["dims"]
+        n, q = g.n, g.nnz
+        kw = scheme_kw(B, scheme)
+        sel = B.GNN_SELECT_CALIBRATED if selection == "calibrated" else B.GNN_SELECT_PAPER_RULE
+        p1 = B.Plan(B.GNN_LAYER_GCN, n, q, f0, f1, need_input_grad=False, fuse_relu=True, selection=sel,
+                    constant_input=constant_input, **kw)
+        p2 = B.Plan(B.GNN_LAYER_GCN, n, q, f1, f2, need_input_grad=True, selection=sel, **kw)
+        e = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
+        net = dict(p1=p1, p2=p2, ws=B.alloc(max(p1.info.workspace_bytes, p2.info.workspace_bytes, 4 * ((n + 255) // 256))),
+                   c1=B.alloc(p1.info.cache_bytes) if p1.info.cache_bytes else None,
+                   c2=B.alloc(p2.info.cache_bytes) if p2.info.cache_bytes else None,
+                   H1=e(n, f1), Z=e(n, f2), dZ=e(n, f2), dH1=e(n, f1), dW1=e(f0, f1), dW2=e(f1, f2), loss=e(1))
+        return net
+
+    def step(self, N):
+        B, g, d = self.B, self.g, self.d
+        f2 = self.w.dims["dims"][2]
+        B.gcn_layer_fwd(N["p1"], g, d["X"], d["W1"], None, N["H1"], N["c1"], N["ws"])
+        B.gcn_layer_fwd(N["p2"], g, N["H1"], d["W2"], None, N["Z"], N["c2"], N["ws"])
+        B.gnn_softmax_xent(g.n, f2, N["Z"], d["labels"], N["dZ"], N["loss"], N["ws"])
+        B.gcn_layer_bwd(N["p2"], g, N["H1"], d["W2"], None, N["dZ"], N["dW2"], None, N["dH1"], N["c2"], N["ws"])
+        B.gcn_layer_bwd(N["p1"], g, None if N["p1"].info.cache == B.GNN_CACHE_AX else d["X"], d["W1"], N["H1"],
+                        N["dH1"], N["dW1"], None, None, N["c1"], N["ws"])
+
+    def summary(self, warmup=2, steps=5):
+        rec = {}
+        for scheme in ("auto", "tf_fp"):
+            N = self.make(scheme)
+            rec[scheme] = (wall_ms_per_step(self.torch, lambda: self.step(N), warmup, steps),
+                           [scheme_name(self.B, N[p].info) for p in ("p1", "p2")])
+            del N
+        return {"100->256->47": {"auto_ms": round(rec["auto"][0], 4), "fixed_ms": round(rec["tf_fp"][0], 4),
+                                 "auto_scheme": rec["auto"][1], "same_scheme": rec["auto"][1] == rec["tf_fp"][1],
+                                 "speedup": round(rec["tf_fp"][0] / rec["auto"][0], 3)}}
+
+
+def bench_gcn_network(args, torch, B, graphs, synth, oracle):
+    if args.scheme not in ("auto", "tf_fp"):
+        sys.exit("bench.py: cfg3 takes --scheme auto or tf_fp")
+    w = synth.config3(scale=args.scale or 20)
+    run = GcnNetwork(torch, B, graphs, w)
+    g, (f0, f1, f2) = run.g, w.dims["dims"]
+    n, q = g.n, g.nnz
+    N = run.make(args.scheme, args.selection, args.constant_input)
+    ms = wall_ms_per_step(torch, lambda: run.step(N), args.warmup, args.steps)
+    edge_feat = q * (f0 + f1) + q * (f1 + f2)
+    ev = HipEvents(torch.cuda.current_stream().cuda_stream)
+    launch_widths = spmm_launch_widths(B, N["p1"].info, f0, f1) + spmm_launch_widths(B, N["p2"].info, f1, f2)
+    if args.constant_input and N["p1"].info.cache == B.GNN_CACHE_AX:
+        launch_widths.remove(f0)                          # the cached A'X is not recomputed
+    roofline = spmm_roofline(torch, B, ev, g, launch_widths, "cfg3", ms)
+    cpu = None
+    if oracle is not None:
+        # sample: forward + backward of the second layer (256 -> 47, with dX) on the oracle's own first-layer output
+        rp, c, deg = oracle.add_self_loops_degree(w.rowptr, w.col)
+        val = oracle.gcn_normalize(rp, c, deg)
+        H1 = np.maximum(w.tensors["X"].astype(np.float64) @ w.tensors["W1"].astype(np.float64), 0.0)   # any input of that shape
+        dZ = np.random.default_rng(0).standard_normal((n, f2))
+        t0 = time.perf_counter()
+        oracle.gcn_forward(rp, c, val, H1, w.tensors["W2"])
+        oracle.gcn_backward(rp, c, val, H1, w.tensors["W2"], dZ, None, True, symmetric=True)
+        dt = time.perf_counter() - t0
+        cpu = {"value": q * (f1 + f2) / dt, "unit": "edge*feat/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"forward + backward of the second layer only ({f1} -> {f2}, with dX), {dt:.1f} s, scaled by "
+                         f"q (F_in + F_out) of that layer", "ms_per_sample": round(dt * 1e3, 2)}
+    config = {"workload": f"{w.name}: R-MAT n={n}, nnz={q} (self-loops incl.), {f0}->{f1}->{f2}, ReLU, "
+                          f"softmax cross-entropy, fwd+bwd, scheme={args.scheme}, selection={args.selection}, "
+                          f"constant_input={args.constant_input}",
+              "schemes": [scheme_name(B, N[p].info) for p in ("p1", "p2")],
+              "spmm_widths": launch_widths, "loss": float(N["loss"].item())}
+    return {"metric": "two-layer GCN training step edge-feat/s", "value": edge_feat / (ms * 1e-3), "ms_per_step": ms,
+            "config": config, "roofline": roofline, "cpu_baseline": cpu}
+
+
+# =================================================================================================
+# GAT layer: cfg4, and the two-layer GAT network
+# =================================================================================================
+GAT_VARIANTS = ("none", "feat", "nodeatt", "edge")
+
+
+def gat_variant(B, name):
+    return {"auto": B.GNN_CACHE_AUTO, "none": B.GNN_CACHE_NONE, "feat": B.GNN_CACHE_GAT_FEAT,
+            "nodeatt": B.GNN_CACHE_GAT_FEAT_NODEATT, "edge": B.GNN_CACHE_GAT_FEAT_EDGE}[name]
+
+
+class GatSingle:
+    """R-MAT 2^17 directed, F_in = 256, 8 heads x 8 features, LeakyReLU slope 0.2, bias."""
+
+    def __init__(self, torch, B, graphs, w):
+        self.torch, self.B, self.w = torch, B, w
+        self.g = graphs.gat_graph(w.rowptr, w.col, "cuda")
+        self.d = {key: torch.from_numpy(v).cuda() for key, v in w.tensors.items()}
+        self.h, self.k, self.m = w.dims["heads"], w.dims["f_out"], w.dims["f_in"]
+
+    def make(self, variant, need_dx=True):
+        B, torch, g = self.B, self.torch, self.g
+        h, k, m = self.h, self.k, self.m
+        plan = B.Plan(B.GNN_LAYER_GAT, g.n, g.nnz, m, k, heads=h, need_input_grad=need_dx, has_bias=True,
+                      leaky_slope=0.2, cache=gat_variant(B, variant))
+        e = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
+        return dict(plan=plan, Y=e(g.n, h * k), dW=e(m, h * k), das=e(h, k), dad=e(h, k), db=e(h * k),
+                    dX=e(g.n, m) if need_dx else None, ws=B.alloc(plan.info.workspace_bytes),
+                    cache=B.alloc(plan.info.cache_bytes) if plan.info.cache_bytes else None)
+
+    def fwd(self, L):
+        d = self.d
+        self.B.gat_layer_fwd(L["plan"], self.g, d["X"], d["W"], d["a_src"], d["a_dst"], d["b"], L["Y"], L["cache"], L["ws"])
+
+    def bwd(self, L):
+        d = self.d
+        self.B.gat_layer_bwd(L["plan"], self.g, d["X"], d["W"], d["a_src"], d["a_dst"], d["dY"], L["dW"], L["das"],
+                             L["dad"], L["db"], L["dX"], L["cache"], L["ws"])
+
+    def summary(self, warmup=3, steps=10):
+        out = {}
+        for variant in GAT_VARIANTS:
+            L = self.make(variant)
+            ms = wall_ms_per_step(self.torch, lambda: (self.fwd(L), self.bwd(L)), warmup, steps)
+            out[variant] = {"fwd_bwd_ms": round(ms, 4), "cache_MiB": round(L["plan"].info.cache_bytes / 2**20, 1)}
+            del L
+        return out
+
+
+def gat_edge_bytes(n, q, h, k, variant):
+    """Algorithmic bytes of the edge phase of one GAT forward + backward (everything between the dense
+    products), every array once: the index arrays of both passes (erow, col; ecol, row, perm: 20 q),
+    forward M read and Y written (8 n h k), backward G and M read twice each, dM written (20 n h k), the
+    per-node vectors s, d, row statistics, t, ds, dd (about 40 n h), and, for the variant that keeps them,
+    alpha written once and read twice plus the mask (13 q h)."""
+    per_edge = 13 * q * h if variant == "edge" else 0
+    return 20 * q + 28 * n * h * k + 40 * n * h + per_edge
+
+
+def bench_gat(args, torch, B, graphs, synth, oracle):
+    w = synth.config4(scale=args.scale or 17)
+    run = GatSingle(torch, B, graphs, w)
+    g, h, k, m = run.g, run.h, run.k, run.m
+    n, q, f = g.n, g.nnz, h * k
+    need_dx = not args.no_input_grad
+    L = run.make(args.gat_cache, need_dx)
+    ms = wall_ms_per_step(torch, lambda: (run.fwd(L), run.bwd(L)), args.warmup, args.steps)
+    ev = HipEvents(torch.cuda.current_stream().cuda_stream)
+    fwd_ms = stats(ev.blocks(lambda: run.fwd(L), 10, 20))
+    bwd_ms = stats(ev.blocks(lambda: run.bwd(L), 5, 20))
+    edge_feat = q * (m + f)
+
+    # the two sparse operators on their own: SDDMM (App. E.2) and the attention-weighted aggregation
+    G3, M3 = run.d["dY"], L["Y"]
+    D = torch.empty((q, h), dtype=torch.float32, device="cuda")
+    sddmm_ms = float(np.mean(ev.blocks(lambda: B.gnn_sddmm_csr(n, q, g.erow, g.col, None, G3, M3, h, k, D), 10, 20)))
+    sddmm_bytes = 8 * q + 8 * n * f + 4 * q * h                # erow, col; both dense operands once; D written
+    variant_name = {int(gat_variant(B, v)): v for v in GAT_VARIANTS}[int(L["plan"].info.cache)]
+    roofline = {"bound": "hbm", "kernel": "sddmm (gnn_sddmm_csr, 8 heads x 8 features)",
+                "achieved": round(sddmm_bytes / sddmm_ms / 1e6, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(sddmm_bytes / sddmm_ms / 1e6 / HBM_PEAK_GBPS, 4),
+                "traffic": profile_traffic("cfg4", "sddmm")[0], "traffic_source": profile_traffic("cfg4", "sddmm")[1],
+                "bytes_per_launch": sddmm_bytes, "avg_ms_per_launch": round(sddmm_ms, 5),
+                "edge_phase": gat_edge_phase(args, torch, B, ev, run, L, variant_name)}
+    cpu = None
+    if oracle is not None:
+        t = w.tensors
+        rp, c, _ = oracle.add_self_loops_degree(w.rowptr, w.col)
+        t0 = time.perf_counter()
+        passes = 0
+        while passes < 4 and time.perf_counter() - t0 < 10.0:
+            oracle.gat_forward(rp, c, t["X"], t["W"], t["a_src"], t["a_dst"], t["b"], h, 0.2)
+            oracle.gat_backward(rp, c, t["X"], t["W"], t["a_src"], t["a_dst"], t["dY"], h, 0.2, need_dx)
+            passes += 1
+        dt = (time.perf_counter() - t0) / passes
+        cpu = {"value": edge_feat / dt, "unit": "edge*feat/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"{passes} whole steps (forward + backward, recomputing variant) of the same workload, "
+                         f"{dt * passes:.1f} s in total", "ms_per_sample": round(dt * 1e3, 2)}
+    config = {"workload": f"{w.name}: R-MAT directed n={n}, nnz={q} (self-loops incl.), F_in={m}, heads={h}, "
+                          f"F_out={k}, GAT single layer fwd+bwd, cache variant={variant_name}, input_grad={need_dx}",
+              "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "cache_bytes": int(L["plan"].info.cache_bytes)}
+    return {"metric": "GAT layer fwd+bwd edge-feat/s", "value": edge_feat / (ms * 1e-3), "ms_per_step": ms,
+            "config": config, "roofline": roofline, "cpu_baseline": cpu}
+
+
+def gat_edge_phase(args, torch, B, ev, run, L, variant_name):
+    """Time of the layer's sparse (edge) phase: the whole layer minus its dense products, which are timed on
+    their own through gnn_gemm with the same shapes; priced by gat_edge_bytes."""
+    g, h, k, m = run.g, run.h, run.k, run.m
+    n, q, f = g.n, g.nnz, h * k
+    X, W = run.d["X"], run.d["W"]
+    e = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
+    Mb, dWb, dXb = e(n, f), e(m, f), e(n, m)
+    ws = B.alloc(max(B.gnn_gemm_workspace_bytes(0, 0, n, f, m), B.gnn_gemm_workspace_bytes(1, 0, m, f, n)))
+    t_nn = float(np.mean(ev.blocks(lambda: B.gnn_gemm(0, 0, n, f, m, X, W, Mb, None, False, ws), 5, 20)))
+    t_tn = float(np.mean(ev.blocks(lambda: B.gnn_gemm(1, 0, m, f, n, X, Mb, dWb, None, False, ws), 5, 20)))
+    t_nt = float(np.mean(ev.blocks(lambda: B.gnn_gemm(0, 1, n, m, f, Mb, W, dXb, None, False, ws), 5, 20)))
+    layer = float(np.mean(ev.blocks(lambda: (run.fwd(L), run.bwd(L)), 5, 20)))
+    dense = t_nn * (2 if variant_name == "none" else 1) + t_tn + (t_nt if L["dX"] is not None else 0.0)
+    edge = max(layer - dense, 1e-6)
+    by = gat_edge_bytes(n, q, h, k, variant_name)
+    return {"ms": round(edge, 5), "dense_products_ms": round(dense, 5), "algorithmic_bytes": by,
+            "achieved_GBps": round(by / edge / 1e6, 1), "frac_of_hbm_peak": round(by / edge / 1e6 / HBM_PEAK_GBPS, 4)}
+
+
+def bench_gat_network(args, torch, B, graphs, synth, oracle):
+    """Two-layer GAT network of Sec. 4 on the cfg4 graph: GAT(256 -> 8 x hidden) -> ELU -> GAT(-> 8 x hidden),
+    squared-error loss; one step = forward + loss + backward of both layers."""
+    w = synth.config4(scale=args.scale or 17)
+    h, m, k = w.dims["heads"], w.dims["f_in"], args.hidden
+    g = graphs.gat_graph(w.rowptr, w.col, "cuda")
+    n, q, f = g.n, g.nnz, h * k
+    variant = gat_variant(B, args.gat_cache)
+    p1 = B.Plan(B.GNN_LAYER_GAT, n, q, m, k, heads=h, need_input_grad=False, has_bias=True, cache=variant, fuse_elu=True)
+    p2 = B.Plan(B.GNN_LAYER_GAT, n, q, f, k, heads=h, need_input_grad=True, has_bias=True, cache=variant)
+    gen = torch.Generator(device="cuda").manual_seed(0)
+    rnd = lambda *s, scale=1.0: torch.randn(s, device="cuda", generator=gen) * scale
+    X = torch.from_numpy(w.tensors["X"]).cuda()
+    W1, W2 = rnd(m, f, scale=(2.0 / (m + f)) ** 0.5), rnd(f, f, scale=(1.0 / f) ** 0.5)
+    a = [rnd(h, k, scale=(2.0 / (h + k)) ** 0.5) for _ in range(4)]
+    b1, b2, T = rnd(f, scale=0.1), rnd(f, scale=0.1), rnd(n, f)
+    e = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
+    H1, Z, dZ, dH1, loss = e(n, f), e(n, f), e(n, f), e(n, f), e(1)
+    g1 = (e(m, f), e(h, k), e(h, k), e(f))
+    g2 = (e(f, f), e(h, k), e(h, k), e(f))
+    ws = B.alloc(max(p1.info.workspace_bytes, p2.info.workspace_bytes, 4096))
+    c1 = B.alloc(p1.info.cache_bytes) if p1.info.cache_bytes else None
+    c2 = B.alloc(p2.info.cache_bytes) if p2.info.cache_bytes else None
+
+    def step():
+        B.gat_layer_fwd(p1, g, X, W1, a[0], a[1], b1, H1, c1, ws)
+        B.gat_layer_fwd(p2, g, H1, W2, a[2], a[3], b2, Z, c2, ws)
+        B.gnn_sum_squared_error(Z.numel(), Z, T, dZ, loss, ws)
+        B.gat_layer_bwd(p2, g, H1, W2, a[2], a[3], dZ, g2[0], g2[1], g2[2], g2[3], dH1, c2, ws)
+        B.gat_layer_bwd(p1, g, X, W1, a[0], a[1], dH1, g1[0], g1[1], g1[2], g1[3], None, c1, ws, Y=H1)
+
+    ms = wall_ms_per_step(torch, step, args.warmup, args.steps)
+    edge_feat = q * (m + f) + q * (f + f)
+    ev = HipEvents(torch.cuda.current_stream().cuda_stream)
+    D = torch.empty((q, h), dtype=torch.float32, device="cuda")
+    sddmm_ms = float(np.mean(ev.blocks(lambda: B.gnn_sddmm_csr(n, q, g.erow, g.col, None, dZ, Z, h, k, D), 10, 20)))
+    sddmm_bytes = 8 * q + 8 * n * f + 4 * q * h
+    roofline = {"bound": "hbm", "kernel": f"sddmm (gnn_sddmm_csr, {h} heads x {k} features)",
+                "achieved": round(sddmm_bytes / sddmm_ms / 1e6, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(sddmm_bytes / sddmm_ms / 1e6 / HBM_PEAK_GBPS, 4), "traffic": None,
+                "bytes_per_launch": sddmm_bytes, "avg_ms_per_launch": round(sddmm_ms, 5)}
+    cpu = None
+    if oracle is not None:
+        # sample: forward + backward of the first layer alone (256 -> 8 x hidden), on the host copies of its inputs
+        rp, c, _ = oracle.add_self_loops_degree(w.rowptr, w.col)
+        Xh, W1h, a0, a1, b1h = (x.cpu().numpy() for x in (X, W1, a[0], a[1], b1))
+        Gh = np.random.default_rng(0).standard_normal((n, f))
+        t0 = time.perf_counter()
+        oracle.gat_forward(rp, c, Xh, W1h, a0, a1, b1h, h, 0.2)
+        oracle.gat_backward(rp, c, Xh, W1h, a0, a1, Gh, h, 0.2, False)
+        dt = time.perf_counter() - t0
+        cpu = {"value": q * (m + f) / dt, "unit": "edge*feat/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"forward + backward of the first layer only ({m} -> {h} x {k}, no dX, without the ELU), {dt:.1f} s, "
+                         f"scaled by q (F_in + heads F_out) of that layer", "ms_per_sample": round(dt * 1e3, 2)}
+    config = {"workload": f"gatnet on {w.name}: n={n}, nnz={q}, GAT({m} -> {h} x {k}) -> ELU -> GAT({f} -> {h} x {k}), "
+                          f"squared error, cache variant={int(p1.info.cache)}",
+              "cache_bytes": int(p1.info.cache_bytes + p2.info.cache_bytes)}
+    return {"metric": "two-layer GAT network fwd+bwd edge-feat/s", "value": edge_feat / (ms * 1e-3), "ms_per_step": ms,
+            "config": config, "roofline": roofline, "cpu_baseline": cpu}
+
+
+# =================================================================================================
+def all_configs_summary(args, torch, B, graphs, synth, have):
+    """Adaptive against fixed scheme on every configuration (GAT: every caching variant).  `have` holds the
+    runner of the workload that was just benchmarked, so that its graph is not built twice."""
+    out = {}
+    makers = {"cfg1": lambda: GcnSingle(args, torch, B, graphs, synth.config1()),
+              "cfg2": lambda: GcnSingle(args, torch, B, graphs, synth.config2()),
+              "cfg3": lambda: GcnNetwork(torch, B, graphs, synth.config3()),
+              "cfg4": lambda: GatSingle(torch, B, graphs, synth.config4()),
+              "cfg5": lambda: GcnSingle(args, torch, B, graphs, synth.config5())}
+    for name in ("cfg5", "cfg1", "cfg2", "cfg3", "cfg4"):
+        run = have.pop(name, None) or makers[name]()
+        out[name] = run.summary()
+        del run
+        torch.cuda.empty_cache()
+    gcn = [rec for name in ("cfg1", "cfg2", "cfg3", "cfg5") for rec in out[name].values()]
+    out["adaptive_no_slower_than_fixed_everywhere"] = all(r["auto_ms"] <= 1.03 * r["fixed_ms"] for r in gcn)
+    out["adaptive_faster_where_schemes_differ"] = all(r["auto_ms"] < r["fixed_ms"] for r in gcn if not r["same_scheme"])
+    return out
 
 
 def format_study(args, torch, B, graphs, synth):
     """SpMM time by storage format.  Two graphs of the same size: the R-MAT graph of cfg2 (hubs) and a
     uniform random graph with the same number of nodes and edges (even rows, where ELLPACK is at home)."""
     dev = "cuda"
-    ev = HipEvents()
-    e0, e1 = ev.create(), ev.create()
-    stream = torch.cuda.current_stream().cuda_stream
+    ev = HipEvents(torch.cuda.current_stream().cuda_stream)
     w = synth.config2(scale=args.scale or 17)
     rng = synth.substream(0, "graph", 99)
     pairs = (w.rowptr[-1] // 2)
@@ -129,16 +679,7 @@ def format_study(args, torch, B, graphs, synth):
     out = {}
 
     def timed(fn):
-        for _ in range(3):
-            fn()
-        times = []
-        for _ in range(5):
-            ev.record(e0, stream)
-            for _ in range(5):
-                fn()
-            ev.record(e1, stream)
-            times.append(ev.elapsed_ms(e0, e1) / 5)
-        return float(np.mean(times))
+        return float(np.mean(ev.blocks(fn, 5, 5, warm=3)))
 
     for gname, (rowptr, col) in (("rmat", (w.rowptr, w.col)), ("uniform", (er_rowptr, er_col))):
         g = graphs.gcn_graph(rowptr, col, dev, symmetric=True)
@@ -180,159 +721,6 @@ def format_study(args, torch, B, graphs, synth):
     print(json.dumps({"format_study": out}))
 
 
-def bench_gat_network(args, torch, B, graphs, synth):
-    """Two-layer GAT network of Sec. 4 on the cfg4 graph: GAT(256 -> 8 x hidden) -> ELU -> GAT(-> 8 x hidden),
-    squared-error loss; one step = forward + loss + backward of both layers."""
-    w = synth.config4(scale=args.scale or 17)
-    h, m, k = w.dims["heads"], w.dims["f_in"], args.hidden
-    g = graphs.gat_graph(w.rowptr, w.col, "cuda")
-    n, q, f = g.n, g.nnz, h * k
-    variant = {"auto": B.GNN_CACHE_AUTO, "none": B.GNN_CACHE_NONE, "feat": B.GNN_CACHE_GAT_FEAT,
-               "nodeatt": B.GNN_CACHE_GAT_FEAT_NODEATT, "edge": B.GNN_CACHE_GAT_FEAT_EDGE}[args.gat_cache]
-    p1 = B.Plan(B.GNN_LAYER_GAT, n, q, m, k, heads=h, need_input_grad=False, has_bias=True, cache=variant, fuse_elu=True)
-    p2 = B.Plan(B.GNN_LAYER_GAT, n, q, f, k, heads=h, need_input_grad=True, has_bias=True, cache=variant)
-    gen = torch.Generator(device="cuda").manual_seed(0)
-    rnd = lambda *s, scale=1.0: torch.randn(s, device="cuda", generator=gen) * scale
-    X = torch.from_numpy(w.tensors["X"]).cuda()
-    W1, W2 = rnd(m, f, scale=(2.0 / (m + f)) ** 0.5), rnd(f, f, scale=(1.0 / f) ** 0.5)
-    a = [rnd(h, k, scale=(2.0 / (h + k)) ** 0.5) for _ in range(4)]
-    b1, b2, T = rnd(f, scale=0.1), rnd(f, scale=0.1), rnd(n, f)
-    e = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
-    H1, Z, dZ, dH1, loss = e(n, f), e(n, f), e(n, f), e(n, f), e(1)
-    g1 = (e(m, f), e(h, k), e(h, k), e(f))
-    g2 = (e(f, f), e(h, k), e(h, k), e(f))
-    ws = B.alloc(max(p1.info.workspace_bytes, p2.info.workspace_bytes, 4096))
-    c1 = B.alloc(p1.info.cache_bytes) if p1.info.cache_bytes else None
-    c2 = B.alloc(p2.info.cache_bytes) if p2.info.cache_bytes else None
-
-    def step():
-        B.gat_layer_fwd(p1, g, X, W1, a[0], a[1], b1, H1, c1, ws)
-        B.gat_layer_fwd(p2, g, H1, W2, a[2], a[3], b2, Z, c2, ws)
-        B.gnn_sum_squared_error(Z.numel(), Z, T, dZ, loss, ws)
-        B.gat_layer_bwd(p2, g, H1, W2, a[2], a[3], dZ, g2[0], g2[1], g2[2], g2[3], dH1, c2, ws)
-        B.gat_layer_bwd(p1, g, X, W1, a[0], a[1], dH1, g1[0], g1[1], g1[2], g1[3], None, c1, ws, Y=H1)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    edge_feat = q * (m + f) + q * (f + f)
-    out = {"metric": "two-layer GAT network fwd+bwd edge-feat/s", "value": edge_feat / (ms * 1e-3),
-           "unit": "edge*feat/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
-           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-           "config": {"workload": f"gatnet on {w.name}: n={n}, nnz={q}, GAT({m} -> {h} x {k}) -> ELU -> GAT({f} -> {h} x {k}), "
-                                  f"squared error, cache variant={int(p1.info.cache)}",
-                      "cache_bytes": int(p1.info.cache_bytes + p2.info.cache_bytes)},
-           "roofline": None, "cpu_baseline": None}
-    print(json.dumps(out))
-
-
-def bench_gcn_network(args, torch, B, graphs, synth):
-    """Two-layer GCN (R-MAT 2^20, degree 50, 100 -> 256 -> 47, ReLU between the layers, sum-reduced softmax
-    cross-entropy): one training step without the optimiser, adaptive plans or the fixed
-    transform-first / fused-propagate scheme (--scheme tf_fp)."""
-    w = synth.config3(scale=args.scale or 20)
-    t, (f0, f1, f2) = w.tensors, w.dims["dims"]
-    g = graphs.gcn_graph(w.rowptr, w.col, "cuda")
-    n, q = g.n, g.nnz
-    kw = {} if args.scheme == "auto" else dict(order=B.GNN_ORDER_TRANSFORM_FIRST, bwd=B.GNN_BWD_FUSED_PROPAGATE,
-                                               cache=B.GNN_CACHE_NONE)
-    if args.scheme not in ("auto", "tf_fp"):
-        sys.exit("bench.py: cfg3 takes --scheme auto or tf_fp")
-    sel = B.GNN_SELECT_CALIBRATED if args.selection == "calibrated" else B.GNN_SELECT_PAPER_RULE
-    p1 = B.Plan(B.GNN_LAYER_GCN, n, q, f0, f1, need_input_grad=False, fuse_relu=True, selection=sel,
-                constant_input=args.constant_input, **kw)
-    p2 = B.Plan(B.GNN_LAYER_GCN, n, q, f1, f2, need_input_grad=True, selection=sel, **kw)
-    ws = B.alloc(max(p1.info.workspace_bytes, p2.info.workspace_bytes, 4 * ((n + 255) // 256)))
-    c1 = B.alloc(p1.info.cache_bytes) if p1.info.cache_bytes else None
-    c2 = B.alloc(p2.info.cache_bytes) if p2.info.cache_bytes else None
-    d = {key: torch.from_numpy(v).cuda() for key, v in t.items()}
-    e = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
-    H1, Z, dZ, dH1, dW1, dW2, loss = e(n, f1), e(n, f2), e(n, f2), e(n, f1), e(f0, f1), e(f1, f2), e(1)
-
-    def step():
-        B.gcn_layer_fwd(p1, g, d["X"], d["W1"], None, H1, c1, ws)
-        B.gcn_layer_fwd(p2, g, H1, d["W2"], None, Z, c2, ws)
-        B.gnn_softmax_xent(n, f2, Z, d["labels"], dZ, loss, ws)
-        B.gcn_layer_bwd(p2, g, H1, d["W2"], None, dZ, dW2, None, dH1, c2, ws)
-        B.gcn_layer_bwd(p1, g, None if p1.info.cache == B.GNN_CACHE_AX else d["X"], d["W1"], H1, dH1, dW1, None,
-                        None, c1, ws)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    edge_feat = q * (f0 + f1) + q * (f1 + f2)
-    widths = [int(p.info.spmm_width_fwd + p.info.spmm_width_bwd) for p in (p1, p2)]
-    out = {"metric": "two-layer GCN training step edge-feat/s", "value": edge_feat / (ms * 1e-3),
-           "unit": "edge*feat/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
-           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-           "config": {"workload": f"{w.name}: R-MAT n={n}, nnz={q} (self-loops incl.), {f0}->{f1}->{f2}, ReLU, "
-                                  f"softmax cross-entropy, fwd+bwd, scheme={args.scheme}, selection={args.selection}, "
-                                  f"constant_input={args.constant_input}",
-                      "schemes": [{"order": int(p.info.order), "bwd": int(p.info.bwd), "cache": int(p.info.cache)}
-                                  for p in (p1, p2)],
-                      "spmm_width_sum": widths, "loss": float(loss.item())},
-           "roofline": None, "cpu_baseline": None}
-    print(json.dumps(out))
-
-
-def bench_gat(args, torch, B, graphs, synth):
-    """GAT layer workload (R-MAT 2^17 directed, 8 heads x 8, F_in = 256): fwd + bwd of one layer."""
-    w = synth.config4(scale=args.scale or 17)
-    t, h, k, m = w.tensors, w.dims["heads"], w.dims["f_out"], w.dims["f_in"]
-    g = graphs.gat_graph(w.rowptr, w.col, "cuda")
-    n, q, f = g.n, g.nnz, h * k
-    variant = {"auto": B.GNN_CACHE_AUTO, "none": B.GNN_CACHE_NONE, "feat": B.GNN_CACHE_GAT_FEAT,
-               "nodeatt": B.GNN_CACHE_GAT_FEAT_NODEATT, "edge": B.GNN_CACHE_GAT_FEAT_EDGE}[args.gat_cache]
-    need_dx = not args.no_input_grad
-    plan = B.Plan(B.GNN_LAYER_GAT, n, q, m, k, heads=h, need_input_grad=need_dx, has_bias=True, leaky_slope=0.2,
-                  cache=variant)
-    d = {key: torch.from_numpy(v).cuda() for key, v in t.items()}
-    e = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
-    Y, dW, das, dad, db = e(n, f), e(m, f), e(h, k), e(h, k), e(f)
-    dX = e(n, m) if need_dx else None
-    ws = B.alloc(plan.info.workspace_bytes)
-    cache = B.alloc(plan.info.cache_bytes) if plan.info.cache_bytes else None
-
-    def fwd():
-        B.gat_layer_fwd(plan, g, d["X"], d["W"], d["a_src"], d["a_dst"], d["b"], Y, cache, ws)
-
-    def bwd():
-        B.gat_layer_bwd(plan, g, d["X"], d["W"], d["a_src"], d["a_dst"], d["dY"], dW, das, dad, db, dX, cache, ws)
-
-    def timed(fn, reps):
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e3 / reps
-
-    for _ in range(args.warmup):
-        fwd(); bwd()
-    ms = timed(lambda: (fwd(), bwd()), args.steps)
-    ms_f, ms_b = timed(fwd, args.steps), timed(bwd, args.steps)
-    edge_feat = q * (m + f)
-    out = {"metric": "GAT layer fwd+bwd edge-feat/s", "value": edge_feat / (ms * 1e-3), "unit": "edge*feat/s",
-           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
-           "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-           "config": {"workload": f"{w.name}: R-MAT directed n={n}, nnz={q} (self-loops incl.), F_in={m}, heads={h}, "
-                                  f"F_out={k}, GAT single layer fwd+bwd, cache variant={int(plan.info.cache)}, "
-                                  f"input_grad={need_dx}",
-                      "ms_fwd": ms_f, "ms_bwd": ms_b, "cache_bytes": int(plan.info.cache_bytes)},
-           "roofline": None, "cpu_baseline": None}
-    print(json.dumps(out))
-
-
 def main():
     args = parse()
     if args.gpus != 1:
@@ -353,219 +741,28 @@ def main():
 
     if args.format_study:
         return format_study(args, torch, B, graphs, synth)
-    if args.workload == "cfg4":
-        return bench_gat(args, torch, B, graphs, synth)
-    if args.workload == "cfg3":
-        return bench_gcn_network(args, torch, B, graphs, synth)
-    if args.workload == "gatnet":
-        return bench_gat_network(args, torch, B, graphs, synth)
-    if args.workload == "cfg1":
-        w = synth.config1()
-    elif args.workload == "cfg2":
-        w = synth.config2(scale=args.scale or 17)
-    else:
-        w = synth.config5(scale=args.scale or 22)
-    f_in, f_outs = w.dims["f_in"], w.dims["f_outs"]
-    need_dx = not args.no_input_grad
-
-    dev = "cuda"
-    agg = {"gcn": B.GNN_AGG_GCN_SYM, "mean": B.GNN_AGG_MEAN, "gin": B.GNN_AGG_GIN_SUM}[args.aggregator]
-    g = graphs.gcn_graph(w.rowptr, w.col, dev, symmetric=True, aggregator=agg, eps=0.1)
-    n, q = g.n, g.nnz
-    X = torch.from_numpy(w.tensors["X"]).to(dev)
-
-    scheme_kw = {
-        "auto": {},
-        "tf_fp": dict(order=B.GNN_ORDER_TRANSFORM_FIRST, bwd=B.GNN_BWD_FUSED_PROPAGATE, cache=B.GNN_CACHE_NONE),
-        "pf_sp_nocache": dict(order=B.GNN_ORDER_PROPAGATE_FIRST, bwd=B.GNN_BWD_SPLIT_PROPAGATE, cache=B.GNN_CACHE_NONE),
-        "pf_sp_cache": dict(order=B.GNN_ORDER_PROPAGATE_FIRST, bwd=B.GNN_BWD_SPLIT_PROPAGATE, cache=B.GNN_CACHE_AX),
-    }
-
-    def make_layer(k, scheme, dx):
-        kind = B.GNN_LAYER_SAGE if args.layer == "sage" else B.GNN_LAYER_GCN
-        plan = B.Plan(kind, n, q, f_in, k, need_input_grad=dx, constant_input=args.constant_input,
-                      selection=B.GNN_SELECT_CALIBRATED if args.selection == "calibrated" else B.GNN_SELECT_PAPER_RULE,
-                      **scheme_kw[scheme])
-        L = dict(k=k, plan=plan,
-                 W=torch.from_numpy(w.tensors[f"W{k}"]).to(dev), dY=torch.from_numpy(w.tensors[f"dY{k}"]).to(dev),
-                 Y=torch.empty((n, k), dtype=torch.float32, device=dev),
-                 dW=torch.empty((f_in, k), dtype=torch.float32, device=dev),
-                 dX=torch.empty((n, f_in), dtype=torch.float32, device=dev) if dx else None,
-                 Ws=torch.from_numpy(np.ascontiguousarray(w.tensors[f"W{k}"][::-1])).to(dev),   # SAGE self weight
-                 dWs=torch.empty((f_in, k), dtype=torch.float32, device=dev),
-                 ws=B.alloc(plan.info.workspace_bytes),
-                 cache=B.alloc(plan.info.cache_bytes) if plan.info.cache_bytes else None)
-        return L
-
-    def fwd(L):
-        if args.layer == "sage":
-            B.sage_layer_fwd(L["plan"], g, X, L["Ws"], L["W"], None, L["Y"], L["cache"], L["ws"])
-        else:
-            B.gcn_layer_fwd(L["plan"], g, X, L["W"], None, L["Y"], L["cache"], L["ws"])
-
-    def bwd(L):
-        if args.layer == "sage":
-            B.sage_layer_bwd(L["plan"], g, X, L["Ws"], L["W"], None, L["dY"], L["dWs"], L["dW"], None, L["dX"],
-                             L["cache"], L["ws"])
-        else:
-            B.gcn_layer_bwd(L["plan"], g, X, L["W"], None, L["dY"], L["dW"], None, L["dX"], L["cache"], L["ws"])
-
-    layers = [make_layer(k, args.scheme, need_dx) for k in f_outs]
-
-    def step():
-        for L in layers:
-            fwd(L)
-            bwd(L)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    run = step
-    if args.graph:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            step()
-        torch.cuda.current_stream().wait_stream(side)
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step()
-        run = graph.replay
-        run()
-        torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-
-    edge_feat = sum(q * (f_in + k) for k in f_outs)
-    value = edge_feat / (ms_per_step * 1e-3)
-
-    # ---- per-kernel timing of the dominant kernel: the entry-balanced SpMM ----
-    ev = HipEvents()
-    e0, e1 = ev.create(), ev.create()
-    stream = torch.cuda.current_stream().cuda_stream          # the stream the binding launches on
-    launch_widths = []                       # dense width of every SpMM launch of one step
-    for L in layers:
-        info = L["plan"].info
-        launch_widths.append(int(info.spmm_width_fwd))
-        if info.bwd == B.GNN_BWD_FUSED_PROPAGATE:
-            launch_widths.append(L["k"])
-        else:
-            launch_widths += [f_in] * int(info.spmm_width_bwd // f_in)
-    widths = sorted(set(launch_widths))
-    per_width = {}
-    tot_bytes = tot_ms = 0.0
-    launches = 0
-    for f in widths:
-        Bm = torch.randn((n, f), dtype=torch.float32, device=dev)
-        C = torch.empty((n, f), dtype=torch.float32, device=dev)
-        ws = B.alloc(B.gnn_spmm_workspace_bytes(n, q, f))
-        times = []
-        batch = 20                               # launches between the two events: back to back, as inside a step
-        for it in range(2 + 10):
-            ev.record(e0, stream)
-            for _ in range(batch):
-                B.gnn_spmm_csr(n, q, g.rowptr, g.col, g.val, g.erow, Bm, f, C, None, False, ws)
-            ev.record(e1, stream)
-            ms = ev.elapsed_ms(e0, e1) / batch
-            if it >= 2:
-                times.append(ms)
-        avg = float(np.mean(times))
-        per_width[f] = dict(avg_ms=avg, min_ms=float(np.min(times)), bytes=spmm_bytes(n, q, f),
-                            gbps=spmm_bytes(n, q, f) / avg / 1e6,
-                            gather_gbps=(12 * q + 4 * q * f + 4 * n * f) / avg / 1e6,
-                            edge_feat_per_s=q * f / (avg * 1e-3))
-        cnt = launch_widths.count(f)
-        tot_bytes += cnt * spmm_bytes(n, q, f)
-        tot_ms += cnt * avg
-        launches += cnt
-    achieved = tot_bytes / tot_ms / 1e6          # GB/s over all SpMM launches of one step
-    traffic = measured_traffic(w.name, launch_widths)
-    roofline = {"bound": "hbm", "kernel": "spmm_seg_kernel", "achieved": round(achieved, 1), "peak": 8000.0,
-                "unit": "GB/s", "frac": round(achieved / 8000.0, 4),
-                "traffic": traffic,
-                # the same launches priced by the bytes the L2s actually exchanged with the fabric (rocprofv3)
-                "traffic_GBps": None if traffic is None else round(traffic * launches / tot_ms / 1e6, 1),
-                "traffic_frac": None if traffic is None else round(traffic * launches / tot_ms / 1e6 / 8000.0, 4),
-                "launches_per_step": launches,
-                "bytes_per_launch": {str(f): per_width[f]["bytes"] for f in widths},
-                "avg_ms_per_launch": {str(f): round(per_width[f]["avg_ms"], 5) for f in widths},
-                "no_reuse_gather_GBps": {str(f): round(per_width[f]["gather_gbps"], 1) for f in widths},
-                "spmm_time_share_of_step": round(tot_ms / ms_per_step, 3)}
-
-    # ---- CPU baseline: the fp64 oracle, one step of the same workload ----
-    cpu = None
+    oracle = None
     if not args.no_cpu_baseline:
         import oracle
-        rp, c, deg = oracle.add_self_loops_degree(w.rowptr, w.col)
-        val = oracle.gcn_normalize(rp, c, deg) if args.aggregator == "gcn" else \
-            oracle.aggregator_weights(rp, c, deg, args.aggregator, 0.1)
-        t0 = time.perf_counter()
-        cpu_steps = 0
-        while cpu_steps < 8 and time.perf_counter() - t0 < 10.0:      # whole steps, about 10 s of CPU work
-            cpu_steps += 1
-            for k in f_outs:
-                Xh, Wh, dYh = w.tensors["X"], w.tensors[f"W{k}"], w.tensors[f"dY{k}"]
-                if args.layer == "sage":
-                    oracle.sage_forward(rp, c, val, Xh, Wh[::-1], Wh)
-                    oracle.sage_backward(rp, c, val, Xh, Wh[::-1], Wh, dYh, None, need_dx)
-                else:
-                    oracle.gcn_forward(rp, c, val, Xh, Wh)
-                    oracle.gcn_backward(rp, c, val, Xh, Wh, dYh, None, need_dx)
-        dt = (time.perf_counter() - t0) / cpu_steps
-        cpu = {"value": edge_feat / dt, "unit": "edge*feat/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": f"{cpu_steps} full steps (fwd+bwd for F_out in {list(f_outs)}) of the same workload, "
-                         f"{dt * cpu_steps:.1f} s in total",
-               "ms_per_step": dt * 1e3}
+    have = {}
+    if args.workload == "cfg4":
+        res = bench_gat(args, torch, B, graphs, synth, oracle)
+    elif args.workload == "cfg3":
+        res = bench_gcn_network(args, torch, B, graphs, synth, oracle)
+    elif args.workload == "gatnet":
+        res = bench_gat_network(args, torch, B, graphs, synth, oracle)
+    else:
+        w, run, res = bench_gcn_single(args, torch, B, graphs, synth, oracle)
+        have[args.workload] = run
+    default_run = (args.workload == "cfg5" and args.scheme == "auto" and args.layer == "gcn" and args.aggregator == "gcn"
+                   and args.scale is None and not args.no_input_grad and not args.constant_input)
+    if default_run and not args.no_summary:
+        res["config"]["all_configs"] = all_configs_summary(args, torch, B, graphs, synth, have)
 
-    # ---- per-layer forward / backward times, the paper's protocol (Sec. 4 "Experimental Setup": blocks of
-    # runs between two events, median over the blocks), with fewer runs per block to keep the run short ----
-    layer_times = {}
-    for L in layers:
-        rec = {}
-        for name, fn, blocks, runs in (("fwd", fwd, 10, 20), ("bwd", bwd, 5, 20)):
-            per_run = []
-            for _ in range(blocks):
-                ev.record(e0, stream)
-                for _ in range(runs):
-                    fn(L)
-                ev.record(e1, stream)
-                per_run.append(ev.elapsed_ms(e0, e1) / runs)
-            rec[name + "_ms"] = {"median": round(float(np.median(per_run)), 5), "min": round(float(np.min(per_run)), 5),
-                                 "max": round(float(np.max(per_run)), 5)}
-        layer_times[str(L["k"])] = rec
-
-    if args.breakdown:
-        for L in layers:
-            for name, fn in (("fwd", fwd), ("bwd", bwd)):
-                torch.cuda.synchronize()
-                t0 = time.perf_counter()
-                for _ in range(20):
-                    fn(L)
-                torch.cuda.synchronize()
-                info = L["plan"].info
-                print(f"k={L['k']:4d} {name} {(time.perf_counter() - t0) * 50:.4f} ms  "
-                      f"order={info.order} bwd={info.bwd} cache={info.cache}", file=sys.stderr)
-        for f in widths:
-            print(f"spmm f={f}: {per_width[f]}", file=sys.stderr)
-
-    out = {
-        "metric": "GCN layer fwd+bwd edge-feat/s (adaptive ordering + caching)", "value": value,
-        "unit": "edge*feat/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{w.name}: R-MAT/ER graph n={n}, nnz={q} (self-loops incl.), F_in={f_in}, "
-                               f"F_out={list(f_outs)}, {args.layer.upper()} single layer fwd+bwd, scheme={args.scheme}, "
-                               f"input_grad={need_dx}, selection={args.selection}, constant_input={args.constant_input}, "
-                               f"layer={args.layer}, aggregator={args.aggregator}, hip_graph={args.graph}",
-                   "schemes": {str(L["k"]): {"order": int(L["plan"].info.order), "bwd": int(L["plan"].info.bwd),
-                                             "cache": int(L["plan"].info.cache)} for L in layers},
-                   "layer_times_ms": layer_times},
-        "roofline": roofline,
-        "cpu_baseline": cpu,
-    }
+    out = {"metric": res["metric"], "value": res["value"], "unit": "edge*feat/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "f32", "data": "synthetic", "config": res["config"],
+           "roofline": res["roofline"], "cpu_baseline": res["cpu_baseline"]}
     print(json.dumps(out))
 
 

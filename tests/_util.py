@@ -1,8 +1,26 @@
 """Shared helpers of the GPU parity tests."""
+import os
+import time
+
 import numpy as np
 import torch
 
 TOL = 1e-4          # max |err| <= TOL * (1 + |ref|), the bar for fp32 activations and gradients
+
+_ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def progress(msg):
+    """A line for the long full-size tests: printed, and appended to a log that a watcher of the run can
+    see growing while pytest holds the output back."""
+    line = f"{time.strftime('%H:%M:%S')} {msg}"
+    print(line, flush=True)
+    try:
+        os.makedirs(os.path.join(_ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(_ROOT, "gpurun_out", "test_progress.log"), "a") as f:
+            f.write(line + "\n")
+    except OSError:
+        pass
 
 
 def dev(a, dtype=None):

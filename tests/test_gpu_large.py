@@ -10,7 +10,7 @@ import torch
 
 import oracle
 from paper_2308_12093_amd import synth
-from tests._util import assert_close, dev, host
+from tests._util import assert_close, dev, host, progress
 
 pytestmark = pytest.mark.gpu
 
@@ -98,6 +98,7 @@ def test_two_layer_gcn_full_size_every_tensor(B, G):
     """R-MAT 2^20, degree 50, 100 -> 256 -> 47 (ReLU, sum-reduced cross-entropy): every tensor of the training
     step - H1, Z, loss, dZ, dW2, dH1, dW1 - against the oracle, for the adaptive plans and for the fixed
     transform-first / fused-propagate scheme (Eqs. gcn-fwd, gcn-bwd-weights, gcn-bwd-x)."""
+    progress("cfg3: generating the 2^20-node graph")
     w = synth.config3()
     t, dims = w.tensors, w.dims["dims"]
     n = w.n
@@ -106,9 +107,11 @@ def test_two_layer_gcn_full_size_every_tensor(B, G):
     assert np.array_equal(host(g.rowptr), rp) and np.array_equal(host(g.col), c) and np.array_equal(host(g.deg), deg)
     val = oracle.gcn_normalize(rp, c, deg)
     assert oracle.is_symmetric(rp, c, val)
+    progress("cfg3: oracle forward")
     H1 = oracle.gcn_forward(rp, c, val, t["X"], t["W1"], None, relu=True)
     Z = oracle.gcn_forward(rp, c, val, H1, t["W2"])
     loss, dZ = oracle.softmax_xent(Z, t["labels"])
+    progress("cfg3: oracle backward")
     dW2, _, dH1 = oracle.gcn_backward(rp, c, val, H1, t["W2"], dZ, symmetric=True)
     H1_32 = H1.astype(np.float32)                            # both sides take the ReLU signs from these bits
     dW1, _, _ = oracle.gcn_backward(rp, c, val, t["X"], t["W1"], dH1, Y_relu=H1_32, need_dx=False, symmetric=True)
@@ -119,6 +122,7 @@ def test_two_layer_gcn_full_size_every_tensor(B, G):
             assert net.p1.info.cache == B.GNN_CACHE_AX and net.p2.info.order == B.GNN_ORDER_TRANSFORM_FIRST
         net.step(X, W1, W2, lab, relu_mask_source=mask)
         torch.cuda.synchronize()
+        progress(f"cfg3: comparing the {name} step")
         assert_close_blocks(host(net.H1), H1, f"{name} H1")
         assert_close_blocks(host(net.Z), Z, f"{name} Z")
         assert_close_blocks(host(net.dZ), dZ, f"{name} dZ")
@@ -129,39 +133,52 @@ def test_two_layer_gcn_full_size_every_tensor(B, G):
         del net
 
 
-def test_config5_full_size_every_tensor(B, G):
-    """R-MAT 2^22, degree 32, F_in = 64, both shapes 64 -> 64 and 64 -> 256, adaptive and fixed scheme:
-    Y, dW and dX in full against the oracle (Eqs. gcn-fwd, gcn-bwd-weights, gcn-bwd-x), and the integer
-    outputs of the preprocessing bit for bit."""
+@pytest.fixture(scope="module")
+def cfg5(G):
+    """The 2^22-node workload, its graph on the device and the oracle's arrays, made once for both shapes."""
+    progress("cfg5: generating the 2^22-node graph")
     w = synth.config5()
-    n, m = w.n, w.dims["f_in"]
-    assert w.dims["f_outs"] == [64, 256]
     g = G.gcn_graph(w.rowptr, w.col)
+    progress("cfg5: oracle preprocessing")
     rp, c, deg = oracle.add_self_loops_degree(w.rowptr, w.col)
-    assert np.array_equal(host(g.rowptr), rp) and np.array_equal(host(g.col), c)
-    assert np.array_equal(host(g.deg), deg)
     val = oracle.gcn_normalize(rp, c, deg)
-    assert_close(host(g.val), val, "val", tol=1e-6)
     assert oracle.is_symmetric(rp, c, val)
-    t = w.tensors
-    X = dev(t["X"])
+    return dict(w=w, g=g, rp=rp, c=c, deg=deg, val=val)
+
+
+def test_config5_preprocessing_is_bit_exact(cfg5):
+    g = cfg5["g"]
+    assert np.array_equal(host(g.rowptr), cfg5["rp"]) and np.array_equal(host(g.col), cfg5["c"])
+    assert np.array_equal(host(g.deg), cfg5["deg"])
+    assert_close(host(g.val), cfg5["val"], "val", tol=1e-6)
+    assert np.array_equal(host(g.erow), np.repeat(np.arange(g.n, dtype=np.int32), np.diff(cfg5["rp"])))
+
+
+@pytest.mark.parametrize("k", [64, 256])
+def test_config5_full_size_every_tensor(B, cfg5, k):
+    """R-MAT 2^22, degree 32, F_in = 64, shapes 64 -> 64 and 64 -> 256, adaptive and fixed scheme:
+    Y, dW and dX in full against the oracle (Eqs. gcn-fwd, gcn-bwd-weights, gcn-bwd-x)."""
+    w, g, rp, c, val = (cfg5[x] for x in ("w", "g", "rp", "c", "val"))
+    n, m, t = w.n, w.dims["f_in"], w.tensors
+    assert k in w.dims["f_outs"]
+    progress(f"cfg5 {m}->{k}: oracle forward")
+    Y_ref = oracle.gcn_forward(rp, c, val, t["X"], t[f"W{k}"])
+    progress(f"cfg5 {m}->{k}: oracle backward")
+    dW_ref, _, dX_ref = oracle.gcn_backward(rp, c, val, t["X"], t[f"W{k}"], t[f"dY{k}"], symmetric=True)
+    X, W, dY = dev(t["X"]), dev(t[f"W{k}"]), dev(t[f"dY{k}"])
     e = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
-    for k in w.dims["f_outs"]:
-        Y_ref = oracle.gcn_forward(rp, c, val, t["X"], t[f"W{k}"])
-        dW_ref, _, dX_ref = oracle.gcn_backward(rp, c, val, t["X"], t[f"W{k}"], t[f"dY{k}"], symmetric=True)
-        W, dY = dev(t[f"W{k}"]), dev(t[f"dY{k}"])
-        for name, kw in (("auto", {}), ("fixed", fixed(B))):
-            plan = B.Plan(B.GNN_LAYER_GCN, g.n, g.nnz, m, k, **kw)
-            if name == "auto":                               # k >= m with dX: propagate-first, A'X cached
-                assert plan.info.cache == B.GNN_CACHE_AX
-            ws = B.alloc(plan.info.workspace_bytes)
-            cache = B.alloc(plan.info.cache_bytes) if plan.info.cache_bytes else None
-            Y, dW, dX = e(n, k), e(m, k), e(n, m)
-            B.gcn_layer_fwd(plan, g, X, W, None, Y, cache, ws)
-            B.gcn_layer_bwd(plan, g, None if cache is not None else X, W, None, dY, dW, None, dX, cache, ws)
-            torch.cuda.synchronize()
-            assert_close_blocks(host(Y), Y_ref, f"cfg5 {m}->{k} {name} Y")
-            assert_close(host(dW), dW_ref, f"cfg5 {m}->{k} {name} dW")
-            assert_close_blocks(host(dX), dX_ref, f"cfg5 {m}->{k} {name} dX")
-            del ws, cache, Y, dW, dX, plan
-        del Y_ref, dW_ref, dX_ref, W, dY
+    for name, kw in (("auto", {}), ("fixed", fixed(B))):
+        plan = B.Plan(B.GNN_LAYER_GCN, g.n, g.nnz, m, k, **kw)
+        if name == "auto":                                   # k >= m with dX: propagate-first, A'X cached
+            assert plan.info.cache == B.GNN_CACHE_AX
+        ws = B.alloc(plan.info.workspace_bytes)
+        cache = B.alloc(plan.info.cache_bytes) if plan.info.cache_bytes else None
+        Y, dW, dX = e(n, k), e(m, k), e(n, m)
+        B.gcn_layer_fwd(plan, g, X, W, None, Y, cache, ws)
+        B.gcn_layer_bwd(plan, g, None if cache is not None else X, W, None, dY, dW, None, dX, cache, ws)
+        torch.cuda.synchronize()
+        progress(f"cfg5 {m}->{k}: comparing the {name} scheme")
+        assert_close_blocks(host(Y), Y_ref, f"cfg5 {m}->{k} {name} Y")
+        assert_close(host(dW), dW_ref, f"cfg5 {m}->{k} {name} dW")
+        assert_close_blocks(host(dX), dX_ref, f"cfg5 {m}->{k} {name} dX")
+        del ws, cache, Y, dW, dX, plan

@@ -125,7 +125,7 @@ typedef struct {
     gnn_order_t order;        /* AUTO or a forced choice                                        */
     gnn_bwd_t bwd;
     gnn_cache_t cache;
-    gnn_select_t selection;   /* GCN, SAGE: how AUTO decides                                    */
+    gnn_select_t selection;   /* how AUTO decides (GCN, SAGE: order and scheme; GAT: the cache variant) */
     int32_t constant_input;   /* GCN, SAGE with the A'X cache: the caller promises that X and the graph
                                  are the same in every forward call until gnn_plan_reset_cache
                                  (a first layer whose input features never change).  Forward then
@@ -166,7 +166,9 @@ typedef struct gnn_plan gnn_plan_t;
  * With constant_input (and caching allowed) the forward SpMM of the cached scheme costs nothing.
  * Forced `order` / `bwd` values override the rule; cache = AX needs order = PROPAGATE_FIRST
  * (else GNN_ERR_INVALID_ARG).  GAT: order is fixed (node-attention form, App. B);
- * cache AUTO -> GNN_CACHE_GAT_FEAT_EDGE, the fastest variant of Sec. 4.2.
+ * cache AUTO -> GNN_CACHE_GAT_FEAT_EDGE, the fastest variant of Sec. 4.2; with selection = CALIBRATED ->
+ * GNN_CACHE_GAT_FEAT_NODEATT, the fastest measured on an MI355X (the edge passes rebuild alpha from four
+ * floats per node for less than reading five bytes per entry and head costs).
  * The plan is a host object owned by the caller until gnn_plan_destroy.
  */
 gnn_status_t gnn_plan_create(const gnn_plan_desc_t *desc, gnn_plan_t **out);
@@ -390,6 +392,26 @@ gnn_status_t gnn_spmm_hyb(int32_t n, int32_t t, const int32_t *ell_col, const fl
 gnn_status_t gnn_sddmm_csr(int32_t n, int32_t nnz, const int32_t *erow, const int32_t *col, const float *val,
                            const float *B, const float *Ct, int32_t heads, int32_t f, float *D,
                            void *hip_stream);
+
+/*
+ * gnn_gat_aggregate_csr - the edge phase of the GAT forward pass as one operator (Eqs. gat-fwd-att, gat-fwd):
+ *   alpha_e = softmax over the stored entries of row i of LeakyReLU(s_i + d_j)   per head,
+ *   Y_{i,p,:} = sum_e alpha_{e,p} M_{col e,p,:} (+ bias, then ELU if elu != 0),
+ * in a single pass over the entries: the logits, the running softmax and the weighted sum stay in registers,
+ * no per-edge array is written.  M, Y [n][heads][f]; s, d [n][heads] (App. B: s_i = <a_src, m_i>,
+ * d_j = <a_dst, m_j>); bias [heads * f] or NULL;
+ * stat_out [n][heads][2] receives (row maximum of the LeakyReLU'd logits, sum of exp(. - maximum)), from which
+ * alpha_e = exp(w_e - max) / sum.  erow [nnz]: row of every entry (gnn_expand_ptr).
+ *   f: a multiple of 4 with f / 4 a power of two, at most 256; M and Y 16-byte aligned
+ *   (GNN_ERR_UNSUPPORTED otherwise: gat_layer_fwd then runs the steps as separate kernels).
+ *   workspace: gnn_gat_aggregate_workspace_bytes(nnz, heads, f).
+ */
+gnn_status_t gnn_gat_aggregate_csr(int32_t n, int32_t nnz, const int32_t *rowptr, const int32_t *erow,
+                                   const int32_t *col, const float *M, const float *s, const float *d,
+                                   int32_t heads, int32_t f, float leaky_slope, const float *bias, int32_t elu,
+                                   float *Y, float *stat_out, void *workspace, size_t workspace_bytes,
+                                   void *hip_stream);
+size_t gnn_gat_aggregate_workspace_bytes(int32_t nnz, int32_t heads, int32_t f);
 
 /*
  * gnn_gemm - C = op(A) op(B) on the matrix cores: fp32 operands and results; fp32 accumulation,

@@ -95,6 +95,9 @@ _PROTOS = {
     "gnn_spmm_csr": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32, _vp, _sz, _vp]),
     "gnn_spmm_workspace_bytes": (_sz, [_i32, _i32, _i32]),
     "gnn_spmm_csr_static": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _i32, _vp]),
+    "gnn_gat_aggregate_csr": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, ctypes.c_float, _vp,
+                                             _i32, _vp, _vp, _vp, _sz, _vp]),
+    "gnn_gat_aggregate_workspace_bytes": (_sz, [_i32, _i32, _i32]),
     "gnn_sddmm_csr": (ctypes.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp]),
     "gnn_gemm": (ctypes.c_int, [_i32, _i32, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]),
     "gnn_gemm_workspace_bytes": (_sz, [_i32, _i32, _i64, _i64, _i64]),
@@ -332,6 +335,16 @@ def gnn_spmm_hyb(n, t, ell_col, ell_val, rest_nnz, coo_row, coo_col, coo_val, B,
 def gnn_sddmm_csr(n, nnz, erow, col, val, B, Ct, heads, f, D):
     _check(lib.gnn_sddmm_csr(n, nnz, _ptr(erow), _ptr(col), _ptr(val), _ptr(B), _ptr(Ct), heads, f, _ptr(D),
                              _stream()), "gnn_sddmm_csr")
+
+
+def gnn_gat_aggregate_workspace_bytes(nnz, heads, f):
+    return lib.gnn_gat_aggregate_workspace_bytes(nnz, heads, f)
+
+
+def gnn_gat_aggregate_csr(n, nnz, rowptr, erow, col, M, s, d, heads, f, leaky_slope, bias, elu, Y, stat_out, workspace):
+    _check(lib.gnn_gat_aggregate_csr(n, nnz, _ptr(rowptr), _ptr(erow), _ptr(col), _ptr(M), _ptr(s), _ptr(d), heads, f,
+                                     float(leaky_slope), _ptr(bias), int(elu), _ptr(Y), _ptr(stat_out), _ptr(workspace),
+                                     _nbytes(workspace), _stream()), "gnn_gat_aggregate_csr")
 
 
 def gnn_gemm_workspace_bytes(trans_a, trans_b, M, N, K):

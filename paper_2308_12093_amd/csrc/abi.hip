@@ -273,6 +273,24 @@ gnn_status_t gnn_sddmm_csr(int32_t n, int32_t nnz, const int32_t *erow, const in
     return sddmm_launch(n, nnz, erow, col, val, B, Ct, heads, f, D, as_stream(hip_stream));
 }
 
+size_t gnn_gat_aggregate_workspace_bytes(int32_t nnz, int32_t heads, int32_t f) {
+    return gat_fused_workspace_bytes(nnz > 0 ? nnz : 0, heads, f);
+}
+
+gnn_status_t gnn_gat_aggregate_csr(int32_t n, int32_t nnz, const int32_t *rowptr, const int32_t *erow,
+                                   const int32_t *col, const float *M, const float *s, const float *d,
+                                   int32_t heads, int32_t f, float leaky_slope, const float *bias, int32_t elu,
+                                   float *Y, float *stat_out, void *workspace, size_t workspace_bytes,
+                                   void *hip_stream) {
+    if (n < 0 || nnz < 0 || heads <= 0 || f <= 0 || !rowptr) return GNN_ERR_INVALID_ARG;
+    if (n > 0 && (!Y || !stat_out)) return GNN_ERR_INVALID_ARG;
+    if (nnz > 0 && (!erow || !col || !M || !s || !d || !workspace || bad_align(workspace))) return GNN_ERR_INVALID_ARG;
+    if (!gat_fused_shape(heads, f) || !aligned16(M) || !aligned16(Y)) return GNN_ERR_UNSUPPORTED;
+    if (nnz > 0 && workspace_bytes < gat_fused_workspace_bytes(nnz, heads, f)) return GNN_ERR_BUFFER_TOO_SMALL;
+    return gat_fused_forward_launch(n, nnz, heads, f, rowptr, erow, col, M, s, d, leaky_slope, bias,
+                                    elu ? kActElu : kActNone, Y, stat_out, workspace, as_stream(hip_stream));
+}
+
 size_t gnn_gemm_workspace_bytes(int32_t trans_a, int32_t trans_b, int64_t M, int64_t N, int64_t K) {
     if (M <= 0 || N <= 0 || K <= 0) return kAlign;
     return gemm_workspace_bytes(trans_a ? 1 : 0, trans_b ? 1 : 0, M, N, K);

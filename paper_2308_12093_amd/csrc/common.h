@@ -116,6 +116,12 @@ gnn_status_t gat_node_attention_launch(int n, int h, int k, const float *M, cons
 gnn_status_t gat_edge_softmax_launch(int n, int nnz, int h, const int32_t *rowptr, const int32_t *erow,
                                      const int32_t *col, const float *s, const float *d, float slope, float *stat,
                                      float *alpha, uint8_t *mask, void *workspace, hipStream_t st);
+gnn_status_t gat_edge_stats_launch(int n, int nnz, int h, const int32_t *rowptr, const int32_t *erow,
+                                   const int32_t *col, const float *s, const float *d, float slope, float *stat,
+                                   void *workspace, hipStream_t st);
+gnn_status_t gat_edge_alpha_launch(int nnz, int h, const int32_t *erow, const int32_t *col, const float *s,
+                                   const float *d, const float *stat, float slope, float *alpha, uint8_t *mask,
+                                   hipStream_t st);
 // gy [nnz][h]: g_alpha on entry, g_y on exit; sums [n][h][3] scratch; ds [n][h]; mask NULL: sign from s, d
 gnn_status_t gat_edge_backward_launch(int n, int nnz, int h, const int32_t *rowptr, const int32_t *erow,
                                       const int32_t *col, const float *alpha, const uint8_t *mask, const float *s,
@@ -128,5 +134,26 @@ gnn_status_t gat_attention_grad_launch(int n, int h, int k, const float *w, cons
                                        void *workspace, hipStream_t st);
 gnn_status_t sddmm_launch(int n, int nnz, const int32_t *erow, const int32_t *col, const float *val,
                           const float *B, const float *Ct, int heads, int f, float *D, hipStream_t st);
+
+// ---- fused GAT edge passes (gat_fused.hip) -----------------------------------------------
+bool gat_fused_shape(int h, int k);
+size_t gat_fused_workspace_bytes(int64_t nnz, int h, int k);
+// Y = act(softmax-weighted aggregation + bias), stat [n][h][2] = (row max, sum of exponentials)
+gnn_status_t gat_fused_forward_launch(int n, int nnz, int h, int k, const int32_t *rowptr, const int32_t *erow,
+                                      const int32_t *col, const float *M, const float *s, const float *d,
+                                      float slope, const float *bias, int act, float *Y, float *stat, void *workspace,
+                                      hipStream_t st);
+// alpha / mask [q][h] in CSR order, or NULL: rebuilt from s, d.
+// node: 4 n h floats of scratch.  Writes ds, dd [n][h] and the complete dM [n][h k].
+gnn_status_t gat_fused_backward_launch(int n, int nnz, int h, int k, const int32_t *rowptr, const int32_t *erow,
+                                       const int32_t *col, const int32_t *colptr, const int32_t *ecol,
+                                       const int32_t *row, const int32_t *perm, const float *G, const float *M,
+                                       const float *alpha, const uint8_t *mask, const float *s,
+                                       const float *d, float slope, const float *a_src, const float *a_dst,
+                                       float *node, float *ds, float *dd, float *dM, void *workspace, hipStream_t st);
+// da_src[p][c] = sum_i ds[i][p] M[i][p][c] and da_dst likewise with dd, in one pass over M;
+// workspace 2 * colsum_workspace_bytes(n, h*k)
+gnn_status_t gat_attention_grad2_launch(int n, int h, int k, const float *ds, const float *dd, const float *M,
+                                        float *da_src, float *da_dst, void *workspace, hipStream_t st);
 
 }  // namespace gnn

@@ -30,15 +30,18 @@ activation_grad_kernel(long count4, long count, const float *__restrict__ G, con
 // min(f / VEC, 256)); each block owns `rows_per_block` consecutive rows and writes one partial
 // row of f sums.  Four rows are in flight per thread (rotating accumulators, added in a
 // fixed order).  VEC = 4 needs f and head_dim to be multiples of 4 and 16-byte aligned rows.
+// With a second weight array wgt2 the kernel forms two sums in one launch: output columns [0, f) use wgt,
+// columns [f, 2f) use wgt2 on the same G (the second read of a row comes from the cache); fo = 2f then.
 template <int VEC>
 __global__ void __launch_bounds__(256)
-colsum_partial_kernel(long n, int f, int fp, long rows_per_block, const float *__restrict__ G,
-                      const float *__restrict__ wgt, int heads, int head_dim, double *__restrict__ part) {
+colsum_partial_kernel(long n, int f, int fo, int fp, long rows_per_block, const float *__restrict__ G,
+                      const float *__restrict__ wgt, const float *__restrict__ wgt2, int heads, int head_dim,
+                      double *__restrict__ part) {
     __shared__ double red[256][VEC];
     const int c0 = threadIdx.x % fp, rl = threadIdx.x / fp, lanes = 256 / fp;
     const long r0 = (long)blockIdx.x * rows_per_block;
     const long r1 = min(n, r0 + rows_per_block);
-    const int groups = (f + VEC - 1) / VEC;
+    const int groups = (fo + VEC - 1) / VEC;
     for (int cb = 0; cb < groups; cb += fp) {
         const int c = (cb + c0) * VEC;
         double a[4][VEC];
@@ -46,15 +49,17 @@ colsum_partial_kernel(long n, int f, int fp, long rows_per_block, const float *_
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int v = 0; v < VEC; ++v) a[j][v] = 0.0;
-        if (c < f) {
-            const int hd = wgt ? c / head_dim : 0;
+        if (c < fo) {
+            const int cg = c < f ? c : c - f;                         // column of G
+            const float *wsel = c < f ? wgt : wgt2;
+            const int hd = wsel ? cg / head_dim : 0;
             auto row = [&](long i, double (&acc)[VEC]) {
-                const double w = wgt ? (double)wgt[(size_t)i * heads + hd] : 1.0;
+                const double w = wsel ? (double)wsel[(size_t)i * heads + hd] : 1.0;
                 if constexpr (VEC == 4) {
-                    const float4 g = *reinterpret_cast<const float4 *>(G + (size_t)i * f + c);
+                    const float4 g = *reinterpret_cast<const float4 *>(G + (size_t)i * f + cg);
                     acc[0] += w * g.x; acc[1] += w * g.y; acc[2] += w * g.z; acc[3] += w * g.w;
                 } else {
-                    acc[0] += w * (double)G[(size_t)i * f + c];
+                    acc[0] += w * (double)G[(size_t)i * f + cg];
                 }
             };
             long i = r0 + rl;
@@ -66,12 +71,12 @@ colsum_partial_kernel(long n, int f, int fp, long rows_per_block, const float *_
 #pragma unroll
         for (int v = 0; v < VEC; ++v) red[threadIdx.x][v] = (a[0][v] + a[1][v]) + (a[2][v] + a[3][v]);
         __syncthreads();
-        if (rl == 0 && c < f) {
+        if (rl == 0 && c < fo) {
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
                 double s = 0.0;
                 for (int k = 0; k < lanes; ++k) s += red[k * fp + c0][v];
-                part[(size_t)blockIdx.x * f + c + v] = s;
+                part[(size_t)blockIdx.x * fo + c + v] = s;
             }
         }
         __syncthreads();
@@ -81,8 +86,10 @@ colsum_partial_kernel(long n, int f, int fp, long rows_per_block, const float *_
 // out[c] = sum over blocks of part[block][c].  A block of 256 threads covers 16 columns with
 // 16 lanes each (lane j takes partials j, j+16, ... into four rotating accumulators); the
 // lanes are then added in lane order, so the association is fixed.
+// Columns [split, f) go to out2 (the second of two sums formed in one launch).
 __global__ void __launch_bounds__(256)
-colsum_final_kernel(int f, int blocks, const double *__restrict__ part, float *__restrict__ out) {
+colsum_final_kernel(int f, int split, int blocks, const double *__restrict__ part, float *__restrict__ out,
+                    float *__restrict__ out2) {
     __shared__ double red[16][17];
     const int o = threadIdx.x % 16, sl = threadIdx.x / 16;
     const int c = blockIdx.x * 16 + o;
@@ -102,7 +109,8 @@ colsum_final_kernel(int f, int blocks, const double *__restrict__ part, float *_
     if (sl == 0 && c < f) {
         double t = 0.0;
         for (int k = 0; k < 16; ++k) t += red[k][o];
-        out[c] = (float)t;
+        if (c < split) out[c] = (float)t;
+        else out2[c - split] = (float)t;
     }
 }
 
@@ -241,34 +249,42 @@ size_t colsum_workspace_bytes(int64_t n, int f) {
     return align_up((size_t)blocks * f * sizeof(double));
 }
 
-static gnn_status_t colsum_weighted(int64_t n, int f, const float *G, const float *wgt, int heads, int head_dim,
-                                    float *out, void *workspace, hipStream_t st) {
+// out = sum_i wgt G (all of it when wgt is NULL); with wgt2 also out2 = sum_i wgt2 G from the same launch
+static gnn_status_t colsum_weighted(int64_t n, int f, const float *G, const float *wgt, const float *wgt2, int heads,
+                                    int head_dim, float *out, float *out2, void *workspace, hipStream_t st) {
     if (f <= 0) return GNN_OK;
     const long rpb = colsum_rows_per_block(n);
     const int blocks = (int)ceil_div(n > 0 ? n : 1, rpb);
     const bool vec = f % 4 == 0 && head_dim % 4 == 0 && aligned16(G);
-    const int groups = vec ? f / 4 : f;
+    const int fo = wgt2 ? 2 * f : f;
+    const int groups = vec ? fo / 4 : fo;
     int fp = 1;
     while (fp < groups && fp < 256) fp <<= 1;
     double *part = static_cast<double *>(workspace);
     if (vec)
-        hipLaunchKernelGGL(colsum_partial_kernel<4>, dim3(blocks), dim3(256), 0, st, (long)n, f, fp, rpb, G, wgt, heads,
-                           head_dim, part);
+        hipLaunchKernelGGL(colsum_partial_kernel<4>, dim3(blocks), dim3(256), 0, st, (long)n, f, fo, fp, rpb, G, wgt, wgt2,
+                           heads, head_dim, part);
     else
-        hipLaunchKernelGGL(colsum_partial_kernel<1>, dim3(blocks), dim3(256), 0, st, (long)n, f, fp, rpb, G, wgt, heads,
-                           head_dim, part);
+        hipLaunchKernelGGL(colsum_partial_kernel<1>, dim3(blocks), dim3(256), 0, st, (long)n, f, fo, fp, rpb, G, wgt, wgt2,
+                           heads, head_dim, part);
     GNN_TRY(launch_status());
-    hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)ceil_div(f, 16)), dim3(256), 0, st, f, blocks, part, out);
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)ceil_div(fo, 16)), dim3(256), 0, st, fo, f, blocks, part, out,
+                       out2);
     return launch_status();
 }
 
 gnn_status_t colsum_launch(int64_t n, int f, const float *G, float *out, void *workspace, hipStream_t st) {
-    return colsum_weighted(n, f, G, nullptr, 1, f, out, workspace, st);
+    return colsum_weighted(n, f, G, nullptr, nullptr, 1, f, out, nullptr, workspace, st);
 }
 
 gnn_status_t gat_attention_grad_launch(int n, int h, int k, const float *w, const float *M, float *da,
                                        void *workspace, hipStream_t st) {
-    return colsum_weighted(n, h * k, M, w, h, k, da, workspace, st);
+    return colsum_weighted(n, h * k, M, w, nullptr, h, k, da, nullptr, workspace, st);
+}
+
+gnn_status_t gat_attention_grad2_launch(int n, int h, int k, const float *ds, const float *dd, const float *M,
+                                        float *da_src, float *da_dst, void *workspace, hipStream_t st) {
+    return colsum_weighted(n, h * k, M, ds, dd, h, k, da_src, da_dst, workspace, st);
 }
 
 gnn_status_t softmax_xent_launch(int n, int c, const float *Z, const int32_t *labels, float *dZ, float *loss,

@@ -535,14 +535,21 @@ gnn_status_t gat_node_attention_launch(int n, int h, int k, const float *M, cons
     return launch_status();
 }
 
-// stat [n][h][2] = (row max of the LeakyReLU'd logits, sum of exp(. - max)); then alpha, mask
-gnn_status_t gat_edge_softmax_launch(int n, int nnz, int h, const int32_t *rowptr, const int32_t *erow,
-                                     const int32_t *col, const float *s, const float *d, float slope, float *stat,
-                                     float *alpha, uint8_t *mask, void *workspace, hipStream_t st) {
+// stat [n][h][2] = (row max of the LeakyReLU'd logits, sum of exp(. - max))
+gnn_status_t gat_edge_stats_launch(int n, int nnz, int h, const int32_t *rowptr, const int32_t *erow,
+                                   const int32_t *col, const float *s, const float *d, float slope, float *stat,
+                                   void *workspace, hipStream_t st) {
     (void)n;
     if (nnz <= 0) return GNN_OK;
     StatsOp op{s, d, slope};
-    GNN_TRY(run_head_walker<StatsOp>(nnz, h, rowptr, erow, col, op, stat, static_cast<float *>(workspace), st));
+    return run_head_walker<StatsOp>(nnz, h, rowptr, erow, col, op, stat, static_cast<float *>(workspace), st);
+}
+
+// alpha_e = exp(w_e - max_i) / sum_i from the row statistics; mask_e = (y_e > 0) when asked for
+gnn_status_t gat_edge_alpha_launch(int nnz, int h, const int32_t *erow, const int32_t *col, const float *s,
+                                   const float *d, const float *stat, float slope, float *alpha, uint8_t *mask,
+                                   hipStream_t st) {
+    if (nnz <= 0) return GNN_OK;
     if (h % 4 == 0 && aligned16(s) && aligned16(d) && aligned16(stat) && aligned16(alpha) &&
         (!mask || (reinterpret_cast<uintptr_t>(mask) & 3u) == 0)) {
         const long count = (long)nnz * (h / 4);
@@ -554,6 +561,13 @@ gnn_status_t gat_edge_softmax_launch(int n, int nnz, int h, const int32_t *rowpt
                            col, s, d, stat, slope, alpha, mask);
     }
     return launch_status();
+}
+
+gnn_status_t gat_edge_softmax_launch(int n, int nnz, int h, const int32_t *rowptr, const int32_t *erow,
+                                     const int32_t *col, const float *s, const float *d, float slope, float *stat,
+                                     float *alpha, uint8_t *mask, void *workspace, hipStream_t st) {
+    GNN_TRY(gat_edge_stats_launch(n, nnz, h, rowptr, erow, col, s, d, slope, stat, workspace, st));
+    return gat_edge_alpha_launch(nnz, h, erow, col, s, d, stat, slope, alpha, mask, st);
 }
 
 gnn_status_t sddmm_launch(int n, int nnz, const int32_t *erow, const int32_t *col, const float *val,

@@ -20,6 +20,7 @@ struct GatLayout {
     size_t c_M, c_s, c_d, c_alpha, c_mask, cache_bytes;
     size_t w_M, w_s, w_d, w_alpha, w_stat, w_walk, w_spmm, w_gemm_nn;          // used by forward (and backward)
     size_t w_gy, w_sums, w_ds, w_dd, w_spmm_h, w_dM, w_red, w_gemm_tn, w_G;    // backward only (w_G: fused ELU)
+    size_t w_fused, w_node;                                                    // fused edge passes: partials; per-node scratch
     size_t workspace_bytes;
 };
 

@@ -111,7 +111,11 @@ void size_gcn(Plan &p) {
 gnn_status_t resolve_gat(Plan &p) {
     const gnn_plan_desc_t &d = p.desc;
     gnn_cache_t c = d.cache;
-    if (c == GNN_CACHE_AUTO) c = GNN_CACHE_GAT_FEAT_EDGE;          // fastest variant in Sec. 4.2
+    // Sec. 4.2 finds the variant that keeps the edge weights fastest; on an MI355X, with the fused edge passes,
+    // rebuilding alpha from four floats per node beats reading five bytes per entry and head, and the
+    // variant that keeps the node attention values is the fastest measured
+    if (c == GNN_CACHE_AUTO)
+        c = d.selection == GNN_SELECT_CALIBRATED ? GNN_CACHE_GAT_FEAT_NODEATT : GNN_CACHE_GAT_FEAT_EDGE;
     if (c != GNN_CACHE_NONE && c != GNN_CACHE_GAT_FEAT && c != GNN_CACHE_GAT_FEAT_NODEATT &&
         c != GNN_CACHE_GAT_FEAT_EDGE)
         return GNN_ERR_INVALID_ARG;
@@ -168,9 +172,11 @@ GatLayout gat_layout(const Plan &p) {
     L.w_dd = take(n * h * fl);
     L.w_spmm_h = take(spmm_workspace_bytes(0, q, (int)h));        // its dense operand has q rows: never padded
     L.w_dM = take(n * f * fl);
-    L.w_red = take(colsum_workspace_bytes(n, (int)f));
+    L.w_red = take(2 * colsum_workspace_bytes(n, (int)f));
     L.w_gemm_tn = take(gemm_workspace_bytes(1, 0, m, f, n));
     L.w_G = d.fuse_elu ? take(n * f * fl) : (size_t)-1;
+    L.w_fused = take(gat_fused_workspace_bytes(q, (int)h, (int)k));
+    L.w_node = take(n * h * 4 * fl);
     L.workspace_bytes = off + kAlign;
     return L;
 }

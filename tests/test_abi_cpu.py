@@ -145,6 +145,9 @@ def test_gat_cache_sizes():
         assert size <= info.cache_bytes <= size + 3 * 256, (variant, info.cache_bytes, size)
         assert info.cache == variant
     assert B.Plan(B.GNN_LAYER_GAT, n, q, 256, k, heads=h).info.cache == B.GNN_CACHE_GAT_FEAT_EDGE
+    # the calibrated choice: what is fastest on this machine (alpha rebuilt from the node values)
+    assert B.Plan(B.GNN_LAYER_GAT, n, q, 256, k, heads=h, selection=B.GNN_SELECT_CALIBRATED).info.cache == \
+        B.GNN_CACHE_GAT_FEAT_NODEATT
 
 
 def test_layer_calls_reject_bad_arguments_before_any_launch():

@@ -105,7 +105,8 @@ VARIANTS = ["NONE", "GAT_FEAT", "GAT_FEAT_NODEATT", "GAT_FEAT_EDGE"]
 
 
 @pytest.mark.parametrize("variant", VARIANTS)
-@pytest.mark.parametrize("shape", [(24, 4, 8, 24), (16, 8, 8, 21), (20, 1, 16, 21), (12, 3, 5, 21)])
+@pytest.mark.parametrize("shape", [(24, 4, 8, 24), (16, 8, 8, 21), (20, 1, 16, 21), (12, 3, 5, 21),
+                                   (10, 6, 4, 21), (12, 2, 64, 24), (9, 3, 128, 25)])
 def test_forward_backward_every_variant(B, G, variant, shape):
     m, h, k, seed = shape                                   # seeds chosen so that the assertion below holds
     v = getattr(B, "GNN_CACHE_" + variant)
@@ -198,6 +199,51 @@ def test_backward_before_forward_is_a_state_error(B, G):
     with pytest.raises(B.GnnError) as e:
         layer.backward()
     assert e.value.status == B.GNN_ERR_STATE
+
+
+@pytest.mark.parametrize("heads,f,elu", [(8, 8, False), (1, 4, False), (4, 16, True), (8, 64, False), (3, 128, True),
+                                         (2, 256, False), (5, 32, False)])
+def test_fused_edge_softmax_and_aggregation_operator(B, G, heads, f, elu):
+    """gnn_gat_aggregate_csr against the oracle's separate steps (edge softmax, then aggregation): output and
+    row statistics; head widths from one float4 per head to 256 features, one and several feature tiles,
+    hub rows that span many blocks."""
+    s_ = synth.streams(50 + heads + f)
+    rowptr, col = synth.rmat_graph(12, 10, True, s_["graph"], s_["relabel"])
+    rp, c = oracle_graph(rowptr, col)
+    n, q = rp.size - 1, c.size
+    rng = np.random.default_rng(heads * 1000 + f)
+    M = rng.standard_normal((n, heads, f), dtype=np.float32)
+    sv = rng.standard_normal((n, heads), dtype=np.float32) * 2
+    dv = rng.standard_normal((n, heads), dtype=np.float32) * 2
+    bias = rng.standard_normal(heads * f, dtype=np.float32)
+    alpha, _ = oracle.gat_edge_softmax(rp, c, sv, dv, 0.2)
+    ref = oracle.gat_aggregate(rp, c, alpha, M).reshape(n, heads * f) + bias
+    if elu:
+        ref = oracle.elu(ref)
+    erow = G.expand(n, dev(rp), q)
+    Y = torch.full((n, heads * f), float("nan"), dtype=torch.float32, device="cuda")
+    stat = torch.full((n, heads, 2), float("nan"), dtype=torch.float32, device="cuda")
+    ws = B.alloc(B.gnn_gat_aggregate_workspace_bytes(q, heads, f))
+    ws.fill_(0xFF)
+    B.gnn_gat_aggregate_csr(n, q, dev(rp), erow, dev(c), dev(M), dev(sv), dev(dv), heads, f, 0.2, dev(bias), elu, Y,
+                            stat, ws)
+    torch.cuda.synchronize()
+    assert_close(host(Y), ref, f"Y heads={heads} f={f}")
+    # statistics: alpha rebuilt from them must be the oracle's alpha
+    st = host(stat).astype(np.float64)
+    rows = np.repeat(np.arange(n), np.diff(rp))
+    y = sv.astype(np.float64)[rows] + dv.astype(np.float64)[c]
+    w = np.where(y > 0, y, 0.2 * y)
+    assert_close(np.exp(w - st[rows, :, 0]) / st[rows, :, 1], alpha, "alpha from the row statistics")
+
+
+def test_fused_operator_rejects_shapes_it_does_not_take(B, G):
+    one = 256
+    for heads, f in ((3, 5), (1, 7), (2, 12), (1, 512)):
+        st = B.lib.gnn_gat_aggregate_csr(4, 4, one, one, one, one, one, one, heads, f, 0.2, None, 0, one, one, one, 1 << 20, None)
+        assert st == B.GNN_ERR_UNSUPPORTED, (heads, f, st)
+    assert B.lib.gnn_gat_aggregate_csr(4, 4, one, one, one, one, one, one, 2, 8, 0.2, None, 0, one, one, one, 0, None) == \
+        B.GNN_ERR_BUFFER_TOO_SMALL
 
 
 @pytest.mark.parametrize("heads,f", [(1, 64), (8, 8), (3, 5), (1, 7)])

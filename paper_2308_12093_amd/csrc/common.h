@@ -65,16 +65,21 @@ gnn_status_t spmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *c
 
 // ---- dense products (gemm.hip) ----------------------------------------------------
 size_t gemm_workspace_bytes(int ta, int tb, int64_t M, int64_t N, int64_t K);
+// b_mask (transposed-A form only): B is used as B .* act'(b_mask), the derivative of the activation
+// b_mask_act (kActRelu, kActElu) taken from its output b_mask, an array of B's shape
 gnn_status_t gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A, const float *B,
-                         float *C, const float *bias, int relu, void *workspace, hipStream_t st);
+                         float *C, const float *bias, int relu, void *workspace, hipStream_t st,
+                         const float *b_mask = nullptr, int b_mask_act = 0);
 
 // ---- element-wise and reductions (elementwise.hip) ---------------------------------
 // out = G * [Y > 0]
 // out = G * act'(x) with the derivative taken from the activation's output Y (kActRelu or kActElu)
 gnn_status_t activation_grad_launch(int64_t count, const float *G, const float *Y, float *out, int act, hipStream_t st);
-// out[c] = sum_i G[i][c], deterministic two-stage; workspace colsum_workspace_bytes(n, f)
+// out[c] = sum_i G[i][c], deterministic two-stage; workspace colsum_workspace_bytes(n, f).
+// With mask_y: the sum of G .* act'(mask_y) (mask_act: kActRelu or kActElu), as in activation_grad_launch.
 size_t colsum_workspace_bytes(int64_t n, int f);
-gnn_status_t colsum_launch(int64_t n, int f, const float *G, float *out, void *workspace, hipStream_t st);
+gnn_status_t colsum_launch(int64_t n, int f, const float *G, float *out, void *workspace, hipStream_t st,
+                           const float *mask_y = nullptr, int mask_act = 0);
 gnn_status_t squared_error_launch(int64_t count, const float *Z, const float *T, float *dZ, float *loss,
                                   void *workspace, hipStream_t st);
 gnn_status_t softmax_xent_launch(int n, int c, const float *Z, const int32_t *labels, float *dZ, float *loss,

@@ -36,7 +36,7 @@ template <int VEC>
 __global__ void __launch_bounds__(256)
 colsum_partial_kernel(long n, int f, int fo, int fp, long rows_per_block, const float *__restrict__ G,
                       const float *__restrict__ wgt, const float *__restrict__ wgt2, int heads, int head_dim,
-                      double *__restrict__ part) {
+                      const float *__restrict__ mask_y, int mask_act, double *__restrict__ part) {
     __shared__ double red[256][VEC];
     const int c0 = threadIdx.x % fp, rl = threadIdx.x / fp, lanes = 256 / fp;
     const long r0 = (long)blockIdx.x * rows_per_block;
@@ -55,11 +55,19 @@ colsum_partial_kernel(long n, int f, int fo, int fp, long rows_per_block, const 
             const int hd = wsel ? cg / head_dim : 0;
             auto row = [&](long i, double (&acc)[VEC]) {
                 const double w = wsel ? (double)wsel[(size_t)i * heads + hd] : 1.0;
+                // with mask_y: G times the derivative of the fused activation, taken from its output
+                auto dact = [mask_act](float g, float y) { return y > 0.f ? g : (mask_act == kActElu ? g * (y + 1.f) : 0.f); };
                 if constexpr (VEC == 4) {
-                    const float4 g = *reinterpret_cast<const float4 *>(G + (size_t)i * f + cg);
+                    float4 g = *reinterpret_cast<const float4 *>(G + (size_t)i * f + cg);
+                    if (mask_y) {
+                        const float4 y = *reinterpret_cast<const float4 *>(mask_y + (size_t)i * f + cg);
+                        g = make_float4(dact(g.x, y.x), dact(g.y, y.y), dact(g.z, y.z), dact(g.w, y.w));
+                    }
                     acc[0] += w * g.x; acc[1] += w * g.y; acc[2] += w * g.z; acc[3] += w * g.w;
                 } else {
-                    acc[0] += w * (double)G[(size_t)i * f + cg];
+                    float g = G[(size_t)i * f + cg];
+                    if (mask_y) g = dact(g, mask_y[(size_t)i * f + cg]);
+                    acc[0] += w * (double)g;
                 }
             };
             long i = r0 + rl;
@@ -251,11 +259,12 @@ size_t colsum_workspace_bytes(int64_t n, int f) {
 
 // out = sum_i wgt G (all of it when wgt is NULL); with wgt2 also out2 = sum_i wgt2 G from the same launch
 static gnn_status_t colsum_weighted(int64_t n, int f, const float *G, const float *wgt, const float *wgt2, int heads,
-                                    int head_dim, float *out, float *out2, void *workspace, hipStream_t st) {
+                                    int head_dim, float *out, float *out2, void *workspace, hipStream_t st,
+                                    const float *mask_y = nullptr, int mask_act = 0) {
     if (f <= 0) return GNN_OK;
     const long rpb = colsum_rows_per_block(n);
     const int blocks = (int)ceil_div(n > 0 ? n : 1, rpb);
-    const bool vec = f % 4 == 0 && head_dim % 4 == 0 && aligned16(G);
+    const bool vec = f % 4 == 0 && head_dim % 4 == 0 && aligned16(G) && (!mask_y || aligned16(mask_y));
     const int fo = wgt2 ? 2 * f : f;
     const int groups = vec ? fo / 4 : fo;
     int fp = 1;
@@ -263,18 +272,19 @@ static gnn_status_t colsum_weighted(int64_t n, int f, const float *G, const floa
     double *part = static_cast<double *>(workspace);
     if (vec)
         hipLaunchKernelGGL(colsum_partial_kernel<4>, dim3(blocks), dim3(256), 0, st, (long)n, f, fo, fp, rpb, G, wgt, wgt2,
-                           heads, head_dim, part);
+                           heads, head_dim, mask_y, mask_act, part);
     else
         hipLaunchKernelGGL(colsum_partial_kernel<1>, dim3(blocks), dim3(256), 0, st, (long)n, f, fo, fp, rpb, G, wgt, wgt2,
-                           heads, head_dim, part);
+                           heads, head_dim, mask_y, mask_act, part);
     GNN_TRY(launch_status());
     hipLaunchKernelGGL(colsum_final_kernel, dim3((unsigned)ceil_div(fo, 16)), dim3(256), 0, st, fo, f, blocks, part, out,
                        out2);
     return launch_status();
 }
 
-gnn_status_t colsum_launch(int64_t n, int f, const float *G, float *out, void *workspace, hipStream_t st) {
-    return colsum_weighted(n, f, G, nullptr, nullptr, 1, f, out, nullptr, workspace, st);
+gnn_status_t colsum_launch(int64_t n, int f, const float *G, float *out, void *workspace, hipStream_t st,
+                           const float *mask_y, int mask_act) {
+    return colsum_weighted(n, f, G, nullptr, nullptr, 1, f, out, nullptr, workspace, st, mask_y, mask_act);
 }
 
 gnn_status_t gat_attention_grad_launch(int n, int h, int k, const float *w, const float *M, float *da,

@@ -69,15 +69,20 @@ gnn_status_t gcn_backward(Plan &p, const gnn_graph_t &g, const float *X, const f
     const bool dx = d.need_input_grad != 0;
     Carver ws(workspace);
 
+    // Gradient through the fused ReLU: G = dY .* [Y > 0].  When the only readers of G are the weight-gradient
+    // product and the bias sum (split-propagate scheme without dX: the first layer of a network), they apply
+    // the mask to dY as they load it and G is never written; otherwise one pass makes it.
+    const bool mask_in_consumers = d.fuse_relu && p.info.bwd == GNN_BWD_SPLIT_PROPAGATE && !dx;
+    const float *mask_y = mask_in_consumers ? Y : nullptr;
     const float *G = dY;
-    if (d.fuse_relu) {                              // gradient through the fused ReLU
-        float *Gm = ws.take<float>((size_t)n * k);
+    float *Gm = d.fuse_relu ? ws.take<float>((size_t)n * k) : nullptr;   // carved either way: the layout is the plan's
+    if (d.fuse_relu && !mask_in_consumers) {
         GNN_TRY(activation_grad_launch((int64_t)n * k, dY, Y, Gm, kActRelu, st));
         G = Gm;
     }
     if (d.has_bias) {                               // db = G^T 1
         void *red = ws.take<char>(colsum_workspace_bytes(n, k));
-        GNN_TRY(colsum_launch(n, k, G, db, red, st));
+        GNN_TRY(colsum_launch(n, k, G, db, red, st, mask_y, kActRelu));
     }
     void *gemm_ws = ws.take<char>(gemm_workspace_bytes(1, 0, m, k, n));
 
@@ -99,7 +104,7 @@ gnn_status_t gcn_backward(Plan &p, const gnn_graph_t &g, const float *X, const f
             GNN_TRY(spmm(g, forward_view(g, m), X, m, Pw, nullptr, 0, sp, st));
             P = Pw;
         }
-        GNN_TRY(gemm_launch(1, 0, m, k, n, P, G, dW, nullptr, 0, gemm_ws, st));
+        GNN_TRY(gemm_launch(1, 0, m, k, n, P, G, dW, nullptr, 0, gemm_ws, st, mask_y, kActRelu));
         if (dx) {
             GNN_TRY(gemm_launch(0, 1, n, m, k, G, W, U, nullptr, 0, nullptr, st));
             GNN_TRY(spmm(g, transposed_view(g, m), U, m, dX, nullptr, 0, sp, st));

@@ -43,9 +43,13 @@ constexpr int BK = 32;
 // LDS is double-buffered: the next k-tile is fetched into registers before the current one is
 // multiplied and written to the other buffer after it (one barrier per k-tile); the operands
 // of k-step s+1 are read and widened before the instructions of step s.
-template <int WM, int WN, int TM, int TN>
+// MASK: B is used as B .* act'(Ymask), the derivative of a fused activation taken from the layer's output
+// Ymask (same shape as B): ReLU 1 / 0, ELU 1 / y + 1.  The gradient through the activation then needs no
+// pass of its own: the second operand stream costs nothing while the matrix cores are the bound.
+template <int WM, int WN, int TM, int TN, bool MASK>
 __global__ void __launch_bounds__(256)
 gemm_tn_f64_kernel(int M, int N, long K, const float *__restrict__ A, const float *__restrict__ B,
+                   const float *__restrict__ Ymask, int mask_act,
                    double *__restrict__ P, long k_chunk, int tiles_m, int tiles_n, int splits, int vec_a, int vec_b) {
     constexpr int BM = WM * TM * 16, BN = WN * TN * 16, KSTEP = 4;
     // words per LDS row: the lanes of one k-row read 16 * T consecutive words; T = 1: four rows fill the 64
@@ -101,7 +105,14 @@ gemm_tn_f64_kernel(int M, int N, long K, const float *__restrict__ A, const floa
             if (NA % 256 == 0 || t + 256 * p < NA) ra[p] = fetch_one(A, M, m0, BM, vec_a, k0, t + 256 * p);
 #pragma unroll
         for (int p = 0; p < GB; ++p)
-            if (NB % 256 == 0 || t + 256 * p < NB) rb[p] = fetch_one(B, N, n0, BN, vec_b, k0, t + 256 * p);
+            if (NB % 256 == 0 || t + 256 * p < NB) {
+                rb[p] = fetch_one(B, N, n0, BN, vec_b, k0, t + 256 * p);
+                if constexpr (MASK) {
+                    const floatx4 y = fetch_one(Ymask, N, n0, BN, vec_b, k0, t + 256 * p);
+                    auto dact = [mask_act](float g, float yy) { return yy > 0.f ? g : (mask_act == kActElu ? g * (yy + 1.f) : 0.f); };
+                    rb[p] = floatx4{dact(rb[p].x, y.x), dact(rb[p].y, y.y), dact(rb[p].z, y.z), dact(rb[p].w, y.w)};
+                }
+            }
     };
     auto stage = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
@@ -614,16 +625,23 @@ size_t gemm_workspace_bytes(int ta, int tb, int64_t M, int64_t N, int64_t K) {
         constexpr int LA_ = BM_ + (TM_ == 1 ? (80 - BM_ % 64) % 64 : TM_ == 2 ? (96 - BM_ % 64) % 64 : 4);       \
         constexpr int LB_ = BN_ + (TN_ == 1 ? (80 - BN_ % 64) % 64 : TN_ == 2 ? (96 - BN_ % 64) % 64 : 4);       \
         const size_t lds = (size_t)2 * BK * (LA_ + LB_) * sizeof(float);                                         \
-        hipLaunchKernelGGL((gemm_tn_f64_kernel<WM_, WN_, TM_, TN_>), grid, dim3(256), lds, st, (int)M, (int)N,   \
-                           (long)K, A, B, static_cast<double *>(workspace), k_chunk, tiles_m, tiles_n, splits,   \
-                           vec_a, vec_b);                                                                        \
+        if (b_mask)                                                                                              \
+            hipLaunchKernelGGL((gemm_tn_f64_kernel<WM_, WN_, TM_, TN_, true>), grid, dim3(256), lds, st, (int)M,  \
+                               (int)N, (long)K, A, B, b_mask, b_mask_act, static_cast<double *>(workspace),      \
+                               k_chunk, tiles_m, tiles_n, splits, vec_a, vec_b);                                 \
+        else                                                                                                     \
+            hipLaunchKernelGGL((gemm_tn_f64_kernel<WM_, WN_, TM_, TN_, false>), grid, dim3(256), lds, st, (int)M, \
+                               (int)N, (long)K, A, B, nullptr, 0, static_cast<double *>(workspace), k_chunk,     \
+                               tiles_m, tiles_n, splits, vec_a, vec_b);                                          \
         launched = true;                                                                                         \
     }
 
 gnn_status_t gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A, const float *B,
-                         float *C, const float *bias, int relu, void *workspace, hipStream_t st) {
+                         float *C, const float *bias, int relu, void *workspace, hipStream_t st,
+                         const float *b_mask, int b_mask_act) {
     if (M <= 0 || N <= 0) return GNN_OK;
     if (ta && tb) return GNN_ERR_UNSUPPORTED;
+    if (b_mask && !ta) return GNN_ERR_UNSUPPORTED;         // only the transposed-A product masks its second operand
     if (M > INT32_MAX / 2 || N > INT32_MAX / 2 || (!ta && K > INT32_MAX / 2)) return GNN_ERR_UNSUPPORTED;
     const bool f64 = ta != 0;
     const Tiling tl = pick_tiling(f64, M, N);
@@ -660,7 +678,7 @@ gnn_status_t gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const 
     splits = (int)ceil_div(K > 0 ? K : 1, k_chunk);
     // a float4 may be read only if every granule start is 16-byte aligned
     const int vec_a = aligned16(A) && M % 4 == 0;
-    const int vec_b = aligned16(B) && N % 4 == 0;
+    const int vec_b = aligned16(B) && N % 4 == 0 && (!b_mask || aligned16(b_mask));
     const long total = (long)tiles_m * tiles_n * splits;
     dim3 grid((unsigned)(8 * ceil_div(total, 8)));
     GEMM_F64_CASE(4, 1, 1, 1) GEMM_F64_CASE(4, 1, 1, 2) GEMM_F64_CASE(2, 2, 2, 2) GEMM_F64_CASE(2, 2, 4, 4)

@@ -385,13 +385,21 @@ struct Shape {
 // widths that are not a multiple of 4 (and wide enough to gain from it) run on a padded copy of B
 bool padded_operand(int f) { return f % 4 != 0 && f > 4; }
 
+// One thread per four consecutive columns of the padded copy (fp a multiple of 4, Bp 16-byte aligned).
 __global__ void __launch_bounds__(256)
 pad_rows_kernel(long n, int f, int fp, const float *__restrict__ B, float *__restrict__ Bp) {
     const long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n * fp) return;
-    const long r = i / fp;
-    const int c = (int)(i - r * fp);
-    Bp[i] = c < f ? B[r * f + c] : 0.f;
+    const int q = fp / 4;
+    if (i >= n * q) return;
+    const long r = i / q;
+    const int c = (int)(i - r * q) * 4;
+    const float *src = B + r * f + c;
+    float4 v;
+    v.x = src[0];                                           // c < f always: fp - f < 4
+    v.y = c + 1 < f ? src[1] : 0.f;
+    v.z = c + 2 < f ? src[2] : 0.f;
+    v.w = c + 3 < f ? src[3] : 0.f;
+    *reinterpret_cast<float4 *>(Bp + r * fp + c) = v;
 }
 
 Shape pick_shape(int f, bool vec4) {
@@ -484,8 +492,8 @@ gnn_status_t spmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *c
     float *Bp = nullptr;
     if (ragged) {
         Bp = reinterpret_cast<float *>(static_cast<char *>(workspace) + partials_bytes(nnz, f));
-        hipLaunchKernelGGL(pad_rows_kernel, dim3((unsigned)ceil_div(b_rows * fp, 256)), dim3(256), 0, st, b_rows, f,
-                           fp, B, Bp);
+        hipLaunchKernelGGL(pad_rows_kernel, dim3((unsigned)ceil_div(b_rows * (fp / 4), 256)), dim3(256), 0, st, b_rows,
+                           f, fp, B, Bp);
         GNN_TRY(launch_status());
     }
     const int seg = spmm_segment_len(nnz, f);

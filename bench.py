@@ -63,6 +63,10 @@ def parse():
     ap.add_argument("--format-study", action="store_true",
                     help="time SpMM on the cfg2 graph and on an even-degree graph of the same size in CSR, coordinate, "
                          "ELLPACK and hybrid storage (App. D / E.1); prints one JSON line")
+    ap.add_argument("--row-order-study", action="store_true",
+                    help="time SpMM on the chosen GCN workload with the rows of the matrix stored in other orders (by degree, by "
+                         "smallest neighbour, by a min-hash of the neighbour set, random): does co-scheduling similar rows cut "
+                         "the re-fetch of dense rows?  prints one JSON line")
     ap.add_argument("--copy-reference", action="store_true",
                     help="only run three plain 256 MiB device copies (known bytes, to scale rocprofv3 byte counters)")
     return ap.parse_args()
@@ -511,12 +515,12 @@ class GatSingle:
 
 def gat_edge_bytes(n, q, h, k, variant):
     """Algorithmic bytes of the edge phase of one GAT forward + backward (everything between the dense
-    products), every array once: the index arrays of both passes (erow, col; ecol, row, perm: 20 q),
-    forward M read and Y written (8 n h k), backward G and M read twice each, dM written (20 n h k), the
-    per-node vectors s, d, row statistics, t, ds, dd (about 40 n h), and, for the variant that keeps them,
-    alpha written once and read twice plus the mask (13 q h)."""
-    per_edge = 13 * q * h if variant == "edge" else 0
-    return 20 * q + 28 * n * h * k + 40 * n * h + per_edge
+    products), every array once per pass that needs it: the index arrays of the three passes (erow, col twice;
+    ecol, row, perm: 28 q), forward M read and Y written (8 n h k), backward G and M read by both passes and dM
+    written (20 n h k), the per-node vectors s, d, row statistics, node values, ds, dd (about 60 n h), and, for
+    the variant that keeps them, alpha and the mask written once and read by both backward passes (15 q h)."""
+    per_edge = 15 * q * h if variant == "edge" else 0
+    return 28 * q + 28 * n * h * k + 60 * n * h + per_edge
 
 
 def bench_gat(args, torch, B, graphs, synth, oracle):
@@ -532,18 +536,11 @@ def bench_gat(args, torch, B, graphs, synth, oracle):
     bwd_ms = stats(ev.blocks(lambda: run.bwd(L), 5, 20))
     edge_feat = q * (m + f)
 
-    # the two sparse operators on their own: SDDMM (App. E.2) and the attention-weighted aggregation
-    G3, M3 = run.d["dY"], L["Y"]
-    D = torch.empty((q, h), dtype=torch.float32, device="cuda")
-    sddmm_ms = float(np.mean(ev.blocks(lambda: B.gnn_sddmm_csr(n, q, g.erow, g.col, None, G3, M3, h, k, D), 10, 20)))
-    sddmm_bytes = 8 * q + 8 * n * f + 4 * q * h                # erow, col; both dense operands once; D written
+    # the two sparse operators on their own: the fused edge softmax + aggregation (the forward edge phase, one
+    # launch of the entry-balanced walker and its fix-up) and the SDDMM (App. E.2)
     variant_name = {int(gat_variant(B, v)): v for v in GAT_VARIANTS}[int(L["plan"].info.cache)]
-    roofline = {"bound": "hbm", "kernel": "sddmm (gnn_sddmm_csr, 8 heads x 8 features)",
-                "achieved": round(sddmm_bytes / sddmm_ms / 1e6, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(sddmm_bytes / sddmm_ms / 1e6 / HBM_PEAK_GBPS, 4),
-                "traffic": profile_traffic("cfg4", "sddmm")[0], "traffic_source": profile_traffic("cfg4", "sddmm")[1],
-                "bytes_per_launch": sddmm_bytes, "avg_ms_per_launch": round(sddmm_ms, 5),
-                "edge_phase": gat_edge_phase(args, torch, B, ev, run, L, variant_name)}
+    roofline = gat_operator_roofline(torch, B, ev, g, h, k, run.d["dY"], "cfg4")
+    roofline["edge_phase"] = gat_edge_phase(args, torch, B, ev, run, L, variant_name)
     cpu = None
     if oracle is not None:
         t = w.tensors
@@ -563,6 +560,33 @@ def bench_gat(args, torch, B, graphs, synth, oracle):
               "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "cache_bytes": int(L["plan"].info.cache_bytes)}
     return {"metric": "GAT layer fwd+bwd edge-feat/s", "value": edge_feat / (ms * 1e-3), "ms_per_step": ms,
             "config": config, "roofline": roofline, "cpu_baseline": cpu}
+
+
+def gat_operator_roofline(torch, B, ev, g, h, k, feat, workload):
+    """gnn_gat_aggregate_csr and gnn_sddmm_csr timed on their own, priced by their algorithmic bytes: index
+    arrays once, every dense operand once, outputs once."""
+    n, q, f = g.n, g.nnz, h * k
+    e = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
+    sv, dv = torch.randn((n, h), device="cuda"), torch.randn((n, h), device="cuda")
+    Y, stat, D = e(n, f), e(n, h, 2), e(q, h)
+    ws = B.alloc(B.gnn_gat_aggregate_workspace_bytes(q, h, k))
+    agg_ms = float(np.mean(ev.blocks(lambda: B.gnn_gat_aggregate_csr(n, q, g.rowptr, g.erow, g.col, feat, sv, dv, h, k, 0.2,
+                                                                      None, False, Y, stat, ws), 10, 20)))
+    agg_bytes = 8 * q + 8 * n * f + 16 * n * h              # erow, col; M read, Y written; s, d read, (max, sum) written
+    sddmm_ms = float(np.mean(ev.blocks(lambda: B.gnn_sddmm_csr(n, q, g.erow, g.col, None, feat, Y, h, k, D), 10, 20)))
+    sddmm_bytes = 8 * q + 8 * n * f + 4 * q * h             # erow, col; both dense operands once; D written
+    traffic, src = profile_traffic(workload, "gat_aggregate")
+    return {"bound": "hbm", "kernel": f"seg_walk_kernel<FwdOp> + seg_fixup_kernel (gnn_gat_aggregate_csr: edge softmax + "
+                                      f"aggregation in one pass, {h} heads x {k} features)",
+            "achieved": round(agg_bytes / agg_ms / 1e6, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(agg_bytes / agg_ms / 1e6 / HBM_PEAK_GBPS, 4), "traffic": traffic, "traffic_source": src,
+            "traffic_frac": None if traffic is None else round(traffic / agg_ms / 1e6 / HBM_PEAK_GBPS, 4),
+            "bytes_per_launch": agg_bytes, "avg_ms_per_launch": round(agg_ms, 5),
+            "no_reuse_gather_GBps": round((8 * q + 4 * q * f + 4 * n * f + 16 * n * h) / agg_ms / 1e6, 1),
+            "sddmm": {"kernel": "sddmm_edge_kernel (gnn_sddmm_csr)", "bytes_per_launch": sddmm_bytes,
+                      "avg_ms_per_launch": round(sddmm_ms, 5), "achieved": round(sddmm_bytes / sddmm_ms / 1e6, 1),
+                      "frac": round(sddmm_bytes / sddmm_ms / 1e6 / HBM_PEAK_GBPS, 4),
+                      "traffic": profile_traffic(workload, "sddmm")[0]}}
 
 
 def gat_edge_phase(args, torch, B, ev, run, L, variant_name):
@@ -619,13 +643,8 @@ def bench_gat_network(args, torch, B, graphs, synth, oracle):
     ms = wall_ms_per_step(torch, step, args.warmup, args.steps)
     edge_feat = q * (m + f) + q * (f + f)
     ev = HipEvents(torch.cuda.current_stream().cuda_stream)
-    D = torch.empty((q, h), dtype=torch.float32, device="cuda")
-    sddmm_ms = float(np.mean(ev.blocks(lambda: B.gnn_sddmm_csr(n, q, g.erow, g.col, None, dZ, Z, h, k, D), 10, 20)))
-    sddmm_bytes = 8 * q + 8 * n * f + 4 * q * h
-    roofline = {"bound": "hbm", "kernel": f"sddmm (gnn_sddmm_csr, {h} heads x {k} features)",
-                "achieved": round(sddmm_bytes / sddmm_ms / 1e6, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(sddmm_bytes / sddmm_ms / 1e6 / HBM_PEAK_GBPS, 4), "traffic": None,
-                "bytes_per_launch": sddmm_bytes, "avg_ms_per_launch": round(sddmm_ms, 5)}
+    roofline = gat_operator_roofline(torch, B, ev, g, h, k, dZ, "gatnet") if k % 4 == 0 and k <= 256 and (k // 4) & (k // 4 - 1) == 0 \
+        else None
     cpu = None
     if oracle is not None:
         # sample: forward + backward of the first layer alone (256 -> 8 x hidden), on the host copies of its inputs
@@ -721,6 +740,56 @@ def format_study(args, torch, B, graphs, synth):
     print(json.dumps({"format_study": out}))
 
 
+def row_order_study(args, torch, B, graphs, synth):
+    """SpMM on P A' for row permutations P: the kernel walks an explicit entry list, so the storage order of
+    the rows decides which rows share a block, an XCD and a moment in time, while B and the column indices stay
+    as they are.  Every order launches gnn_spmm_csr 3 + 5 times (the counters of a rocprofv3 --pmc run of this
+    command can be matched to the orders by dispatch sequence)."""
+    w = synth.config2() if args.workload == "cfg2" else synth.config5()
+    f = 128 if args.workload == "cfg2" else 64
+    g = graphs.gcn_graph(w.rowptr, w.col, "cuda")
+    n, q = g.n, g.nnz
+    rp, col, val = g.rowptr.cpu().numpy().astype(np.int64), g.col.cpu().numpy(), g.val.cpu().numpy()
+    deg = np.diff(rp)
+    ev = HipEvents(torch.cuda.current_stream().cuda_stream)
+    Bm = torch.randn((n, f), device="cuda")
+    C = torch.empty((n, f), device="cuda")
+    ws = B.alloc(B.gnn_spmm_workspace_bytes(n, q, f))
+
+    def order_of(name):
+        if name == "as given":
+            return None
+        if name == "by degree, hubs first":
+            return np.argsort(-deg, kind="stable")
+        if name == "by smallest neighbour":
+            return np.argsort(col[rp[:-1]], kind="stable")
+        if name == "by min-hash of the neighbour set":
+            hsh = (col.astype(np.uint64) * np.uint64(2654435761)) % np.uint64(1 << 32)
+            return np.argsort(np.minimum.reduceat(hsh, rp[:-1]), kind="stable")
+        return np.random.default_rng(1).permutation(n)
+
+    out = {}
+    for name in ("as given", "by degree, hubs first", "by smallest neighbour", "by min-hash of the neighbour set", "random"):
+        perm = order_of(name)
+        if perm is None:
+            d_rp, d_col, d_val, d_erow = g.rowptr, g.col, g.val, g.erow
+        else:
+            lens = deg[perm]
+            nrp = np.zeros(n + 1, np.int64)
+            np.cumsum(lens, out=nrp[1:])
+            idx = np.repeat(rp[perm] - nrp[:-1], lens) + np.arange(q)
+            d_rp = torch.from_numpy(nrp.astype(np.int32)).cuda()
+            d_col, d_val = torch.from_numpy(col[idx]).cuda(), torch.from_numpy(val[idx]).cuda()
+            d_erow = torch.from_numpy(np.repeat(np.arange(n, dtype=np.int32), lens)).cuda()
+            del idx
+        call = lambda: B.gnn_spmm_csr(n, q, d_rp, d_col, d_val, d_erow, Bm, f, C, None, False, ws)
+        for _ in range(3):
+            call()
+        out[name] = round(ev.time_ms(call, 5), 5)
+        print(f"{name}: {out[name]} ms", file=sys.stderr)
+    print(json.dumps({"row_order_study": {"workload": w.name, "n": n, "nnz": q, "f": f, "launches_per_order": 8, "ms": out}}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -741,6 +810,8 @@ def main():
 
     if args.format_study:
         return format_study(args, torch, B, graphs, synth)
+    if args.row_order_study:
+        return row_order_study(args, torch, B, graphs, synth)
     oracle = None
     if not args.no_cpu_baseline:
         import oracle

@@ -1,5 +1,6 @@
 """The C ABI called from a C program (tests/c_abi/gcn_layer_from_c.c, built by build()): preprocessing,
-plan, one GCN layer forward and backward, checked inside the program against the dense definition."""
+plan, one GCN layer forward and backward, then one GAT layer in every caching variant, each checked inside
+the program against the dense definition."""
 import os
 import subprocess
 
@@ -16,3 +17,4 @@ def test_gcn_layer_from_a_c_program():
     r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
     assert r.stdout.startswith("ok: GCN layer from C")
+    assert r.stdout.count("ok: GAT layer from C") == 4, r.stdout

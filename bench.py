@@ -194,6 +194,15 @@ def spmm_launch_widths(B, info, f_in, k):
     return out
 
 
+def summary_record(rec):
+    """One line of the adaptive-against-fixed table.  `equal_spmm_work`: both schemes run SpMMs of the same total
+    dense width (F_out = F_in with dX, or the same scheme): the method predicts a tie there (Sec. 3.1)."""
+    (auto_ms, auto_name, auto_w), (fix_ms, fix_name, fix_w) = rec["auto"], rec["tf_fp"]
+    return {"auto_ms": round(auto_ms, 4), "fixed_ms": round(fix_ms, 4), "auto_scheme": auto_name,
+            "spmm_width_auto": auto_w, "spmm_width_fixed": fix_w, "equal_spmm_work": auto_w == fix_w,
+            "speedup": round(fix_ms / auto_ms, 3)}
+
+
 SCHEMES = ("auto", "tf_fp", "pf_sp_nocache", "pf_sp_cache")
 
 
@@ -268,12 +277,11 @@ class GcnSingle:
                 rec = {}
                 for scheme in ("auto", "tf_fp"):
                     L = self.make_layer(k, scheme, dx)
-                    rec[scheme] = (self.step_ms([L], warmup, steps), scheme_name(self.B, L["plan"].info))
+                    info = L["plan"].info
+                    rec[scheme] = (self.step_ms([L], warmup, steps), scheme_name(self.B, info),
+                                   int(info.spmm_width_fwd + info.spmm_width_bwd))
                     del L
-                out[f"F_out={k},{'dX' if dx else 'no dX'}"] = {
-                    "auto_ms": round(rec["auto"][0], 4), "fixed_ms": round(rec["tf_fp"][0], 4),
-                    "auto_scheme": rec["auto"][1], "same_scheme": rec["auto"][1] == rec["tf_fp"][1],
-                    "speedup": round(rec["tf_fp"][0] / rec["auto"][0], 3)}
+                out[f"F_out={k},{'dX' if dx else 'no dX'}"] = summary_record(rec)
         return out
 
 
@@ -419,11 +427,10 @@ class GcnNetwork:
         for scheme in ("auto", "tf_fp"):
             N = self.make(scheme)
             rec[scheme] = (wall_ms_per_step(self.torch, lambda: self.step(N), warmup, steps),
-                           [scheme_name(self.B, N[p].info) for p in ("p1", "p2")])
+                           [scheme_name(self.B, N[p].info) for p in ("p1", "p2")],
+                           sum(int(N[p].info.spmm_width_fwd + N[p].info.spmm_width_bwd) for p in ("p1", "p2")))
             del N
-        return {"100->256->47": {"auto_ms": round(rec["auto"][0], 4), "fixed_ms": round(rec["tf_fp"][0], 4),
-                                 "auto_scheme": rec["auto"][1], "same_scheme": rec["auto"][1] == rec["tf_fp"][1],
-                                 "speedup": round(rec["tf_fp"][0] / rec["auto"][0], 3)}}
+        return {"100->256->47": summary_record(rec)}
 
 
 def bench_gcn_network(args, torch, B, graphs, synth, oracle):
@@ -681,8 +688,9 @@ def all_configs_summary(args, torch, B, graphs, synth, have):
         del run
         torch.cuda.empty_cache()
     gcn = [rec for name in ("cfg1", "cfg2", "cfg3", "cfg5") for rec in out[name].values()]
-    out["adaptive_no_slower_than_fixed_everywhere"] = all(r["auto_ms"] <= 1.03 * r["fixed_ms"] for r in gcn)
-    out["adaptive_faster_where_schemes_differ"] = all(r["auto_ms"] < r["fixed_ms"] for r in gcn if not r["same_scheme"])
+    out["adaptive_within_3_percent_of_fixed_where_work_is_equal"] = all(
+        r["auto_ms"] <= 1.03 * r["fixed_ms"] for r in gcn if r["equal_spmm_work"])
+    out["adaptive_faster_where_work_differs"] = all(r["auto_ms"] < r["fixed_ms"] for r in gcn if not r["equal_spmm_work"])
     return out
 
 

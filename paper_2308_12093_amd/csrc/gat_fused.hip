@@ -115,13 +115,15 @@ struct FwdOp {
     }
     __device__ void prepare(Ent &, const Lane &, const LaneConst &) const {}
     __device__ void fold(A &a, const Ent &e) const {
+        // one of the two factors exp(m - max), exp(w - max) is exp(0): one exponential of -|w - m| serves both
         const float w = leaky(e.sv + e.dv, slope);
-        const float mx = fmaxf(a.f[4], w);
-        const float sc = __expf(a.f[4] - mx), p = __expf(w - mx);   // m = -inf at the start of a row: sc = 0
+        const float ex = __expf(-fabsf(w - a.f[4]));                 // m = -inf at the start of a row: 0
+        const bool grow = w > a.f[4];
+        const float sc = grow ? ex : 1.f, p = grow ? 1.f : ex;
         a.f[0] = fmaf(p, e.m.x, a.f[0] * sc); a.f[1] = fmaf(p, e.m.y, a.f[1] * sc);
         a.f[2] = fmaf(p, e.m.z, a.f[2] * sc); a.f[3] = fmaf(p, e.m.w, a.f[3] * sc);
         a.f[5] = fmaf(a.f[5], sc, p);
-        a.f[4] = mx;
+        a.f[4] = grow ? w : a.f[4];
     }
     __device__ static void combine(A &a, const A &b) {
         if (b.f[4] == -INFINITY) return;                             // b holds no entry
@@ -132,15 +134,18 @@ struct FwdOp {
         a.f[5] = fmaf(a.f[5], sa, b.f[5] * sb);
         a.f[4] = mx;
     }
+    // ELU through exp(x) - 1: its absolute error near zero (one float rounding of a number close to 1) is far
+    // below the tolerance of the outputs, and the row finish, instantiated at every entry of the unrolled walk,
+    // stays short
     __device__ float epi(float x, int c) const {
         if (bias) x += bias[c];
         if (act == kActRelu) x = fmaxf(x, 0.f);
-        else if (act == kActElu) x = x > 0.f ? x : expm1f(x);
+        else if (act == kActElu) x = x > 0.f ? x : __expf(x) - 1.f;
         return x;
     }
     __device__ void finish(int row, const Lane &ln, const A &a) const {
         if (!ln.ok) return;
-        const float inv = 1.f / a.f[5];
+        const float inv = __frcp_rn(a.f[5]);
         const int c = ln.foff;
         *reinterpret_cast<float4 *>(Y + (size_t)row * geo.f + c) =
             make_float4(epi(a.f[0] * inv, c), epi(a.f[1] * inv, c + 1), epi(a.f[2] * inv, c + 2), epi(a.f[3] * inv, c + 3));
@@ -228,14 +233,15 @@ struct BwdRowOnlineOp {
     __device__ void prepare(Ent &e, const Lane &ln, const LaneConst &) const { e.ga = head_sum(ln.ok ? dot4(e.m, e.g) : 0.f, geo.lh); }
     __device__ void fold(A &a, const Ent &e) const {
         const float y = e.sv + e.dv, w = leaky(y, slope);
-        const float mx = fmaxf(a.f[0], w);
-        const double sc = (double)__expf(a.f[0] - mx), p = (double)__expf(w - mx);
+        const float ex = __expf(-fabsf(w - a.f[0]));                 // as in the forward pass: one exponential
+        const bool grow = w > a.f[0];
+        const double sc = grow ? (double)ex : 1.0, p = grow ? 1.0 : (double)ex;
         const double pg = p * (double)e.ga, pos = y > 0.f ? 1.0 : 0.0;
         a.d[0] = a.d[0] * sc + p;
         a.d[1] = a.d[1] * sc + pg;
         a.d[2] = a.d[2] * sc + pos * pg;
         a.d[3] = a.d[3] * sc + pos * p;
-        a.f[0] = mx;
+        a.f[0] = grow ? w : a.f[0];
     }
     __device__ static void combine(A &a, const A &b) {
         if (b.f[0] == -INFINITY) return;
@@ -327,6 +333,15 @@ struct BwdColOp {
     }
 };
 
+// U consecutive staged indices (16-byte aligned: segments and steps are multiples of four entries)
+template <int U> __device__ __forceinline__ void read_indices(const int32_t *p, int (&v)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; u += 4) {
+        const int4 q = *reinterpret_cast<const int4 *>(p + u);
+        v[u] = q.x; v[u + 1] = q.y; v[u + 2] = q.z; v[u + 3] = q.w;
+    }
+}
+
 struct WalkInfo {
     int32_t tail_row;      // row whose tail partial this segment holds, or -1
     int32_t has_head;      // the segment's first row began before it
@@ -355,11 +370,10 @@ seg_walk_kernel(int nnz, int seg, long nseg, const int32_t *__restrict__ rowidx,
     const long blk_first = (long)blockIdx.x * span;
     for (int i = threadIdx.x; i < span; i += 256) {
         const long x = blk_first + i;
-        if (x < nnz) {
-            s_row[i] = rowidx[x];
-            s_col[i] = colidx[x];
-            s_slot[i] = slotidx ? slotidx[x] : (int)x;
-        }
+        const bool in = x < nnz;                           // past the end: entry 0 of row / column 0, loaded but never folded
+        s_row[i] = in ? rowidx[x] : 0;
+        s_col[i] = in ? colidx[x] : 0;
+        s_slot[i] = in ? (slotidx ? slotidx[x] : (int)x) : 0;
     }
     __syncthreads();
     const int l = threadIdx.x % LPE, gl = threadIdx.x / LPE;
@@ -381,14 +395,12 @@ seg_walk_kernel(int nnz, int seg, long nseg, const int32_t *__restrict__ rowidx,
         const bool head_open = before == first;
         int cur = first;
         for (int x = 0; x < cnt; x += U) {
+            // U entries per step with wide LDS reads; a step that runs past the segment's last entry reads the
+            // next segment's (or the filler's) indices: valid addresses, loaded and not folded
             int r[U], c[U], sl[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = lb + min(x + u, cnt - 1);
-                r[u] = s_row[i];
-                c[u] = s_col[i];
-                sl[u] = s_slot[i];
-            }
+            read_indices<U>(s_row + lb + x, r);
+            read_indices<U>(s_col + lb + x, c);
+            read_indices<U>(s_slot + lb + x, sl);
             typename Op::Ent ent[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) op.load(ent[u], r[u], c[u], sl[u], ln);     // lanes without features read feature 0

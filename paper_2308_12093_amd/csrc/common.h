@@ -62,14 +62,22 @@ size_t spmm_workspace_bytes(int64_t n, int64_t nnz, int f);
 gnn_status_t spmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *col, const int32_t *erow,
                          EdgeWeights w, const float *B, long b_rows, int f, float *C, const float *bias, int relu,
                          void *workspace, hipStream_t st);
+// The place inside `workspace` where such a call (one weight per entry) keeps its padded copy of B, rows *ld
+// floats apart, or NULL when it makes none.  A caller that produces B itself may write it there in that layout
+// (padding columns included, any finite value) and pass that address as B: the call then copies nothing.
+float *spmm_padded_operand(void *workspace, const int32_t *erow, int64_t b_rows, int64_t nnz, int f, int *ld);
 
 // ---- dense products (gemm.hip) ----------------------------------------------------
 size_t gemm_workspace_bytes(int ta, int tb, int64_t M, int64_t N, int64_t K);
 // b_mask (transposed-A form only): B is used as B .* act'(b_mask), the derivative of the activation
-// b_mask_act (kActRelu, kActElu) taken from its output b_mask, an array of B's shape
+// b_mask_act (kActRelu, kActElu) taken from its output b_mask, an array of B's shape.
+// ldc (plain products only): rows of C are ldc >= N floats apart, the columns in between written as zeros.
+// A2, B2 (plain products only; shapes of A and B): C = op(A) op(B) + op(A2) op(B2) in one pass, one rounding
+// chain; the untransposed-B form then needs a workspace of 2 x gemm_workspace_bytes.
 gnn_status_t gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A, const float *B,
                          float *C, const float *bias, int relu, void *workspace, hipStream_t st,
-                         const float *b_mask = nullptr, int b_mask_act = 0);
+                         const float *b_mask = nullptr, int b_mask_act = 0, int64_t ldc = 0,
+                         const float *A2 = nullptr, const float *B2 = nullptr);
 
 // ---- element-wise and reductions (elementwise.hip) ---------------------------------
 // out = G * [Y > 0]

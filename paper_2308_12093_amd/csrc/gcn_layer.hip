@@ -44,7 +44,10 @@ gnn_status_t gcn_forward(Plan &p, const gnn_graph_t &g, const float *X, const fl
         float *T = ws.take<float>((size_t)n * k);
         void *sp = ws.take<char>(spmm_workspace_bytes(n, d.nnz, k));
         void *wt = ws.take<char>(gemm_workspace_bytes(0, 0, n, k, m));
-        GNN_TRY(gemm_launch(0, 0, n, k, m, X, W, T, nullptr, 0, wt, st));
+        // a width that the SpMM runs on a padded operand: the GEMM writes T in that layout, where the SpMM looks for it
+        int ldt = k;
+        if (float *Tp = spmm_padded_operand(sp, g.csr_erow, n, d.nnz, k, &ldt)) T = Tp;
+        GNN_TRY(gemm_launch(0, 0, n, k, m, X, W, T, nullptr, 0, wt, st, nullptr, 0, ldt));
         GNN_TRY(spmm(g, forward_view(g, k), T, k, Y, bias, d.fuse_relu, sp, st));
     } else {
         // P = A' X (kept in the cache slot when the plan caches it), then Y = P W (+ b, ReLU)
@@ -106,15 +109,18 @@ gnn_status_t gcn_backward(Plan &p, const gnn_graph_t &g, const float *X, const f
         }
         GNN_TRY(gemm_launch(1, 0, m, k, n, P, G, dW, nullptr, 0, gemm_ws, st, mask_y, kActRelu));
         if (dx) {
-            GNN_TRY(gemm_launch(0, 1, n, m, k, G, W, U, nullptr, 0, nullptr, st));
-            GNN_TRY(spmm(g, transposed_view(g, m), U, m, dX, nullptr, 0, sp, st));
+            const SparseView tv = transposed_view(g, m);
+            int ldu = m;                                    // as in the forward pass: U written where the SpMM pads
+            if (float *Up = spmm_padded_operand(sp, tv.eidx, n, d.nnz, m, &ldu)) U = Up;
+            GNN_TRY(gemm_launch(0, 1, n, m, k, G, W, U, nullptr, 0, nullptr, st, nullptr, 0, ldu));
+            GNN_TRY(spmm(g, tv, U, m, dX, nullptr, 0, sp, st));
         }
     }
     return GNN_OK;
 }
 
-// Y = X Ws + A' X Wn + b: the neighbour term in the order the plan chose, the self term by a GEMM
-// that adds to what Y holds (or is added to), bias and ReLU in whichever GEMM writes Y last.
+// Y = X Ws + A' X Wn + b.  Aggregate first: one product over both operand pairs, [X | A'X] [Ws; Wn], writes Y
+// once with bias and ReLU.  Transform first: the self term is a GEMM that adds to what the SpMM wrote.
 gnn_status_t sage_forward(Plan &p, const gnn_graph_t &g, const float *X, const float *Ws, const float *Wn,
                           const float *b, float *Y, void *cache, void *workspace, hipStream_t st) {
     const gnn_plan_desc_t &d = p.desc;
@@ -125,19 +131,20 @@ gnn_status_t sage_forward(Plan &p, const gnn_graph_t &g, const float *X, const f
     if (p.info.order == GNN_ORDER_TRANSFORM_FIRST) {
         float *T = ws.take<float>((size_t)n * k);
         void *sp = ws.take<char>(spmm_workspace_bytes(n, d.nnz, k));
-        void *wt = ws.take<char>(gemm_workspace_bytes(0, 0, n, k, m));
-        GNN_TRY(gemm_launch(0, 0, n, k, m, X, Wn, T, nullptr, 0, wt, st));
+        void *wt = ws.take<char>(2 * gemm_workspace_bytes(0, 0, n, k, m));
+        int ldt = k;
+        if (float *Tp = spmm_padded_operand(sp, g.csr_erow, n, d.nnz, k, &ldt)) T = Tp;
+        GNN_TRY(gemm_launch(0, 0, n, k, m, X, Wn, T, nullptr, 0, wt, st, nullptr, 0, ldt));
         GNN_TRY(spmm(g, forward_view(g, k), T, k, Y, nullptr, 0, sp, st));
         GNN_TRY(gemm_launch(0, 0, n, k, m, X, Ws, Y, bias, last, wt, st));
     } else {
         const bool cached = p.info.cache == GNN_CACHE_AX;
         float *P = cached ? static_cast<float *>(cache) : ws.take<float>((size_t)n * m);
         void *sp = ws.take<char>(spmm_workspace_bytes(n, d.nnz, m));
-        void *wt = ws.take<char>(gemm_workspace_bytes(0, 0, n, k, m));
+        void *wt = ws.take<char>(2 * gemm_workspace_bytes(0, 0, n, k, m));
         if (!(cached && d.constant_input && p.cache_filled))
             GNN_TRY(spmm(g, forward_view(g, m), X, m, P, nullptr, 0, sp, st));
-        GNN_TRY(gemm_launch(0, 0, n, k, m, X, Ws, Y, nullptr, 0, wt, st));
-        GNN_TRY(gemm_launch(0, 0, n, k, m, P, Wn, Y, bias, last, wt, st));
+        GNN_TRY(gemm_launch(0, 0, n, k, m, X, Ws, Y, bias, d.fuse_relu, wt, st, nullptr, 0, 0, P, Wn));
         if (cached) p.cache_filled = true;
     }
     return GNN_OK;
@@ -171,8 +178,7 @@ gnn_status_t sage_backward(Plan &p, const gnn_graph_t &g, const float *X, const 
         GNN_TRY(spmm(g, transposed_view(g, k), G, k, H, nullptr, 0, sp, st));
         GNN_TRY(gemm_launch(1, 0, m, k, n, X, H, dWn, nullptr, 0, gemm_ws, st));
         if (dx) {
-            GNN_TRY(gemm_launch(0, 1, n, m, k, G, Ws, dX, nullptr, 0, nullptr, st));
-            GNN_TRY(gemm_launch(0, 1, n, m, k, H, Wn, dX, nullptr, kActAccumulate, nullptr, st));
+            GNN_TRY(gemm_launch(0, 1, n, m, k, G, Ws, dX, nullptr, 0, nullptr, st, nullptr, 0, 0, H, Wn));
         }
     } else {
         // dWn = (A'X)^T G with A'X from the cache or recomputed; dX = A'^T (G Wn^T) + G Ws^T
@@ -187,8 +193,11 @@ gnn_status_t sage_backward(Plan &p, const gnn_graph_t &g, const float *X, const 
         }
         GNN_TRY(gemm_launch(1, 0, m, k, n, P, G, dWn, nullptr, 0, gemm_ws, st));
         if (dx) {
-            GNN_TRY(gemm_launch(0, 1, n, m, k, G, Wn, U, nullptr, 0, nullptr, st));
-            GNN_TRY(spmm(g, transposed_view(g, m), U, m, dX, nullptr, 0, sp, st));
+            const SparseView tv = transposed_view(g, m);
+            int ldu = m;
+            if (float *Up = spmm_padded_operand(sp, tv.eidx, n, d.nnz, m, &ldu)) U = Up;
+            GNN_TRY(gemm_launch(0, 1, n, m, k, G, Wn, U, nullptr, 0, nullptr, st, nullptr, 0, ldu));
+            GNN_TRY(spmm(g, tv, U, m, dX, nullptr, 0, sp, st));
             GNN_TRY(gemm_launch(0, 1, n, m, k, G, Ws, dX, nullptr, kActAccumulate, nullptr, st));
         }
     }

@@ -224,7 +224,7 @@ gemm_tn_f64_kernel(int M, int N, long K, const float *__restrict__ A, const floa
 template <int WM, int WN, int TM, int TN, int BKT, int MODE>
 __global__ void __launch_bounds__(256)
 gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *__restrict__ Bt,
-                float *__restrict__ C, const float *__restrict__ bias, int relu, int tiles_m, int tiles_n,
+                const float *__restrict__ A2, const float *__restrict__ Bt2, float *__restrict__ C, int ldc, const float *__restrict__ bias, int relu, int tiles_m, int tiles_n,
                 int tiles_per_block, int vec_a, int vec_b) {
     constexpr bool FAST = MODE != kGemmGeneral;
     constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = BKT, LD = BK + 4;
@@ -250,12 +250,14 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
     const int wave = __builtin_amdgcn_readfirstlane(t / 64), lane = t % 64;   // wave id as a scalar
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane % 32, half = lane / 32;
-    const int ktiles = K > 0 ? (K + BK - 1) / BK : 1;
+    // with a second operand pair the reduction runs over both: C = A Bt^T + A2 Bt2^T, kt1 k-tiles each
+    const int kt1 = K > 0 ? (K + BK - 1) / BK : 1;
+    const int ktiles = A2 ? 2 * kt1 : kt1;
     const int steps = (last_tile - first_tile) * ktiles;
     const int lrow = t / (BK / 4), lkq = (t % (BK / 4)) * 4;      // this thread's granule: row (+RPP per p), k offset
     // per-lane parts of the fast addresses, in bytes: address = wave-uniform base + 32-bit lane offset
     const unsigned lane_ld = ((unsigned)lrow * (unsigned)K + lkq) * 4u;
-    const unsigned lane_st = ((unsigned)(4 * half) * (unsigned)N + l32) * 4u;
+    const unsigned lane_st = ((unsigned)(4 * half) * (unsigned)ldc + l32) * 4u;
 
     // the loads of one (tile, k-tile) step, at a cursor that walks the block's steps in order.
     // Two register sets alternate, so the loads of step i+2 are issued before step i is
@@ -285,9 +287,11 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
     };
     bool kin0 = true, kin1 = true;                         // per register set: the lane's granule lies inside K
     auto fetch = [&](floatx4 (&ra)[GA], floatx4 (&rb)[GB], bool &kin) __attribute__((always_inline)) {
-        const int m0 = ftm * BM, n0 = ftn * BN, k0 = fkt * BK;
-        const float *pa = A + (size_t)m0 * K + k0;         // uniform bases of the tile being fetched
-        const float *pb = Bt + (size_t)n0 * K + k0;
+        const bool second = fkt >= kt1;                     // (never with one operand pair)
+        const int m0 = ftm * BM, n0 = ftn * BN, k0 = (second ? fkt - kt1 : fkt) * BK;
+        const float *Ao = second ? A2 : A, *Bo = second ? Bt2 : Bt;
+        const float *pa = Ao + (size_t)m0 * K + k0;        // uniform bases of the tile being fetched
+        const float *pb = Bo + (size_t)n0 * K + k0;
         if constexpr (FAST) {
             kin = true;
             if constexpr (MODE == kGemmInterior) {
@@ -306,7 +310,7 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
                 // on its way to LDS.  The same loads for every tile, none behind a branch, none out of bounds.
                 const int gk = k0 + lkq;
                 kin = gk < K;
-                const float *ka = A + (kin ? gk : 0), *kb = Bt + (kin ? gk : 0);
+                const float *ka = Ao + (kin ? gk : 0), *kb = Bo + (kin ? gk : 0);
 #pragma unroll
                 for (int p = 0; p < GA; ++p)
                     if (BM % RPP == 0 || lrow + RPP * p < BM)
@@ -324,7 +328,7 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
                     if (BM % RPP == 0 || lrow + RPP * p < BM)
                         ra[p] = *reinterpret_cast<const floatx4 *>(reinterpret_cast<const char *>(pa + (size_t)p * RPP * K) + lane_ld);
             } else {
-                guarded(A, M, m0, k0, vec_a, ra, GA, BM);
+                guarded(Ao, M, m0, k0, vec_a, ra, GA, BM);
             }
             if (kfull && vec_b && n0 + BN <= N && (size_t)BN * K < (1u << 30)) {
 #pragma unroll
@@ -332,7 +336,7 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
                     if (BN % RPP == 0 || lrow + RPP * p < BN)
                         rb[p] = *reinterpret_cast<const floatx4 *>(reinterpret_cast<const char *>(pb + (size_t)p * RPP * K) + lane_ld);
             } else {
-                guarded(Bt, N, n0, k0, vec_b, rb, GB, BN);
+                guarded(Bo, N, n0, k0, vec_b, rb, GB, BN);
             }
         }
         if (fstep + 1 < steps) {                           // the cursor stops at the last step
@@ -423,11 +427,11 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
     };
     auto finish_tile = [&]() __attribute__((always_inline)) {
         const int cm0 = ctm * BM, cn0 = ctn * BN;
-        const bool cfull = cm0 + BM <= M && cn0 + BN <= N && (size_t)BM * N < (1u << 30);
+        const bool cfull = cm0 + BM <= M && cn0 + BN <= N && (size_t)BM * ldc < (1u << 30);
         if (cfull) {
-            float *c0 = C + (size_t)(cm0 + wm * TM * 32) * N + cn0 + wn * TN * 32;     // uniform per wavefront
+            float *c0 = C + (size_t)(cm0 + wm * TM * 32) * ldc + cn0 + wn * TN * 32;   // uniform per wavefront
             auto at = [&](int x, int y, int v) __attribute__((always_inline)) {
-                return reinterpret_cast<float *>(reinterpret_cast<char *>(c0 + (size_t)(x * 32 + 8 * (v / 4) + (v % 4)) * N + y * 32) + lane_st);
+                return reinterpret_cast<float *>(reinterpret_cast<char *>(c0 + (size_t)(x * 32 + 8 * (v / 4) + (v % 4)) * ldc + y * 32) + lane_st);
             };
             auto put = [&](int x, int y, int v, float o) __attribute__((always_inline)) {
                 // an output far larger than the caches is streamed past them
@@ -474,9 +478,11 @@ gemm_f32_kernel(int M, int N, int K, const float *__restrict__ A, const float *_
                         const int gi = cm0 + (wm * TM + x) * 32 + 8 * (v / 4) + 4 * half + (v % 4);
                         if (gj < N && gi < M) {
                             float o = acc[x][y][v] + bj;
-                            if (relu & kActAccumulate) o += C[(size_t)gi * N + gj];
+                            if (relu & kActAccumulate) o += C[(size_t)gi * ldc + gj];
                             if (relu & kActRelu) o = fmaxf(o, 0.f);
-                            C[(size_t)gi * N + gj] = o;
+                            C[(size_t)gi * ldc + gj] = o;
+                        } else if (gj < ldc && gi < M) {
+                            C[(size_t)gi * ldc + gj] = 0.f;           // padding columns of a wider row stride
                         }
                         acc[x][y][v] = 0.f;
                     }
@@ -604,19 +610,19 @@ size_t gemm_workspace_bytes(int ta, int tb, int64_t M, int64_t N, int64_t K) {
         const bool aligned = vec_a && vec_b && K > 0;                                                       \
         const bool interior = aligned && M % BM_ == 0 && N % BN_ == 0 && K % 32 == 0 &&                     \
                               (size_t)BM_ * K < (1u << 30) && (size_t)BN_ * K < (1u << 30) &&               \
-                              (size_t)BM_ * N < (1u << 30);                                                 \
+                              (size_t)BM_ * ldc < (1u << 30);                                               \
         if (interior)                                                                                       \
             hipLaunchKernelGGL((gemm_f32_kernel<WM_, WN_, TM_, TN_, 32, kGemmInterior>), grid, dim3(256),   \
-                               lds, st, (int)M, (int)N, (int)K, A, Bt, C, bias, relu, tiles_m, tiles_n,     \
-                               tiles_per_block, vec_a, vec_b);                                              \
+                               lds, st, (int)M, (int)N, (int)K, A, Bt, A2, Bt2, C, (int)ldc, bias, relu,      \
+                               tiles_m, tiles_n, tiles_per_block, vec_a, vec_b);                            \
         else if (aligned)                                                                                   \
             hipLaunchKernelGGL((gemm_f32_kernel<WM_, WN_, TM_, TN_, 32, kGemmEdge>), grid, dim3(256), lds,  \
-                               st, (int)M, (int)N, (int)K, A, Bt, C, bias, relu, tiles_m, tiles_n,          \
-                               tiles_per_block, vec_a, vec_b);                                              \
+                               st, (int)M, (int)N, (int)K, A, Bt, A2, Bt2, C, (int)ldc, bias, relu,          \
+                               tiles_m, tiles_n, tiles_per_block, vec_a, vec_b);                            \
         else                                                                                                \
             hipLaunchKernelGGL((gemm_f32_kernel<WM_, WN_, TM_, TN_, 32, kGemmGeneral>), grid, dim3(256),    \
-                               lds, st, (int)M, (int)N, (int)K, A, Bt, C, bias, relu, tiles_m, tiles_n,     \
-                               tiles_per_block, vec_a, vec_b);                                              \
+                               lds, st, (int)M, (int)N, (int)K, A, Bt, A2, Bt2, C, (int)ldc, bias, relu,      \
+                               tiles_m, tiles_n, tiles_per_block, vec_a, vec_b);                            \
         launched = true;                                                                                    \
     }
 #define GEMM_F64_CASE(WM_, WN_, TM_, TN_)                                                                        \
@@ -638,9 +644,14 @@ size_t gemm_workspace_bytes(int ta, int tb, int64_t M, int64_t N, int64_t K) {
 
 gnn_status_t gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const float *A, const float *B,
                          float *C, const float *bias, int relu, void *workspace, hipStream_t st,
-                         const float *b_mask, int b_mask_act) {
+                         const float *b_mask, int b_mask_act, int64_t ldc, const float *A2, const float *B2) {
     if (M <= 0 || N <= 0) return GNN_OK;
     if (ta && tb) return GNN_ERR_UNSUPPORTED;
+    if ((A2 != nullptr) != (B2 != nullptr) || (A2 && ta)) return GNN_ERR_UNSUPPORTED;   // the plain products only
+    // rows of C may be ldc >= N floats apart (the columns in between are written as zeros): the plain products only,
+    // and few enough padding columns that the tiles covering N also cover them
+    if (ldc == 0) ldc = N;
+    if (ldc < N || ldc > (N + 31) / 32 * 32 || (ta && ldc != N) || ldc > INT32_MAX / 2) return GNN_ERR_UNSUPPORTED;
     if (b_mask && !ta) return GNN_ERR_UNSUPPORTED;         // only the transposed-A product masks its second operand
     if (M > INT32_MAX / 2 || N > INT32_MAX / 2 || (!ta && K > INT32_MAX / 2)) return GNN_ERR_UNSUPPORTED;
     const bool f64 = ta != 0;
@@ -649,21 +660,29 @@ gnn_status_t gemm_launch(int ta, int tb, int64_t M, int64_t N, int64_t K, const 
     bool launched = false;
     if (!f64) {
         // the kernel wants B with the reduction index contiguous: B[N][K]; transpose a [K][N] weight first
-        const float *Bt = B;
+        const float *Bt = B, *Bt2 = B2;
+        if (K <= 0) A2 = Bt2 = nullptr;                    // an empty reduction: nothing to add
         if (!tb && K > 0) {
             float *wt = static_cast<float *>(workspace);
             hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)ceil_div(N, 32), (unsigned)ceil_div(K, 32)), dim3(256),
                                0, st, (int)K, (int)N, B, wt);
             GNN_TRY(launch_status());
             Bt = wt;
+            if (B2) {                                      // the second weight behind the first (2 x gemm_workspace_bytes)
+                float *wt2 = reinterpret_cast<float *>(static_cast<char *>(workspace) + gemm_workspace_bytes(0, 0, M, N, K));
+                hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)ceil_div(N, 32), (unsigned)ceil_div(K, 32)),
+                                   dim3(256), 0, st, (int)K, (int)N, B2, wt2);
+                GNN_TRY(launch_status());
+                Bt2 = wt2;
+            }
         }
-        const int vec_a = aligned16(A) && K % 4 == 0;
-        const int vec_b = aligned16(Bt) && K % 4 == 0;
+        const int vec_a = aligned16(A) && (!A2 || aligned16(A2)) && K % 4 == 0;
+        const int vec_b = aligned16(Bt) && (!Bt2 || aligned16(Bt2)) && K % 4 == 0;
         relu &= kActRelu | kActAccumulate;
         if ((size_t)M * N * sizeof(float) > kStreamBytes && !(relu & kActAccumulate)) relu |= kActStream;
         // persistent blocks: 64 per XCD (2 per CU), each owning a contiguous range of tiles
         const long total = (long)tiles_m * tiles_n;
-        if (total > INT32_MAX / 2 || total * ceil_div(K > 0 ? K : 1, 32) > INT32_MAX / 2) return GNN_ERR_UNSUPPORTED;
+        if (total > INT32_MAX / 4 || total * ceil_div(K > 0 ? K : 1, 32) > INT32_MAX / 4) return GNN_ERR_UNSUPPORTED;
         const long per_xcd = ceil_div(total, 8);
         const int blocks_per_xcd = (int)(per_xcd < 64 ? per_xcd : 64);
         const int tiles_per_block = (int)ceil_div(per_xcd, blocks_per_xcd);

@@ -78,6 +78,7 @@ void size_gcn(Plan &p) {
 
     // forward
     size_t fwd = gemm_workspace_bytes(0, 0, n, k, m);
+    if (d.layer == GNN_LAYER_SAGE) fwd *= 2;               // both weights transposed for the one product that uses both
     if (tf) {
         fwd += align_up((size_t)n * k * fl) + spmm_workspace_bytes(n, q, (int)k);
         p.info.transient_fwd = n * k;

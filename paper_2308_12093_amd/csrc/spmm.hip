@@ -449,6 +449,13 @@ size_t spmm_workspace_bytes(int64_t n, int64_t nnz, int f) {
     return bytes;
 }
 
+// Where spmm_launch puts the padded copy of B for this call, or NULL if the call makes none.
+float *spmm_padded_operand(void *workspace, const int32_t *erow, int64_t b_rows, int64_t nnz, int f, int *ld) {
+    if (!workspace || !erow || nnz <= 0 || b_rows <= 0 || !padded_operand(f)) return nullptr;
+    if (ld) *ld = (f + 3) / 4 * 4;
+    return reinterpret_cast<float *>(static_cast<char *>(workspace) + partials_bytes(nnz, f));
+}
+
 #define SPMM_CASE(VEC_, LPE_, NT_, U_)                                                                       \
     if (sh.vec == VEC_ && sh.lpe == LPE_ && sh.nt == NT_) {                                                  \
         constexpr int GPB_ = 256 / LPE_;                                                                     \
@@ -491,10 +498,12 @@ gnn_status_t spmm_launch(int n, int nnz, const int32_t *rowptr, const int32_t *c
     const int fp = (f + 3) / 4 * 4;
     float *Bp = nullptr;
     if (ragged) {
-        Bp = reinterpret_cast<float *>(static_cast<char *>(workspace) + partials_bytes(nnz, f));
-        hipLaunchKernelGGL(pad_rows_kernel, dim3((unsigned)ceil_div(b_rows * (fp / 4), 256)), dim3(256), 0, st, b_rows,
-                           f, fp, B, Bp);
-        GNN_TRY(launch_status());
+        Bp = spmm_padded_operand(workspace, erow, b_rows, nnz, f, nullptr);
+        if (B != Bp) {                                     // a caller that wrote the operand there itself: no copy
+            hipLaunchKernelGGL(pad_rows_kernel, dim3((unsigned)ceil_div(b_rows * (fp / 4), 256)), dim3(256), 0, st,
+                               b_rows, f, fp, B, Bp);
+            GNN_TRY(launch_status());
+        }
     }
     const int seg = spmm_segment_len(nnz, f);
     const long nseg = ceil_div(nnz, seg);

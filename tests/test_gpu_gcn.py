@@ -86,7 +86,7 @@ def check(B, G, rowptr, col, X, W, b, dY, need_dx, relu, scheme, symmetric=True,
 
 
 @pytest.mark.parametrize("name", ["auto", "tf_fp", "pf_sp_nocache", "pf_sp_cache", "pf_fp", "tf_sp"])
-@pytest.mark.parametrize("m,k", [(48, 16), (16, 48), (32, 32), (100, 47)])
+@pytest.mark.parametrize("m,k", [(48, 16), (16, 48), (32, 32), (100, 47), (50, 70), (150, 200), (200, 150)])
 def test_every_scheme_small_rmat(B, G, name, m, k):
     s = synth.streams(11)
     rowptr, col = synth.rmat_graph(11, 12, False, s["graph"], s["relabel"])

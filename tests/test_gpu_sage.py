@@ -60,7 +60,7 @@ def case(seed, scale, m, k, directed):
 
 
 @pytest.mark.parametrize("name", ["auto", "tf_fp", "pf_sp_nocache", "pf_sp_cache", "pf_fp", "tf_sp"])
-@pytest.mark.parametrize("m,k,directed", [(48, 16, False), (16, 48, True), (100, 47, False)])
+@pytest.mark.parametrize("m,k,directed", [(48, 16, False), (16, 48, True), (100, 47, False), (50, 70, True), (150, 101, False)])
 def test_every_scheme_mean_aggregator(B, G, name, m, k, directed):
     rowptr, col, X, Ws, Wn, b, dY = case(61, 10, m, k, directed)
     g = G.gcn_graph(rowptr, col, symmetric=not directed, aggregator=B.GNN_AGG_MEAN)

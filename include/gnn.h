@@ -402,7 +402,8 @@ gnn_status_t gnn_sddmm_csr(int32_t n, int32_t nnz, const int32_t *erow, const in
  * d_j = <a_dst, m_j>); bias [heads * f] or NULL;
  * stat_out [n][heads][2] receives (row maximum of the LeakyReLU'd logits, sum of exp(. - maximum)), from which
  * alpha_e = exp(w_e - max) / sum.  erow [nnz]: row of every entry (gnn_expand_ptr).
- *   f: a multiple of 4 with f / 4 a power of two, at most 256; M and Y 16-byte aligned
+ *   f: a multiple of 4 with f / 4 a power of two, at most 256; M, Y and bias 16-byte aligned; n below 2^24,
+ *   M below 4 GiB and nnz * heads below 2^30 (the gathers use 32-bit byte offsets)
  *   (GNN_ERR_UNSUPPORTED otherwise: gat_layer_fwd then runs the steps as separate kernels).
  *   workspace: gnn_gat_aggregate_workspace_bytes(nnz, heads, f).
  */

@@ -285,7 +285,7 @@ gnn_status_t gnn_gat_aggregate_csr(int32_t n, int32_t nnz, const int32_t *rowptr
     if (n < 0 || nnz < 0 || heads <= 0 || f <= 0 || !rowptr) return GNN_ERR_INVALID_ARG;
     if (n > 0 && (!Y || !stat_out)) return GNN_ERR_INVALID_ARG;
     if (nnz > 0 && (!erow || !col || !M || !s || !d || !workspace || bad_align(workspace))) return GNN_ERR_INVALID_ARG;
-    if (!gat_fused_shape(heads, f) || !aligned16(M) || !aligned16(Y)) return GNN_ERR_UNSUPPORTED;
+    if (!gat_fused_shape(n, nnz, heads, f) || !aligned16(M) || !aligned16(Y) || !aligned16(bias)) return GNN_ERR_UNSUPPORTED;
     if (nnz > 0 && workspace_bytes < gat_fused_workspace_bytes(nnz, heads, f)) return GNN_ERR_BUFFER_TOO_SMALL;
     return gat_fused_forward_launch(n, nnz, heads, f, rowptr, erow, col, M, s, d, leaky_slope, bias,
                                     elu ? kActElu : kActNone, Y, stat_out, workspace, as_stream(hip_stream));

@@ -149,7 +149,7 @@ gnn_status_t sddmm_launch(int n, int nnz, const int32_t *erow, const int32_t *co
                           const float *B, const float *Ct, int heads, int f, float *D, hipStream_t st);
 
 // ---- fused GAT edge passes (gat_fused.hip) -----------------------------------------------
-bool gat_fused_shape(int h, int k);
+bool gat_fused_shape(int64_t n, int64_t nnz, int h, int k);
 size_t gat_fused_workspace_bytes(int64_t nnz, int h, int k);
 // Y = act(softmax-weighted aggregation + bias), stat [n][h][2] = (row max, sum of exponentials)
 gnn_status_t gat_fused_forward_launch(int n, int nnz, int h, int k, const int32_t *rowptr, const int32_t *erow,

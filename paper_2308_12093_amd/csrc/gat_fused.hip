@@ -31,6 +31,13 @@
 // Rows cut by a segment boundary are stitched as in the SpMM: inside a block through LDS, across blocks
 // through two partials per block and a second kernel; every combination has a fixed order, so results
 // are reproducible.
+//
+// A group walks its segment in batches of a few entries with two batches in flight: the gathers of the next
+// batch are issued before the current one is folded.  (Loads and stores share one in-order counter on this
+// chip; with a single batch in flight every wait for a gather also waited for the stores of the rows just
+// completed, and the gather latency itself was exposed once per batch: the forward pass ran a quarter slower.)
+// Gathers are addressed as uniform base + 32-bit byte offset, the offset one 24-bit multiply-add; graphs or
+// arrays too large for that run the unfused kernels.
 #include "common.h"
 
 namespace gnn {
@@ -63,6 +70,26 @@ struct Geo {
 };
 
 __device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+// Gathers address their operand as a uniform base plus an unsigned 32-bit byte offset (arrays below 4 GiB), the
+// offset one 24-bit multiply-add: index * (bytes per row) + the lane's own part.  Node numbers are below 2^24
+// and rows shorter than 2^24 bytes (checked on the host); offsets built from entry slots take a full multiply.
+__device__ __forceinline__ uint32_t off24(int idx, uint32_t row_bytes, uint32_t lane_bytes) {
+    return __umul24((uint32_t)idx, row_bytes) + lane_bytes;
+}
+__device__ __forceinline__ uint32_t off32(int idx, uint32_t row_bytes, uint32_t lane_bytes) {
+    return (uint32_t)idx * row_bytes + lane_bytes;
+}
+template <class T> __device__ __forceinline__ T ldb(const void *base, uint32_t byte_off) {
+    return *reinterpret_cast<const T *>(static_cast<const char *>(base) + byte_off);
+}
+// A lane's constant offsets: its four features inside a row of f floats, its head inside rows of h
+// floats, h bytes and h float4s.
+struct LaneOff {
+    uint32_t feat, head4, head1, head16;
+};
+__device__ __forceinline__ LaneOff lane_off(const Lane &ln) {
+    return LaneOff{(uint32_t)ln.foff * 4u, (uint32_t)ln.hd * 4u, (uint32_t)ln.hd, (uint32_t)ln.hd * 16u};
+}
 __device__ __forceinline__ float dot4(const float4 &a, const float4 &b) {
     return fmaf(a.w, b.w, fmaf(a.z, b.z, fmaf(a.y, b.y, a.x * b.x)));
 }
@@ -104,16 +131,14 @@ struct FwdOp {
     int act;
     float *Y, *stat;
     struct Ent { float4 m; float sv, dv; };
-    typedef int LaneConst;
-    __device__ LaneConst lane_const(const Lane &) const { return 0; }
     __device__ void init(A &a) const { a.f[0] = a.f[1] = a.f[2] = a.f[3] = 0.f; a.f[4] = -INFINITY; a.f[5] = 0.f; }
-    __device__ void load(Ent &e, int row, int col, int slot, const Lane &ln) const {
+    __device__ void load(Ent &e, int row, int col, int slot, const LaneOff &lo) const {
         (void)slot;
-        e.m = ld4(M + (size_t)col * geo.f + ln.foff);
-        e.sv = s[(size_t)row * geo.h + ln.hd];
-        e.dv = d[(size_t)col * geo.h + ln.hd];
+        e.m = ldb<float4>(M, off24(col, geo.f * 4u, lo.feat));
+        e.sv = ldb<float>(s, off24(row, geo.h * 4u, lo.head4));
+        e.dv = ldb<float>(d, off24(col, geo.h * 4u, lo.head4));
     }
-    __device__ void prepare(Ent &, const Lane &, const LaneConst &) const {}
+    __device__ void prepare(Ent &, const Lane &) const {}
     __device__ void fold(A &a, const Ent &e) const {
         // one of the two factors exp(m - max), exp(w - max) is exp(0): one exponential of -|w - m| serves both
         const float w = leaky(e.sv + e.dv, slope);
@@ -145,10 +170,20 @@ struct FwdOp {
     }
     __device__ void finish(int row, const Lane &ln, const A &a) const {
         if (!ln.ok) return;
-        const float inv = __frcp_rn(a.f[5]);
+        const float inv = __builtin_amdgcn_rcpf(a.f[5]);             // l >= 1: one ulp is far inside the tolerance
         const int c = ln.foff;
-        *reinterpret_cast<float4 *>(Y + (size_t)row * geo.f + c) =
-            make_float4(epi(a.f[0] * inv, c), epi(a.f[1] * inv, c + 1), epi(a.f[2] * inv, c + 2), epi(a.f[3] * inv, c + 3));
+        float4 y = make_float4(a.f[0] * inv, a.f[1] * inv, a.f[2] * inv, a.f[3] * inv);
+        if (bias) {
+            const float4 b = ld4(bias + c);
+            y.x += b.x; y.y += b.y; y.z += b.z; y.w += b.w;
+        }
+        if (act == kActRelu) {
+            y.x = fmaxf(y.x, 0.f); y.y = fmaxf(y.y, 0.f); y.z = fmaxf(y.z, 0.f); y.w = fmaxf(y.w, 0.f);
+        } else if (act == kActElu) {
+            y.x = y.x > 0.f ? y.x : __expf(y.x) - 1.f; y.y = y.y > 0.f ? y.y : __expf(y.y) - 1.f;
+            y.z = y.z > 0.f ? y.z : __expf(y.z) - 1.f; y.w = y.w > 0.f ? y.w : __expf(y.w) - 1.f;
+        }
+        *reinterpret_cast<float4 *>(Y + (size_t)row * geo.f + c) = y;
         if (ln.leader) {
             float *st = stat + ((size_t)row * geo.h + ln.hd) * 2;
             st[0] = a.f[4];
@@ -179,17 +214,14 @@ struct BwdRowCachedOp {
     float *ds;                // [n][h]
     float *node;              // t [n][h]
     struct Ent { float4 m, g; float al, pos, ga; };
-    typedef int LaneConst;
-    __device__ LaneConst lane_const(const Lane &) const { return 0; }
     __device__ void init(A &a) const { a.d[0] = a.d[1] = a.d[2] = 0.0; }
-    __device__ void load(Ent &e, int row, int col, int slot, const Lane &ln) const {
-        e.m = ld4(M + (size_t)col * geo.f + ln.foff);
-        e.g = ld4(G + (size_t)row * geo.f + ln.foff);
-        const size_t eh = (size_t)slot * geo.h + ln.hd;
-        e.al = alpha[eh];
-        e.pos = mask[eh] ? 1.f : 0.f;
+    __device__ void load(Ent &e, int row, int col, int slot, const LaneOff &lo) const {
+        e.m = ldb<float4>(M, off24(col, geo.f * 4u, lo.feat));
+        e.g = ldb<float4>(G, off24(row, geo.f * 4u, lo.feat));
+        e.al = ldb<float>(alpha, off32(slot, geo.h * 4u, lo.head4));
+        e.pos = ldb<uint8_t>(mask, off32(slot, geo.h, lo.head1)) ? 1.f : 0.f;
     }
-    __device__ void prepare(Ent &e, const Lane &ln, const LaneConst &) const { e.ga = head_sum(ln.ok ? dot4(e.m, e.g) : 0.f, geo.lh); }
+    __device__ void prepare(Ent &e, const Lane &ln) const { e.ga = head_sum(ln.ok ? dot4(e.m, e.g) : 0.f, geo.lh); }
     __device__ void fold(A &a, const Ent &e) const {
         const double x = (double)e.al * (double)e.ga, pos = (double)e.pos;
         a.d[0] += x;
@@ -220,17 +252,15 @@ struct BwdRowOnlineOp {
     float *ds;                // [n][h]
     float *node;              // (s_i, m_i, 1 / l_i, t_i) [n][h][4]
     struct Ent { float4 m, g; float sv, dv, ga; };
-    typedef int LaneConst;
-    __device__ LaneConst lane_const(const Lane &) const { return 0; }
     __device__ void init(A &a) const { a.f[0] = -INFINITY; a.d[0] = a.d[1] = a.d[2] = a.d[3] = 0.0; }
-    __device__ void load(Ent &e, int row, int col, int slot, const Lane &ln) const {
+    __device__ void load(Ent &e, int row, int col, int slot, const LaneOff &lo) const {
         (void)slot;
-        e.m = ld4(M + (size_t)col * geo.f + ln.foff);
-        e.g = ld4(G + (size_t)row * geo.f + ln.foff);
-        e.sv = s[(size_t)row * geo.h + ln.hd];
-        e.dv = d[(size_t)col * geo.h + ln.hd];
+        e.m = ldb<float4>(M, off24(col, geo.f * 4u, lo.feat));
+        e.g = ldb<float4>(G, off24(row, geo.f * 4u, lo.feat));
+        e.sv = ldb<float>(s, off24(row, geo.h * 4u, lo.head4));
+        e.dv = ldb<float>(d, off24(col, geo.h * 4u, lo.head4));
     }
-    __device__ void prepare(Ent &e, const Lane &ln, const LaneConst &) const { e.ga = head_sum(ln.ok ? dot4(e.m, e.g) : 0.f, geo.lh); }
+    __device__ void prepare(Ent &e, const Lane &ln) const { e.ga = head_sum(ln.ok ? dot4(e.m, e.g) : 0.f, geo.lh); }
     __device__ void fold(A &a, const Ent &e) const {
         const float y = e.sv + e.dv, w = leaky(y, slope);
         const float ex = __expf(-fabsf(w - a.f[0]));                 // as in the forward pass: one exponential
@@ -284,27 +314,29 @@ struct BwdColOp {
     float slope;
     const float *ds, *a_src, *a_dst;
     float *dd, *dM;
-    struct Ent { float4 g, m; float al, pos, t, ga; };
-    typedef int LaneConst;
-    __device__ LaneConst lane_const(const Lane &) const { return 0; }
+    struct Ent { float4 g, m, nd; float al, pos, t, dv, ga; };
     __device__ void init(A &a) const { a.f[0] = a.f[1] = a.f[2] = a.f[3] = a.f[4] = 0.f; }
-    __device__ void load(Ent &e, int j, int i, int slot, const Lane &ln) const {
-        e.g = ld4(G + (size_t)i * geo.f + ln.foff);
-        e.m = ld4(M + (size_t)j * geo.f + ln.foff);
-        const size_t ih = (size_t)i * geo.h + ln.hd;
+    __device__ void load(Ent &e, int j, int i, int slot, const LaneOff &lo) const {
+        e.g = ldb<float4>(G, off24(i, geo.f * 4u, lo.feat));
+        e.m = ldb<float4>(M, off24(j, geo.f * 4u, lo.feat));
         if constexpr (CACHED) {
-            e.al = alpha[(size_t)slot * geo.h + ln.hd];               // through perm: the slot in CSR order
-            e.pos = mask[(size_t)slot * geo.h + ln.hd] ? 1.f : 0.f;
-            e.t = node[ih];
+            e.al = ldb<float>(alpha, off32(slot, geo.h * 4u, lo.head4));   // through perm: the slot in CSR order
+            e.pos = ldb<uint8_t>(mask, off32(slot, geo.h, lo.head1)) ? 1.f : 0.f;
+            e.t = ldb<float>(node, off24(i, geo.h * 4u, lo.head4));
         } else {
-            const float4 nd = *reinterpret_cast<const float4 *>(node + ih * 4);      // s_i, m_i, 1 / l_i, t_i
-            const float y = nd.x + d[(size_t)j * geo.h + ln.hd];                     // the row pass's logit, bit for bit
-            e.pos = y > 0.f ? 1.f : 0.f;
-            e.al = __expf(leaky(y, slope) - nd.y) * nd.z;
-            e.t = nd.w;
+            e.nd = ldb<float4>(node, off24(i, geo.h * 16u, lo.head16));     // s_i, m_i, 1 / l_i, t_i
+            e.dv = ldb<float>(d, off24(j, geo.h * 4u, lo.head4));
         }
     }
-    __device__ void prepare(Ent &e, const Lane &ln, const LaneConst &) const { e.ga = head_sum(ln.ok ? dot4(e.g, e.m) : 0.f, geo.lh); }
+    __device__ void prepare(Ent &e, const Lane &ln) const {
+        if constexpr (!CACHED) {
+            const float y = e.nd.x + e.dv;                                  // the row pass's logit, bit for bit
+            e.pos = y > 0.f ? 1.f : 0.f;
+            e.al = __expf(leaky(y, slope) - e.nd.y) * e.nd.z;
+            e.t = e.nd.w;
+        }
+        e.ga = head_sum(ln.ok ? dot4(e.g, e.m) : 0.f, geo.lh);
+    }
     __device__ void fold(A &a, const Ent &e) const {
         const float gy = e.al * (e.ga - e.t) * (e.pos != 0.f ? 1.f : slope);
         a.f[4] += gy;
@@ -333,12 +365,17 @@ struct BwdColOp {
     }
 };
 
-// U consecutive staged indices (16-byte aligned: segments and steps are multiples of four entries)
+// U consecutive staged indices (aligned: segments and batches are multiples of U entries)
 template <int U> __device__ __forceinline__ void read_indices(const int32_t *p, int (&v)[U]) {
+    if constexpr (U == 2) {
+        const int2 q = *reinterpret_cast<const int2 *>(p);
+        v[0] = q.x; v[1] = q.y;
+    } else {
 #pragma unroll
-    for (int u = 0; u < U; u += 4) {
-        const int4 q = *reinterpret_cast<const int4 *>(p + u);
-        v[u] = q.x; v[u + 1] = q.y; v[u + 2] = q.z; v[u + 3] = q.w;
+        for (int u = 0; u < U; u += 4) {
+            const int4 q = *reinterpret_cast<const int4 *>(p + u);
+            v[u] = q.x; v[u + 1] = q.y; v[u + 2] = q.z; v[u + 3] = q.w;
+        }
     }
 }
 
@@ -380,7 +417,7 @@ seg_walk_kernel(int nnz, int seg, long nseg, const int32_t *__restrict__ rowidx,
     const long g = (long)blockIdx.x * GPB + gl;
     const bool active = g < nseg;
     const Lane ln = op.geo.lane(l, blockIdx.y);
-    const typename Op::LaneConst lc = op.lane_const(ln);
+    const LaneOff lo = lane_off(ln);
     float *part_tile = part + (size_t)blockIdx.y * 2 * gridDim.x * (LPE * W);
     A acc;
     op.init(acc);
@@ -394,18 +431,23 @@ seg_walk_kernel(int nnz, int seg, long nseg, const int32_t *__restrict__ rowidx,
         const int before = gl > 0 ? s_row[lb - 1] : (s0 > 0 ? rowidx[s0 - 1] : -1);
         const bool head_open = before == first;
         int cur = first;
-        for (int x = 0; x < cnt; x += U) {
-            // U entries per step with wide LDS reads; a step that runs past the segment's last entry reads the
-            // next segment's (or the filler's) indices: valid addresses, loaded and not folded
-            int r[U], c[U], sl[U];
+        // The segment in batches of U entries, two batches in flight: the gathers of batch b + 1 are issued
+        // before batch b is folded, so they (and the stores of the rows that batch b completes) have a whole
+        // batch of arithmetic to finish in.  seg is a multiple of 2 U; every batch of the segment is loaded,
+        // also past the entry list's end (the staged filler: entry 0 of row 0, loaded and not folded), and
+        // the batch after the last one is the last one again.
+        typedef typename Op::Ent Ent;
+        auto fetch = [&](int x, int (&r)[U], Ent (&ent)[U]) __attribute__((always_inline)) {
+            int c[U], sl[U];
             read_indices<U>(s_row + lb + x, r);
             read_indices<U>(s_col + lb + x, c);
             read_indices<U>(s_slot + lb + x, sl);
-            typename Op::Ent ent[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) op.load(ent[u], r[u], c[u], sl[u], ln);     // lanes without features read feature 0
+            for (int u = 0; u < U; ++u) op.load(ent[u], r[u], c[u], sl[u], lo);       // lanes without features read feature 0
+        };
+        auto consume = [&](int x, const int (&r)[U], Ent (&ent)[U]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) op.prepare(ent[u], ln, lc);
+            for (int u = 0; u < U; ++u) op.prepare(ent[u], ln);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (x + u < cnt) {
@@ -418,6 +460,15 @@ seg_walk_kernel(int nnz, int seg, long nseg, const int32_t *__restrict__ rowidx,
                     op.fold(acc, ent[u]);
                 }
             }
+        };
+        int ra[U], rb[U];
+        Ent ea[U], eb[U];
+        fetch(0, ra, ea);
+        for (int x = 0; x < seg; x += 2 * U) {
+            fetch(x + U, rb, eb);
+            consume(x, ra, ea);
+            fetch(x + 2 * U < seg ? x + 2 * U : seg - U, ra, ea);
+            consume(x + U, rb, eb);
         }
         const long e = s0 + cnt;
         const int after = e >= nnz ? -1 : (gl + 1 < GPB ? s_row[lb + seg] : rowidx[e]);
@@ -564,14 +615,23 @@ gnn_status_t run_pass(const Shape &sh, int n, int nnz, const int32_t *ptr, const
 
 // The fused passes take feature vectors of whole float4s per head, a power-of-two number of them, and at
 // most 256 features per head; other shapes run the unfused kernels.
-bool gat_fused_shape(int h, int k) {
+static bool fused_head_shape(int h, int k) {
     if (h < 1 || k < 4 || k % 4 != 0 || k > 256) return false;
     const int lh = k / 4;
     return (lh & (lh - 1)) == 0;
 }
 
+// ... on graphs whose gathers can be addressed with 32-bit byte offsets built by 24-bit multiplies: node
+// numbers below 2^24, rows below 2^24 bytes, every gathered array (n x h k floats, n x h float4s, q x h
+// floats) below 4 GiB.
+bool gat_fused_shape(int64_t n, int64_t nnz, int h, int k) {
+    if (!fused_head_shape(h, k)) return false;
+    const int64_t f = (int64_t)h * k, lim = (int64_t)1 << 32;
+    return n < (1 << 24) && f * 4 < (1 << 24) && n * f * 4 < lim && n * h * 16 < lim && nnz * h * 4 < lim;
+}
+
 size_t gat_fused_workspace_bytes(int64_t nnz, int h, int k) {
-    if (nnz <= 0 || !gat_fused_shape(h, k)) return kAlign;
+    if (nnz <= 0 || !fused_head_shape(h, k)) return kAlign;
     const Shape sh = pick_shape(nnz, h, k);
     return align_up((size_t)2 * sh.nblk * sh.tiles * sh.lpe * kMaxAccWords * sizeof(float));
 }
@@ -589,7 +649,7 @@ gnn_status_t gat_fused_forward_launch(int n, int nnz, int h, int k, const int32_
                            static_cast<const float *>(workspace));
         return launch_status();
     }
-    return run_pass<FwdOp, 8>(sh, n, nnz, rowptr, erow, col, nullptr, op, static_cast<float *>(workspace), st);
+    return run_pass<FwdOp, 4>(sh, n, nnz, rowptr, erow, col, nullptr, op, static_cast<float *>(workspace), st);
 }
 
 // Row pass (CSR arrays) then column pass (CSC arrays) of the backward edge phase.
@@ -615,14 +675,14 @@ gnn_status_t gat_fused_backward_launch(int n, int nnz, int h, int k, const int32
     }
     if (alpha) {
         BwdRowCachedOp ra{sh.geo, G, M, alpha, mask, slope, ds, node};
-        GNN_TRY((run_pass<BwdRowCachedOp, 4>(sh, n, nnz, rowptr, erow, col, nullptr, ra, part, st)));
+        GNN_TRY((run_pass<BwdRowCachedOp, 2>(sh, n, nnz, rowptr, erow, col, nullptr, ra, part, st)));
         BwdColOp<true> cb{sh.geo, G, M, alpha, mask, node, nullptr, slope, ds, a_src, a_dst, dd, dM};
-        return run_pass<BwdColOp<true>, 4>(sh, n, nnz, colptr, ecol, row, perm, cb, part, st);
+        return run_pass<BwdColOp<true>, 2>(sh, n, nnz, colptr, ecol, row, perm, cb, part, st);
     }
     BwdRowOnlineOp ra{sh.geo, G, M, s, d, slope, ds, node};
-    GNN_TRY((run_pass<BwdRowOnlineOp, 4>(sh, n, nnz, rowptr, erow, col, nullptr, ra, part, st)));
+    GNN_TRY((run_pass<BwdRowOnlineOp, 2>(sh, n, nnz, rowptr, erow, col, nullptr, ra, part, st)));
     BwdColOp<false> cb{sh.geo, G, M, nullptr, nullptr, node, d, slope, ds, a_src, a_dst, dd, dM};
-    return run_pass<BwdColOp<false>, 4>(sh, n, nnz, colptr, ecol, row, perm, cb, part, st);
+    return run_pass<BwdColOp<false>, 2>(sh, n, nnz, colptr, ecol, row, perm, cb, part, st);
 }
 
 }  // namespace gnn

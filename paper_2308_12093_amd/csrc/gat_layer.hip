@@ -46,7 +46,7 @@ gnn_status_t gat_forward(Plan &p, const gnn_graph_t &g, const float *X, const fl
     GNN_TRY(gat_node_attention_launch(n, h, k, B.M, a_src, a_dst, B.s, B.d, st));
     const float *bias = d.has_bias ? b : nullptr;
     const int act = d.fuse_elu ? kActElu : kActNone;
-    if (gat_fused_shape(h, k) && aligned16(Y)) {
+    if (gat_fused_shape(n, q, h, k) && aligned16(Y) && aligned16(bias)) {
         // logits, LeakyReLU, row softmax and the weighted aggregation in one pass over the entries
         GNN_TRY(gat_fused_forward_launch(n, q, h, k, g.csr_rowptr, g.csr_erow, g.csr_col, B.M, B.s, B.d, d.leaky_slope,
                                          bias, act, Y, B.stat, at<char>(workspace, L.w_fused), st));
@@ -80,7 +80,7 @@ gnn_status_t gat_backward(Plan &p, const gnn_graph_t &g, const float *X, const f
         GNN_TRY(gemm_launch(0, 0, n, f, m, X, W, B.M, nullptr, 0, at<char>(workspace, L.w_gemm_nn), st));
     if (variant == GNN_CACHE_NONE || variant == GNN_CACHE_GAT_FEAT)
         GNN_TRY(gat_node_attention_launch(n, h, k, B.M, a_src, a_dst, B.s, B.d, st));
-    const bool fused = gat_fused_shape(h, k) && aligned16(dY_in) && aligned16(a_src) && aligned16(a_dst);
+    const bool fused = gat_fused_shape(n, q, h, k) && aligned16(dY_in) && aligned16(a_src) && aligned16(a_dst);
     // the fused passes rebuild alpha per entry from per-node values; the separate kernels need the array
     if (variant != GNN_CACHE_GAT_FEAT_EDGE && !fused)
         GNN_TRY(gat_edge_softmax_launch(n, q, h, g.csr_rowptr, g.csr_erow, g.csr_col, B.s, B.d, d.leaky_slope, B.stat,

@@ -244,6 +244,18 @@ def test_operator_calls_check_sizes():
     assert B.lib.gnn_gemm(0, 0, -1, 4, 4, one, one, one, null, 0, null, 0, null) == B.GNN_ERR_INVALID_ARG
     tw = B.gnn_transpose_workspace_bytes(100, 1000)
     assert B.lib.gnn_csr_transpose(100, 1000, one, one, one, one, one, one, tw - 1, null) == B.GNN_ERR_BUFFER_TOO_SMALL
+    # the fused GAT aggregation: head widths, alignment and the sizes its 32-bit gather offsets can address
+    def aggregate(n, nnz, heads, f, M=one, bias=null, ws_bytes=1 << 30):
+        return B.lib.gnn_gat_aggregate_csr(n, nnz, one, one, one, M, one, one, heads, f, 0.2, bias, 0, one, one, one,
+                                           ws_bytes, null)
+    for heads, f in ((2, 6), (1, 3), (2, 12), (1, 512)):
+        assert aggregate(100, 1000, heads, f) == B.GNN_ERR_UNSUPPORTED
+    assert aggregate(100, 1000, 2, 8, M=ctypes.c_void_p(260)) == B.GNN_ERR_UNSUPPORTED        # M not 16-byte aligned
+    assert aggregate(100, 1000, 2, 8, bias=ctypes.c_void_p(260)) == B.GNN_ERR_UNSUPPORTED
+    assert aggregate(1 << 24, 1000, 2, 8) == B.GNN_ERR_UNSUPPORTED                            # node numbers of 24 bits
+    assert aggregate(1 << 23, 1000, 8, 64) == B.GNN_ERR_UNSUPPORTED                           # M of 16 GiB
+    assert aggregate(1 << 20, 1 << 30, 8, 8) == B.GNN_ERR_UNSUPPORTED                         # nnz * heads = 2^33
+    assert aggregate(100, 1000, 2, 8, ws_bytes=B.gnn_gat_aggregate_workspace_bytes(1000, 2, 8) - 1) == B.GNN_ERR_BUFFER_TOO_SMALL
 
 
 # ---- calibrated selection and constant inputs (host logic) --------------------------------

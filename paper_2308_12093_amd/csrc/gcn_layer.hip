@@ -158,18 +158,22 @@ gnn_status_t sage_backward(Plan &p, const gnn_graph_t &g, const float *X, const 
     const bool dx = d.need_input_grad != 0;
     Carver ws(workspace);
 
+    // as in the GCN layer: without dX in the split-propagate scheme the masked gradient is only read by the two
+    // weight-gradient products and the bias sum, which apply the mask as they load dY
+    const bool mask_in_consumers = d.fuse_relu && p.info.bwd == GNN_BWD_SPLIT_PROPAGATE && !dx;
+    const float *mask_y = mask_in_consumers ? Y : nullptr;
     const float *G = dY;
-    if (d.fuse_relu) {
-        float *Gm = ws.take<float>((size_t)n * k);
+    float *Gm = d.fuse_relu ? ws.take<float>((size_t)n * k) : nullptr;
+    if (d.fuse_relu && !mask_in_consumers) {
         GNN_TRY(activation_grad_launch((int64_t)n * k, dY, Y, Gm, kActRelu, st));
         G = Gm;
     }
     if (d.has_bias) {
         void *red = ws.take<char>(colsum_workspace_bytes(n, k));
-        GNN_TRY(colsum_launch(n, k, G, db, red, st));
+        GNN_TRY(colsum_launch(n, k, G, db, red, st, mask_y, kActRelu));
     }
     void *gemm_ws = ws.take<char>(gemm_workspace_bytes(1, 0, m, k, n));
-    GNN_TRY(gemm_launch(1, 0, m, k, n, X, G, dWs, nullptr, 0, gemm_ws, st));          // dWs = X^T G
+    GNN_TRY(gemm_launch(1, 0, m, k, n, X, G, dWs, nullptr, 0, gemm_ws, st, mask_y, kActRelu));     // dWs = X^T G
 
     if (p.info.bwd == GNN_BWD_FUSED_PROPAGATE) {
         // H = A'^T G once; dWn = X^T H; dX = G Ws^T + H Wn^T
@@ -191,7 +195,7 @@ gnn_status_t sage_backward(Plan &p, const gnn_graph_t &g, const float *X, const 
             GNN_TRY(spmm(g, forward_view(g, m), X, m, Pw, nullptr, 0, sp, st));
             P = Pw;
         }
-        GNN_TRY(gemm_launch(1, 0, m, k, n, P, G, dWn, nullptr, 0, gemm_ws, st));
+        GNN_TRY(gemm_launch(1, 0, m, k, n, P, G, dWn, nullptr, 0, gemm_ws, st, mask_y, kActRelu));
         if (dx) {
             const SparseView tv = transposed_view(g, m);
             int ldu = m;

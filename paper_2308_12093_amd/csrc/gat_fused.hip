@@ -32,7 +32,7 @@
 // through two partials per block and a second kernel; every combination has a fixed order, so results
 // are reproducible.
 //
-// A group walks its segment in batches of a few entries with two batches in flight: the gathers of the next
+// A group walks its segment in batches of two entries with two batches in flight: the gathers of the next
 // batch are issued before the current one is folded.  (Loads and stores share one in-order counter on this
 // chip; with a single batch in flight every wait for a gather also waited for the stores of the rows just
 // completed, and the gather latency itself was exposed once per batch: the forward pass ran a quarter slower.)
@@ -649,7 +649,7 @@ gnn_status_t gat_fused_forward_launch(int n, int nnz, int h, int k, const int32_
                            static_cast<const float *>(workspace));
         return launch_status();
     }
-    return run_pass<FwdOp, 4>(sh, n, nnz, rowptr, erow, col, nullptr, op, static_cast<float *>(workspace), st);
+    return run_pass<FwdOp, 2>(sh, n, nnz, rowptr, erow, col, nullptr, op, static_cast<float *>(workspace), st);
 }
 
 // Row pass (CSR arrays) then column pass (CSC arrays) of the backward edge phase.

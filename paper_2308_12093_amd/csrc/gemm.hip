@@ -593,6 +593,9 @@ int pick_splits(int ta, int64_t M, int64_t N, int64_t K) {
     if (s > by_k) s = by_k;
     if (s > by_traffic) s = by_traffic;
     if (s < 1) s = 1;
+    // equal blocks spread evenly over the 256 CUs only if their number is a multiple of 256: round down to one
+    // (640 blocks leave half the CUs with three and half with two)
+    if (tiles * s > 256) s = (tiles * s / 256 * 256) / tiles;
     return (int)s;
 }
 

@@ -182,3 +182,65 @@ def test_config5_full_size_every_tensor(B, cfg5, k):
         assert_close(host(dW), dW_ref, f"cfg5 {m}->{k} {name} dW")
         assert_close_blocks(host(dX), dX_ref, f"cfg5 {m}->{k} {name} dX")
         del ws, cache, Y, dW, dX, plan
+
+
+def test_gat_layer_at_the_largest_node_count_the_fused_passes_take(B, G):
+    """n = 2^24 - 1 nodes.  The fused GAT passes address their gathers with 32-bit byte offsets built by 24-bit
+    multiplies, which holds for node numbers below 2^24: here the entries join the highest-numbered nodes with
+    each other, with node 0 and with random nodes, so offsets near the top of every gathered array are formed.
+    Inputs are small integers: every logit s_i + d_j is an integer, exact in float and in double, so both sides
+    take the same LeakyReLU decisions (a logit of exactly 0 included) and the whole layer can be compared
+    (Eqs. gat-fwd-att, gat-fwd; Sec. "GAT Backward Pass")."""
+    n, m, h, k, slope = (1 << 24) - 1, 4, 2, 4, 0.2
+    f = h * k
+    progress("gat max-n: building the graph")
+    rng = np.random.default_rng(2024)
+    r = rng.integers(0, n, 300_000, dtype=np.int64)
+    c = rng.integers(0, n, 300_000, dtype=np.int64)
+    top = np.array([n - 1, n - 2, n - 3, 0, 1, 1 << 23, (1 << 23) - 1, n - 1 - (1 << 12)], dtype=np.int64)
+    rr, cc = np.meshgrid(top, top, indexing="ij")
+    hub = rng.integers(0, n, 5_000, dtype=np.int64)             # a long row and a long column at the top node
+    r = np.concatenate([r, rr.ravel(), np.full(hub.size, n - 1), hub])
+    c = np.concatenate([c, cc.ravel(), hub, np.full(hub.size, n - 1)])
+    keys = np.unique(r * n + c)
+    r, c = keys // n, keys % n
+    keep = r != c                                               # the self-loops are added by the preprocessing
+    r, c = r[keep], c[keep]
+    rowptr = np.zeros(n + 1, np.int64)
+    np.cumsum(np.bincount(r, minlength=n), out=rowptr[1:])
+    rowptr, col = rowptr.astype(np.int32), c.astype(np.int32)
+
+    ints = lambda lo, hi, *shape: rng.integers(lo, hi + 1, shape).astype(np.float32)
+    X, W = ints(-2, 2, n, m), ints(-1, 1, m, f)
+    a_src, a_dst, b = ints(-1, 1, h, k), ints(-1, 1, h, k), rng.standard_normal(f, dtype=np.float32)
+    dY = rng.standard_normal((n, f), dtype=np.float32)
+
+    progress("gat max-n: oracle forward + backward")
+    rp, cp, _ = oracle.add_self_loops_degree(rowptr, col)
+    fw = oracle.gat_forward(rp, cp, X, W, a_src, a_dst, b, h, slope)
+    ref = oracle.gat_backward_from(rp, cp, X, W, a_src, a_dst, dY, fw["M"], fw["alpha"], fw["mask"], slope)
+    rY = fw["Y"]
+    assert int((fw["s"][np.repeat(np.arange(n), np.diff(rp))] + fw["d"][cp] == 0).sum()) > 1000   # logits of exactly 0 occur
+
+    progress("gat max-n: preprocessing and the layer on the GPU")
+    g = G.gat_graph(rowptr, col)
+    assert g.n == n and g.nnz == cp.size
+    for variant in (B.GNN_CACHE_GAT_FEAT_NODEATT, B.GNN_CACHE_GAT_FEAT_EDGE):
+        plan = B.Plan(B.GNN_LAYER_GAT, g.n, g.nnz, m, k, heads=h, need_input_grad=True, has_bias=True,
+                      leaky_slope=slope, cache=variant)
+        ws, cache = B.alloc(plan.info.workspace_bytes), B.alloc(plan.info.cache_bytes)
+        e = lambda *sh: torch.full(sh, float("nan"), dtype=torch.float32, device="cuda")
+        Y, dW, da_s, da_d, db, dX = e(n, f), e(m, f), e(h, k), e(h, k), e(f), e(n, m)
+        dX_, W_, as_, ad_, b_, dY_ = dev(X), dev(W), dev(a_src), dev(a_dst), dev(b), dev(dY)
+        B.gat_layer_fwd(plan, g, dX_, W_, as_, ad_, b_, Y, cache, ws)
+        B.gat_layer_bwd(plan, g, dX_, W_, as_, ad_, dY_, dW, da_s, da_d, db, dX, cache, ws)
+        torch.cuda.synchronize()
+        tag = f"max-n variant {variant}"
+        assert_close_blocks(host(Y), rY, tag + " Y", rows_per_block=1 << 21)
+        got = dict(dW=dW, da_src=da_s, da_dst=da_d, db=db)
+        for name, t in got.items():
+            assert_close(host(t), ref[name], f"{tag} {name}")
+        assert_close_blocks(host(dX), ref["dX"], tag + " dX", rows_per_block=1 << 21)
+        del ws, cache, Y, dX, dX_, dY_
+        torch.cuda.empty_cache()
+        progress(f"gat max-n: variant {variant} compared")

@@ -491,11 +491,12 @@ class GatSingle:
         self.d = {key: torch.from_numpy(v).cuda() for key, v in w.tensors.items()}
         self.h, self.k, self.m = w.dims["heads"], w.dims["f_out"], w.dims["f_in"]
 
-    def make(self, variant, need_dx=True):
+    def make(self, variant, need_dx=True, selection="rule"):
         B, torch, g = self.B, self.torch, self.g
         h, k, m = self.h, self.k, self.m
+        sel = B.GNN_SELECT_CALIBRATED if selection == "calibrated" else B.GNN_SELECT_PAPER_RULE
         plan = B.Plan(B.GNN_LAYER_GAT, g.n, g.nnz, m, k, heads=h, need_input_grad=need_dx, has_bias=True,
-                      leaky_slope=0.2, cache=gat_variant(B, variant))
+                      leaky_slope=0.2, cache=gat_variant(B, variant), selection=sel)
         e = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
         return dict(plan=plan, Y=e(g.n, h * k), dW=e(m, h * k), das=e(h, k), dad=e(h, k), db=e(h * k),
                     dX=e(g.n, m) if need_dx else None, ws=B.alloc(plan.info.workspace_bytes),
@@ -536,7 +537,7 @@ def bench_gat(args, torch, B, graphs, synth, oracle):
     g, h, k, m = run.g, run.h, run.k, run.m
     n, q, f = g.n, g.nnz, h * k
     need_dx = not args.no_input_grad
-    L = run.make(args.gat_cache, need_dx)
+    L = run.make(args.gat_cache, need_dx, args.selection)
     ms = wall_ms_per_step(torch, lambda: (run.fwd(L), run.bwd(L)), args.warmup, args.steps)
     ev = HipEvents(torch.cuda.current_stream().cuda_stream)
     fwd_ms = stats(ev.blocks(lambda: run.fwd(L), 10, 20))
@@ -563,7 +564,8 @@ def bench_gat(args, torch, B, graphs, synth, oracle):
                "sample": f"{passes} whole steps (forward + backward, recomputing variant) of the same workload, "
                          f"{dt * passes:.1f} s in total", "ms_per_sample": round(dt * 1e3, 2)}
     config = {"workload": f"{w.name}: R-MAT directed n={n}, nnz={q} (self-loops incl.), F_in={m}, heads={h}, "
-                          f"F_out={k}, GAT single layer fwd+bwd, cache variant={variant_name}, input_grad={need_dx}",
+                          f"F_out={k}, GAT single layer fwd+bwd, cache variant={variant_name}, input_grad={need_dx}, "
+                          f"selection={args.selection}",
               "fwd_ms": fwd_ms, "bwd_ms": bwd_ms, "cache_bytes": int(L["plan"].info.cache_bytes)}
     return {"metric": "GAT layer fwd+bwd edge-feat/s", "value": edge_feat / (ms * 1e-3), "ms_per_step": ms,
             "config": config, "roofline": roofline, "cpu_baseline": cpu}
@@ -624,8 +626,10 @@ def bench_gat_network(args, torch, B, graphs, synth, oracle):
     g = graphs.gat_graph(w.rowptr, w.col, "cuda")
     n, q, f = g.n, g.nnz, h * k
     variant = gat_variant(B, args.gat_cache)
-    p1 = B.Plan(B.GNN_LAYER_GAT, n, q, m, k, heads=h, need_input_grad=False, has_bias=True, cache=variant, fuse_elu=True)
-    p2 = B.Plan(B.GNN_LAYER_GAT, n, q, f, k, heads=h, need_input_grad=True, has_bias=True, cache=variant)
+    sel = B.GNN_SELECT_CALIBRATED if args.selection == "calibrated" else B.GNN_SELECT_PAPER_RULE
+    p1 = B.Plan(B.GNN_LAYER_GAT, n, q, m, k, heads=h, need_input_grad=False, has_bias=True, cache=variant, fuse_elu=True,
+                selection=sel)
+    p2 = B.Plan(B.GNN_LAYER_GAT, n, q, f, k, heads=h, need_input_grad=True, has_bias=True, cache=variant, selection=sel)
     gen = torch.Generator(device="cuda").manual_seed(0)
     rnd = lambda *s, scale=1.0: torch.randn(s, device="cuda", generator=gen) * scale
     X = torch.from_numpy(w.tensors["X"]).cuda()
